@@ -1,0 +1,139 @@
+"""The APOLLO / APOLLO-Mini step in fp64, one weight matrix at a time (oracle side).
+
+Test infrastructure only (see the package docstring).  Follows Algorithm 1 of the paper step
+by step, in its notation: G (gradient), P (random projection), R = P G (low-rank gradient),
+M^R / V^R (low-rank Adam moments, Section 4.1), R~ = M^R / (sqrt(V^R) + eps), the channel-wise
+factor s_j = ||R~[:, j]|| / ||R[:, j]|| (Eq. 4) or the tensor-wise factor s = ||R~|| / ||R||
+(Section 4.2, APOLLO-Mini), the norm-growth limiter (Eq. 3, gamma = 1.01) and the update
+W <- W - lr * alpha * G S - lr * lambda * W (Algorithm 1, step 4; the caller passes the
+ordinary gradient, so the update subtracts).
+
+Readings taken where the paper is silent or inconsistent:
+  * Algorithm 1 assumes m <= n.  A stored tensor with more rows than columns is handled as its
+    transpose: the smaller dimension is projected away, channels run along the larger one
+    (Section 3.2 groups "based on the larger dimension"; the state size 2nr+2 of Table 1 with
+    n the larger dimension agrees).
+  * Adam's bias correction is applied (Algorithm 1 calls "AdamW(R_t, ...)"); eps is added after
+    the bias-corrected square root.  bias_correction=False gives the literal Section 4.1 formula.
+  * P ~ N(0, 1/r) (Algorithm 1, Theorem A.1): unit-variance z times 1/sqrt(r).
+  * The limiter acts on the Frobenius norm of the whole scaled gradient alpha * G diag(s), one
+    number per tensor (Table 1 counts one stored norm); nothing is limited while the stored norm
+    is 0 (first step); the stored norm is the one after limiting.
+  * A channel whose projected gradient is exactly zero gets s_j = 0 (0/0 otherwise).
+  * M^R, V^R are kept when P is re-sampled.
+  * Steps are 1-based: P is re-sampled when (t-1) mod T == 0, epoch = (t-1) div T.
+"""
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import gauss
+
+CHANNEL = "channel"   # APOLLO: one factor per channel
+TENSOR = "tensor"     # APOLLO-Mini: one factor per tensor
+
+
+@dataclass
+class Config:
+    rank: int
+    mode: str = CHANNEL
+    seed: int = 0
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    scale: float = 1.0             # alpha
+    weight_decay: float = 0.0      # lambda
+    nl_gamma: float = 1.01         # gamma; 0 switches the limiter off
+    refresh_interval: int = 200    # T
+    bias_correction: bool = True
+    side: str = "auto"             # "auto" | "left" (project rows) | "right" (project columns)
+
+
+class TensorState:
+    """Per-tensor optimizer state: M^R, V^R (r x n) and the previous scaled-gradient norm."""
+
+    def __init__(self, r, n):
+        self.M = np.zeros((r, n), dtype=np.float64)
+        self.V = np.zeros((r, n), dtype=np.float64)
+        self.prev_norm = 0.0
+
+
+def is_left(rows, cols, side="auto"):
+    if side == "left":
+        return True
+    if side == "right":
+        return False
+    return rows <= cols
+
+
+def init_state(cfg, rows, cols):
+    n = cols if is_left(rows, cols, cfg.side) else rows
+    return TensorState(cfg.rank, n)
+
+
+def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None):
+    """One optimizer step on one tensor.  W, G: float64 arrays (rows x cols); W is updated in
+    place and also returned.  t is the 1-based step.  P, if given, replaces the generated
+    r x m projection INCLUDING its 1/sqrt(r) (used by tests to inject a hand-set matrix).
+    Returns a dict with the intermediate quantities (R, R~, s, colsq, norm, c).
+    """
+    rows, cols = G.shape
+    left = is_left(rows, cols, cfg.side)
+    Gm = G if left else G.T                       # m x n with the projected dimension first
+    m, n = Gm.shape
+    r = cfg.rank
+
+    # Step 1: gradient into the low-rank space.
+    if P is None:
+        epoch = (t - 1) // cfg.refresh_interval
+        z = gauss.projection(cfg.seed, tensor_id, epoch, r, m, grad_is_bf16)
+        R = (z @ Gm) / np.sqrt(np.float64(r))
+    else:
+        R = np.asarray(P, dtype=np.float64) @ Gm
+
+    # Step 2: low-rank moments and the Adam-normalised low-rank gradient.
+    state.M = cfg.beta1 * state.M + (1.0 - cfg.beta1) * R
+    state.V = cfg.beta2 * state.V + (1.0 - cfg.beta2) * R * R
+    if cfg.bias_correction:
+        bc1 = 1.0 - cfg.beta1 ** t
+        bc2 = 1.0 - cfg.beta2 ** t
+    else:
+        bc1 = bc2 = 1.0
+    Rt = (state.M / bc1) / (np.sqrt(state.V / bc2) + cfg.eps)
+
+    # Step 3: the scaling factor.
+    a = np.sum(Rt * Rt, axis=0)                   # ||R~[:, j]||^2
+    b = np.sum(R * R, axis=0)                     # ||R[:, j]||^2
+    if cfg.mode == CHANNEL:
+        s = np.zeros(n)
+        nz = b > 0
+        s[nz] = np.sqrt(a[nz]) / np.sqrt(b[nz])
+    else:
+        bt = b.sum()
+        s = np.full(n, np.sqrt(a.sum()) / np.sqrt(bt) if bt > 0 else 0.0)
+
+    # Norm-growth limiter on || alpha * G diag(s) ||_F.
+    colsq = np.sum(Gm * Gm, axis=0)
+    norm = cfg.scale * np.sqrt(np.sum(s * s * colsq))
+    c = 1.0
+    if cfg.nl_gamma > 0 and state.prev_norm > 0 and norm > cfg.nl_gamma * state.prev_norm:
+        c = cfg.nl_gamma * state.prev_norm / norm
+        norm = cfg.nl_gamma * state.prev_norm
+    state.prev_norm = norm
+
+    # Step 4: update in the original space.
+    U = cfg.scale * c * (Gm * s[None, :])         # the scaled gradient, m x n
+    if not left:
+        U = U.T
+    W -= lr * U + lr * cfg.weight_decay * W
+    return {"R": R, "Rt": Rt, "s": s, "colsq": colsq, "norm": norm, "c": c, "left": left}
+
+
+def state_elements(cfg, shapes):
+    """Number of stored optimizer-state scalars (Table 1: 2nr + 2 per tensor for APOLLO,
+    2n + 2 for Mini at r = 1, n the larger dimension; the "+2" are the seed and the norm)."""
+    total = 0
+    for rows, cols in shapes:
+        n = cols if is_left(rows, cols, cfg.side) else rows
+        total += 2 * n * cfg.rank + 2
+    return total
