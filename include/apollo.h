@@ -1,0 +1,177 @@
+/*
+ * apollo.h -- C ABI of the MI355X (gfx950) APOLLO / APOLLO-Mini optimizer-step library.
+ *
+ * The library performs, for every weight matrix W (rows x cols, row-major, fp32) with
+ * gradient G (same shape, bf16 or fp32), the step of Algorithm 1 of "APOLLO: SGD-like
+ * Memory, AdamW-level Performance" (arXiv 2412.05270):
+ *
+ *   1. P  <- seeded Gaussian random projection, r x m, variance 1/r, re-generated from a
+ *            counter-based generator every step and never kept as optimizer state
+ *            (Algorithm 1 "P_t <- N_seed(0,1/r)"; Section 4.1 "Generating random projection
+ *            matrix"); a new P is drawn every T steps.
+ *   2. R  <- P G                                   (Algorithm 1, step 1; r x n)
+ *   3. M^R, V^R <- Adam moments of R; R~ <- M^R / (sqrt(V^R) + eps)   (Section 4.1)
+ *   4. s_j <- ||R~[:,j]|| / ||R[:,j]||  per channel (APOLLO, Eq. 4), or
+ *      s   <- ||R~|| / ||R||            per tensor  (APOLLO-Mini, Section 4.2)
+ *   5. norm-growth limiter on ||alpha G diag(s)||_F with threshold gamma  (Section 3.2, Eq. 3)
+ *   6. W  <- W - lr * alpha * G diag(s) - lr * lambda * W              (Algorithm 1, step 4)
+ *
+ * m = min(rows, cols) is the projected dimension, n = max(rows, cols) the channel dimension
+ * (Algorithm 1 assumes m <= n; a tensor with rows > cols is treated as its transpose without
+ * being moved).  All of it runs in hand-written HIP kernels on the stream the caller passes.
+ *
+ * Conventions
+ *   - Every pointer argument is a HOST pointer unless its comment says DEVICE.
+ *   - The library allocates no device memory and creates no streams.  The caller owns W, G,
+ *     the state buffer and the workspace (all DEVICE memory) and keeps them alive while the
+ *     handle uses them.  The library owns only the host-side handle.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and return without synchronising.  Nothing is read back to the host.
+ *   - Functions returning apollo_status_t return APOLLO_OK (0) or a negative code; argument
+ *     errors are detected before anything is launched.  apollo_last_error() gives the text.
+ *   - `g` is the ordinary gradient (d loss / d W); the step subtracts.
+ */
+#ifndef APOLLO_H_
+#define APOLLO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct apollo_handle apollo_handle_t; /* opaque, host-side */
+
+typedef int32_t apollo_status_t;
+enum {
+  APOLLO_OK = 0,
+  APOLLO_EINVAL = -1,       /* null pointer, rank < 1, rank > min(rows, cols), T < 1, bad enum,
+                               tensor count mismatch, step < 1, misaligned W/G pointer          */
+  APOLLO_ENOMEM = -2,       /* host allocation failed                                           */
+  APOLLO_ESTATE = -3,       /* state or workspace buffer too small or not 256-byte aligned      */
+  APOLLO_EHIP = -4,         /* a HIP call failed (text in apollo_last_error)                    */
+  APOLLO_EUNSUPPORTED = -5  /* gradient dtype other than fp32 / bf16, or a dimension too large  */
+};
+
+/* gradient element type (W, M^R, V^R and all factors are fp32) */
+enum { APOLLO_F32 = 0, APOLLO_BF16 = 1 };
+/* granularity of the scaling factor: APOLLO (Eq. 4) or APOLLO-Mini (Section 4.2) */
+enum { APOLLO_CHANNEL = 0, APOLLO_TENSOR = 1 };
+/* which dimension is projected away: AUTO = the smaller one (Algorithm 1's m <= n);
+   LEFT = rows (R = P G, channels are columns); RIGHT = columns (R = G P^T, channels are rows) */
+enum { APOLLO_SIDE_AUTO = 0, APOLLO_SIDE_LEFT = 1, APOLLO_SIDE_RIGHT = 2 };
+/* selectors of apollo_debug_get */
+enum {
+  APOLLO_DBG_M = 0,     /* M^R, r x n fp32, channel index contiguous                          */
+  APOLLO_DBG_V = 1,     /* V^R, r x n fp32                                                    */
+  APOLLO_DBG_S = 2,     /* scaling factor of the last step: n fp32 (channel) or 1 fp32 (tensor) */
+  APOLLO_DBG_NORM = 3,  /* stored norm ||alpha G diag(s)||_F after limiting, 1 fp32            */
+  APOLLO_DBG_C = 4,     /* limiter factor c in (0, 1] of the last step, 1 fp32                 */
+  APOLLO_DBG_R = 5,     /* R = P G of the last step, r x n fp32                               */
+  APOLLO_DBG_COLSQ = 6  /* ||G[:,j]||^2 per channel of the last step, n fp32                   */
+};
+
+typedef struct {
+  int64_t rows, cols;   /* W and G are rows x cols, row-major, leading dimension = cols        */
+  int32_t grad_dtype;   /* APOLLO_F32 or APOLLO_BF16                                           */
+  int32_t reserved;     /* set to 0                                                            */
+} apollo_shape_t;
+
+/* Hyper-parameters (Algorithm 1's input list; gamma from Section 3.2). */
+typedef struct {
+  int32_t rank;             /* r >= 1 and r <= min(rows, cols) of every tensor                 */
+  int32_t mode;             /* APOLLO_CHANNEL or APOLLO_TENSOR                                 */
+  uint64_t seed;            /* key of the counter-based generator                              */
+  float beta1, beta2, eps;  /* Adam on R                                                       */
+  float scale;              /* alpha: 1 for APOLLO, sqrt(128) for APOLLO-Mini (Sections 4.1/4.2) */
+  float weight_decay;       /* lambda (decoupled), 0 = none                                    */
+  float nl_gamma;           /* gamma of the norm-growth limiter, 1.01 in the paper; 0 = off    */
+  int32_t refresh_interval; /* T >= 1: a new P is drawn when (step-1) % T == 0                 */
+  int32_t bias_correction;  /* 1 = Adam's bias correction (default), 0 = literal Section 4.1   */
+  int32_t side;             /* APOLLO_SIDE_*                                                   */
+  int32_t reserved;         /* set to 0                                                        */
+} apollo_config_t;
+
+typedef struct {
+  void* w;        /* DEVICE, fp32, rows x cols, 16-byte aligned, updated in place              */
+  const void* g;  /* DEVICE, grad_dtype, rows x cols, 16-byte aligned, read only               */
+} apollo_tensor_t;
+
+/* Bytes of optimizer state for the tensor list (Table 1: 2nr + 2 scalars per tensor, here
+ * 2nr moments + 1 norm, the seed being in the config), 0 on invalid arguments.
+ * Layout, stable and meant for checkpointing: per tensor, in list order, each block starting
+ * on a 256-byte boundary: M^R[r][n] fp32, V^R[r][n] fp32, prev_norm fp32. */
+size_t apollo_state_bytes(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n_tensors);
+
+/* Byte offsets of one tensor's M^R, V^R and prev_norm inside the state buffer.  Any of the
+ * output pointers may be NULL.  Pure host arithmetic. */
+apollo_status_t apollo_state_offsets(const apollo_config_t* cfg, const apollo_shape_t* shapes,
+                                     int32_t n_tensors, int32_t tensor, size_t* m_offset,
+                                     size_t* v_offset, size_t* norm_offset);
+
+/* Bytes of per-step scratch (the transient P tiles, R, per-channel sums, factors, per-tensor
+ * scalars and the device descriptor table); contents are meaningless between steps except for
+ * apollo_debug_get.  0 on invalid arguments. */
+size_t apollo_workspace_bytes(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n_tensors);
+
+/* Creates a handle for a fixed tensor list.  `state` (DEVICE, >= apollo_state_bytes, 256-byte
+ * aligned) is zero-filled on `hip_stream` (M^R_0 = V^R_0 = 0, Section 4.1; stored norm 0 =
+ * "unset") unless `zero_state` is 0 (resume from a checkpointed buffer).  `workspace` (DEVICE,
+ * >= apollo_workspace_bytes, 256-byte aligned).  On failure *out is NULL. */
+apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg,
+                            const apollo_shape_t* shapes, int32_t n_tensors, void* state,
+                            size_t state_bytes, void* workspace, size_t workspace_bytes,
+                            int32_t zero_state, void* hip_stream);
+
+/* One optimizer step (Algorithm 1) on every tensor of the list.  `tensors[i]` carries the
+ * DEVICE pointers of the i-th shape given to apollo_init; n_tensors must match.  `step` is
+ * 1-based; the projection epoch is (step-1) / T and the bias-correction exponent is `step`,
+ * so steps need not be consecutive, but M^R, V^R and the stored norm are what the previous
+ * call left.  Calls on one handle must be ordered on one stream (or otherwise serialised). */
+apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, int32_t n_tensors,
+                            int64_t step, float lr, void* hip_stream);
+
+/* Writes the unit-variance projection z (P = z / sqrt(r)) that `step` would use for tensor
+ * `tensor`, as a row-major r x m matrix of `dtype` (APOLLO_F32: the fp32 variates; APOLLO_BF16:
+ * rounded to bf16, nearest-even) into `out` (DEVICE, r*m elements). */
+apollo_status_t apollo_debug_fill_projection(apollo_handle_t* h, int32_t tensor, int64_t step,
+                                             void* out, int32_t dtype, void* hip_stream);
+
+/* Copies one quantity (APOLLO_DBG_*) of tensor `tensor`, as left by the last step, to `out`
+ * (DEVICE) in the canonical layout given with the selector; `bytes` must equal its size. */
+apollo_status_t apollo_debug_get(apollo_handle_t* h, int32_t tensor, int32_t what, void* out,
+                                 size_t bytes, void* hip_stream);
+
+/* Generator building blocks, for bit-exact checks of the random stream.
+ * apollo_debug_philox: out[4*i .. 4*i+3] (DEVICE, uint32) = Philox4x32-10 of counter
+ * (ctr[4*i .. 4*i+3]) (DEVICE, uint32) under key (key0, key1), i < count.
+ * apollo_debug_gauss_parts: for n = first .. first+count-1 (n < 2^24), the Box-Muller parts of
+ * the 24-bit inputs: radius[i] = sqrt(-2 ln((n+1)/2^24)), cosv[i], sinv[i] = cos, sin of
+ * 2 pi n / 2^24 (all DEVICE fp32, count elements each). */
+apollo_status_t apollo_debug_philox(const void* ctr, uint32_t key0, uint32_t key1, void* out,
+                                    int64_t count, void* hip_stream);
+apollo_status_t apollo_debug_gauss_parts(uint32_t first, int64_t count, void* radius, void* cosv,
+                                         void* sinv, void* hip_stream);
+
+/* Phase timing for benchmarks.  After apollo_profile_enable(h, 1) every apollo_step records
+ * HIP events on its stream around its five phases: [0] P scratch fill, [1] projection R = P G,
+ * [2] low-rank moments + factors, [3] limiter scalars, [4] weight update.  apollo_profile_read
+ * waits for the recorded events, adds each phase's elapsed milliseconds over the steps recorded
+ * since the last read into ms[0..4] (HOST, 5 floats) and their count into *n_steps, and
+ * forgets them.  At most 1024 steps are kept between reads; later ones are not recorded. */
+apollo_status_t apollo_profile_enable(apollo_handle_t* h, int32_t on);
+apollo_status_t apollo_profile_read(apollo_handle_t* h, float* ms, int32_t* n_steps);
+
+/* Text of the last error on this handle; with h == NULL, of the last failed call of this
+ * thread that had no handle (apollo_init, the size queries, the generator checks).  The
+ * string stays valid until the next call on the same handle / thread. */
+const char* apollo_last_error(const apollo_handle_t* h);
+
+/* Frees the host-side handle.  Does not touch device memory or synchronise. */
+void apollo_destroy(apollo_handle_t* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APOLLO_H_ */

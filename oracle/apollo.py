@@ -56,6 +56,10 @@ class TensorState:
         self.M = np.zeros((r, n), dtype=np.float64)
         self.V = np.zeros((r, n), dtype=np.float64)
         self.prev_norm = 0.0
+        # Algorithm 1 keeps P_t between re-samplings; so does the oracle (P is NOT optimizer
+        # state to be saved: it is a function of the seed, and is re-derived when missing).
+        self.z = None
+        self.z_key = None
 
 
 def is_left(rows, cols, side="auto"):
@@ -86,8 +90,11 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None):
     # Step 1: gradient into the low-rank space.
     if P is None:
         epoch = (t - 1) // cfg.refresh_interval
-        z = gauss.projection(cfg.seed, tensor_id, epoch, r, m, grad_is_bf16)
-        R = (z @ Gm) / np.sqrt(np.float64(r))
+        key = (cfg.seed, tensor_id, epoch, r, m, bool(grad_is_bf16))
+        if state.z_key != key:                    # "if t mod T = 0: P_t <- N_seed(0, 1/r)"
+            state.z = gauss.projection(cfg.seed, tensor_id, epoch, r, m, grad_is_bf16)
+            state.z_key = key
+        R = (state.z @ Gm) / np.sqrt(np.float64(r))
     else:
         R = np.asarray(P, dtype=np.float64) @ Gm
 

@@ -1,0 +1,14 @@
+"""MI355X-native APOLLO / APOLLO-Mini optimizer step (arXiv 2412.05270, Algorithm 1).
+
+Thin ctypes binding over the C-ABI library built from csrc/ (see include/apollo.h for the
+contract of every call).  Everything numerical happens in the HIP kernels; this package only
+marshals arguments.  PyTorch is used by callers for device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    APOLLO_BF16, APOLLO_CHANNEL, APOLLO_DBG_C, APOLLO_DBG_COLSQ, APOLLO_DBG_M, APOLLO_DBG_NORM,
+    APOLLO_DBG_R, APOLLO_DBG_S, APOLLO_DBG_V, APOLLO_EHIP, APOLLO_EINVAL, APOLLO_ENOMEM,
+    APOLLO_ESTATE, APOLLO_EUNSUPPORTED, APOLLO_F32, APOLLO_OK, APOLLO_SIDE_AUTO, APOLLO_SIDE_LEFT,
+    APOLLO_SIDE_RIGHT, APOLLO_TENSOR, ApolloConfig, ApolloError, ApolloShape, ApolloStepper,
+    ApolloTensor, apollo_debug_fill_projection, apollo_debug_gauss_parts, apollo_debug_get,
+    apollo_debug_philox, apollo_destroy, apollo_profile_enable, apollo_profile_read, apollo_init, apollo_last_error, apollo_state_bytes,
+    apollo_state_offsets, apollo_step, apollo_workspace_bytes, library_path, load_library)

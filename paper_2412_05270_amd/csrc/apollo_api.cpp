@@ -1,0 +1,507 @@
+// Host side of the APOLLO step library: argument checking, buffer layout, the per-step launch
+// schedule.  The interface is documented in include/apollo.h.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/apollo.h"
+#include "apollo_internal.h"
+
+using namespace apollo;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int64_t kMaxDim = 1 << 20;       // rows / cols limit (grid dimensions, int indexing)
+constexpr int32_t kMaxTensors = 65535;     // gridDim.z
+constexpr int kRingSlots = 4;
+
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+thread_local std::string g_last_error;
+
+enum class Path { kRank1, kMfma, kGeneric };
+
+struct TensorPlan {
+  int32_t rows, cols, m, n, m8;
+  bool left, bf16;
+  Path path;
+  int32_t n_slabs, k2_blocks;
+  size_t st_m, st_v, st_norm;                                   // offsets into the state buffer
+  size_t ws_p, ws_r, ws_colsq, ws_s, ws_partials, ws_scal;       // offsets into the workspace
+  int32_t desc_index;                                           // position in the grouped descriptor table
+};
+
+struct Group {
+  int32_t first, count;          // range in the descriptor table
+  int32_t rows, cols, m, n, m8;
+  bool left, bf16;
+  Path path;
+  int32_t n_slabs;
+};
+
+struct Plan {
+  std::vector<TensorPlan> t;
+  std::vector<Group> groups;
+  size_t state_bytes = 0, workspace_bytes = 0, desc_bytes = 0;
+};
+
+int fail(std::string& dst, int code, const char* fmt, long long a = 0, long long b = 0, long long c = 0) {
+  char buf[256];
+  std::snprintf(buf, sizeof buf, fmt, a, b, c);
+  dst = buf;
+  return code;
+}
+
+// Validates the configuration and the shapes and lays out both buffers.  Host arithmetic only.
+int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n, Plan& plan, std::string& err) {
+  if (!cfg || !shapes) return fail(err, APOLLO_EINVAL, "null config or shape list");
+  if (n < 1 || n > kMaxTensors) return fail(err, APOLLO_EINVAL, "n_tensors %lld outside 1..65535", n);
+  if (cfg->rank < 1) return fail(err, APOLLO_EINVAL, "rank %lld < 1", cfg->rank);
+  if (cfg->mode != APOLLO_CHANNEL && cfg->mode != APOLLO_TENSOR) return fail(err, APOLLO_EINVAL, "unknown mode %lld", cfg->mode);
+  if (cfg->side < APOLLO_SIDE_AUTO || cfg->side > APOLLO_SIDE_RIGHT) return fail(err, APOLLO_EINVAL, "unknown side %lld", cfg->side);
+  if (cfg->refresh_interval < 1) return fail(err, APOLLO_EINVAL, "refresh_interval %lld < 1", cfg->refresh_interval);
+  if (!(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f))
+    return fail(err, APOLLO_EINVAL, "betas must lie in [0, 1)");
+  if (!(cfg->eps >= 0.f) || !(cfg->nl_gamma >= 0.f) || !std::isfinite(cfg->scale) || !std::isfinite(cfg->weight_decay))
+    return fail(err, APOLLO_EINVAL, "eps / nl_gamma negative or scale / weight_decay not finite");
+
+  plan.t.resize(n);
+  size_t st = 0;
+  for (int32_t k = 0; k < n; ++k) {
+    const apollo_shape_t& s = shapes[k];
+    TensorPlan& t = plan.t[k];
+    if (s.rows < 1 || s.cols < 1) return fail(err, APOLLO_EINVAL, "tensor %lld: rows/cols must be >= 1", k);
+    if (s.grad_dtype != APOLLO_F32 && s.grad_dtype != APOLLO_BF16)
+      return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: gradient dtype %lld is neither fp32 nor bf16", k, s.grad_dtype);
+    if (s.rows > kMaxDim || s.cols > kMaxDim)
+      return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: dimension above %lld", k, kMaxDim);
+    t.rows = (int32_t)s.rows;
+    t.cols = (int32_t)s.cols;
+    t.bf16 = s.grad_dtype == APOLLO_BF16;
+    t.left = cfg->side == APOLLO_SIDE_LEFT || (cfg->side == APOLLO_SIDE_AUTO && s.rows <= s.cols);
+    t.m = t.left ? t.rows : t.cols;
+    t.n = t.left ? t.cols : t.rows;
+    t.m8 = (t.m + 7) & ~7;
+    if (cfg->rank > t.m)
+      return fail(err, APOLLO_EINVAL, "tensor %lld: rank %lld exceeds the projected dimension %lld", k, cfg->rank, t.m);
+    if (cfg->rank == 1 && project_rank1_supported(t.rows, t.cols, t.left, t.bf16))
+      t.path = Path::kRank1;
+    else if (project_mfma_supported(t.rows, t.cols, t.left, t.bf16, cfg->rank))
+      t.path = Path::kMfma;
+    else
+      t.path = Path::kGeneric;
+    t.n_slabs = 1;
+    if (t.path == Path::kRank1 && t.left) {
+      int32_t sl = (t.rows + 511) / 512;
+      if (sl > 16) sl = 16;
+      if ((t.rows + sl - 1) / sl > 1020) sl = (t.rows + 1019) / 1020;
+      t.n_slabs = sl;
+    }
+    t.k2_blocks = (t.n + 63) / 64;
+    const size_t rn = (size_t)cfg->rank * (size_t)t.n * sizeof(float);
+    st = align_up(st);
+    t.st_m = st;
+    t.st_v = st + rn;
+    t.st_norm = st + 2 * rn;
+    st = t.st_norm + sizeof(float);
+  }
+  plan.state_bytes = align_up(st);
+
+  // group tensors of identical shape / dtype (orientation and path follow from those)
+  std::vector<int32_t> group_of(n, -1);
+  for (int32_t k = 0; k < n; ++k) {
+    if (group_of[k] >= 0) continue;
+    const TensorPlan& a = plan.t[k];
+    Group g{};
+    g.rows = a.rows; g.cols = a.cols; g.m = a.m; g.n = a.n; g.m8 = a.m8;
+    g.left = a.left; g.bf16 = a.bf16; g.path = a.path; g.n_slabs = a.n_slabs;
+    g.count = 0;
+    const int32_t gi = (int32_t)plan.groups.size();
+    for (int32_t j = k; j < n; ++j) {
+      const TensorPlan& b = plan.t[j];
+      if (group_of[j] < 0 && b.rows == a.rows && b.cols == a.cols && b.bf16 == a.bf16) {
+        group_of[j] = gi;
+        ++g.count;
+      }
+    }
+    plan.groups.push_back(g);
+  }
+  int32_t pos = 0;
+  for (size_t gi = 0; gi < plan.groups.size(); ++gi) {
+    plan.groups[gi].first = pos;
+    for (int32_t k = 0; k < n; ++k)
+      if (group_of[k] == (int32_t)gi) plan.t[k].desc_index = pos++;
+  }
+
+  // workspace: descriptor table, then per tensor P, R, colsq, s, partials, scalars
+  size_t ws = 0;
+  plan.desc_bytes = (size_t)n * sizeof(TensorDesc);
+  ws = align_up(plan.desc_bytes);
+  for (int32_t k = 0; k < n; ++k) {
+    TensorPlan& t = plan.t[k];
+    t.ws_p = ws;
+    if (t.path != Path::kRank1) ws = align_up(ws + (size_t)cfg->rank * t.m8 * (t.bf16 ? 2 : 4));
+    t.ws_r = ws;
+    ws = align_up(ws + (size_t)t.n_slabs * cfg->rank * t.n * sizeof(float));
+    t.ws_colsq = ws;
+    ws = align_up(ws + (size_t)t.n_slabs * t.n * sizeof(float));
+    t.ws_s = ws;
+    ws = align_up(ws + (size_t)t.n * sizeof(float));
+    t.ws_partials = ws;
+    ws = align_up(ws + (size_t)t.k2_blocks * 4 * sizeof(float));
+    t.ws_scal = ws;
+    ws = align_up(ws + 8 * sizeof(float));
+  }
+  plan.workspace_bytes = ws;
+  return APOLLO_OK;
+}
+
+}  // namespace
+
+struct apollo_handle {
+  apollo_config_t cfg;
+  Plan plan;
+  char* state = nullptr;
+  char* ws = nullptr;
+  std::vector<TensorDesc> desc;           // host copy, descriptor-table order
+  std::vector<apollo_tensor_t> last;      // pointers of the previous step, caller order
+  TensorDesc* ring[kRingSlots] = {nullptr, nullptr, nullptr, nullptr};   // pinned staging copies
+  hipEvent_t ring_ev[kRingSlots] = {nullptr, nullptr, nullptr, nullptr};
+  bool ring_used[kRingSlots] = {false, false, false, false};
+  int ring_next = 0;
+  bool have_ptrs = false;
+  bool profiling = false;
+  std::vector<hipEvent_t> prof_events;    // 6 per recorded step
+  size_t prof_used = 0;                   // events recorded since the last read
+  std::string err;
+};
+
+namespace {
+
+int hip_fail(std::string& dst, hipError_t e, const char* what) {
+  dst = std::string(what) + ": " + hipGetErrorString(e);
+  return APOLLO_EHIP;
+}
+
+StepParams make_step_params(const apollo_config_t& c, int64_t step, float lr) {
+  StepParams sp{};
+  sp.ks = philox_key_schedule(c.seed);
+  sp.epoch = (uint32_t)(((uint64_t)(step - 1) / (uint64_t)c.refresh_interval) & 0xffffffffu);
+  sp.r = c.rank;
+  sp.tensor_mode = c.mode == APOLLO_TENSOR;
+  sp.rsqrt_r = (float)(1.0 / std::sqrt((double)c.rank));
+  sp.beta1 = c.beta1;
+  sp.beta2 = c.beta2;
+  sp.omb1 = 1.0f - c.beta1;
+  sp.omb2 = 1.0f - c.beta2;
+  sp.eps = c.eps;
+  if (c.bias_correction) {
+    sp.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)c.beta1, (double)step)));
+    sp.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)c.beta2, (double)step)));
+  } else {
+    sp.inv_bc1 = sp.inv_bc2 = 1.0f;
+  }
+  sp.alpha = c.scale;
+  sp.gamma = c.nl_gamma;
+  sp.lr = lr;
+  sp.lr_decay = lr * c.weight_decay;
+  return sp;
+}
+
+// Copies the host descriptor table to the device through a pinned staging slot.
+int upload_descs(apollo_handle* h, hipStream_t st) {
+  const int slot = h->ring_next;
+  h->ring_next = (slot + 1) % kRingSlots;
+  hipError_t e;
+  if (h->ring_used[slot]) {
+    e = hipEventSynchronize(h->ring_ev[slot]);
+    if (e != hipSuccess) return hip_fail(h->err, e, "hipEventSynchronize");
+  }
+  std::memcpy(h->ring[slot], h->desc.data(), h->plan.desc_bytes);
+  e = hipMemcpyAsync(h->ws, h->ring[slot], h->plan.desc_bytes, hipMemcpyHostToDevice, st);
+  if (e != hipSuccess) return hip_fail(h->err, e, "hipMemcpyAsync(descriptor table)");
+  e = hipEventRecord(h->ring_ev[slot], st);
+  if (e != hipSuccess) return hip_fail(h->err, e, "hipEventRecord");
+  h->ring_used[slot] = true;
+  return APOLLO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t apollo_state_bytes(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n_tensors) {
+  Plan p;
+  if (make_plan(cfg, shapes, n_tensors, p, g_last_error) != APOLLO_OK) return 0;
+  return p.state_bytes;
+}
+
+size_t apollo_workspace_bytes(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n_tensors) {
+  Plan p;
+  if (make_plan(cfg, shapes, n_tensors, p, g_last_error) != APOLLO_OK) return 0;
+  return p.workspace_bytes;
+}
+
+apollo_status_t apollo_state_offsets(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n_tensors,
+                                     int32_t tensor, size_t* m_offset, size_t* v_offset, size_t* norm_offset) {
+  Plan p;
+  const int rc = make_plan(cfg, shapes, n_tensors, p, g_last_error);
+  if (rc != APOLLO_OK) return rc;
+  if (tensor < 0 || tensor >= n_tensors) return fail(g_last_error, APOLLO_EINVAL, "tensor index %lld out of range", tensor);
+  if (m_offset) *m_offset = p.t[tensor].st_m;
+  if (v_offset) *v_offset = p.t[tensor].st_v;
+  if (norm_offset) *norm_offset = p.t[tensor].st_norm;
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg, const apollo_shape_t* shapes,
+                            int32_t n_tensors, void* state, size_t state_bytes, void* workspace,
+                            size_t workspace_bytes, int32_t zero_state, void* hip_stream) {
+  if (!out) return fail(g_last_error, APOLLO_EINVAL, "null output handle pointer");
+  *out = nullptr;
+  apollo_handle* h = new (std::nothrow) apollo_handle();
+  if (!h) return fail(g_last_error, APOLLO_ENOMEM, "out of host memory");
+  int rc = make_plan(cfg, shapes, n_tensors, h->plan, g_last_error);
+  if (rc == APOLLO_OK && (!state || !workspace)) rc = fail(g_last_error, APOLLO_EINVAL, "null state or workspace buffer");
+  if (rc == APOLLO_OK && (((uintptr_t)state | (uintptr_t)workspace) & (kAlign - 1)))
+    rc = fail(g_last_error, APOLLO_ESTATE, "state / workspace not 256-byte aligned");
+  if (rc == APOLLO_OK && state_bytes < h->plan.state_bytes)
+    rc = fail(g_last_error, APOLLO_ESTATE, "state buffer has %lld bytes, %lld needed", (long long)state_bytes,
+              (long long)h->plan.state_bytes);
+  if (rc == APOLLO_OK && workspace_bytes < h->plan.workspace_bytes)
+    rc = fail(g_last_error, APOLLO_ESTATE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes,
+              (long long)h->plan.workspace_bytes);
+  if (rc != APOLLO_OK) {
+    delete h;
+    return rc;
+  }
+  h->cfg = *cfg;
+  h->state = static_cast<char*>(state);
+  h->ws = static_cast<char*>(workspace);
+  h->desc.resize(n_tensors);
+  h->last.assign(n_tensors, apollo_tensor_t{nullptr, nullptr});
+  for (int32_t k = 0; k < n_tensors; ++k) {
+    const TensorPlan& t = h->plan.t[k];
+    TensorDesc& d = h->desc[t.desc_index];
+    std::memset(&d, 0, sizeof d);
+    d.M = reinterpret_cast<float*>(h->state + t.st_m);
+    d.V = reinterpret_cast<float*>(h->state + t.st_v);
+    d.prev_norm = reinterpret_cast<float*>(h->state + t.st_norm);
+    d.P = t.path == Path::kRank1 ? nullptr : static_cast<void*>(h->ws + t.ws_p);
+    d.R = reinterpret_cast<float*>(h->ws + t.ws_r);
+    d.colsq = reinterpret_cast<float*>(h->ws + t.ws_colsq);
+    d.s = reinterpret_cast<float*>(h->ws + t.ws_s);
+    d.partials = reinterpret_cast<float*>(h->ws + t.ws_partials);
+    d.scal = reinterpret_cast<float*>(h->ws + t.ws_scal);
+    d.rows = t.rows; d.cols = t.cols; d.m = t.m; d.n = t.n; d.m8 = t.m8;
+    d.left = t.left; d.tensor_id = k; d.n_slabs = t.n_slabs; d.k2_blocks = t.k2_blocks;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipSuccess;
+  for (int i = 0; i < kRingSlots && e == hipSuccess; ++i) {
+    e = hipHostMalloc(reinterpret_cast<void**>(&h->ring[i]), h->plan.desc_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ring_ev[i], hipEventDisableTiming);
+  }
+  if (e == hipSuccess && zero_state) e = launch_fill_zero(h->state, h->plan.state_bytes, st);
+  if (e != hipSuccess) {
+    hip_fail(g_last_error, e, "apollo_init");
+    apollo_destroy(h);
+    return APOLLO_EHIP;
+  }
+  *out = h;
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, int32_t n_tensors, int64_t step,
+                            float lr, void* hip_stream) {
+  if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
+  const int32_t n = (int32_t)h->plan.t.size();
+  if (!tensors) return fail(h->err, APOLLO_EINVAL, "null tensor list");
+  if (n_tensors != n) return fail(h->err, APOLLO_EINVAL, "n_tensors %lld differs from the %lld given to apollo_init", n_tensors, n);
+  if (step < 1) return fail(h->err, APOLLO_EINVAL, "step %lld < 1 (steps are 1-based)", step);
+  if (!std::isfinite(lr)) return fail(h->err, APOLLO_EINVAL, "learning rate is not finite");
+  bool changed = !h->have_ptrs;
+  for (int32_t k = 0; k < n; ++k) {
+    if (!tensors[k].w || !tensors[k].g) return fail(h->err, APOLLO_EINVAL, "tensor %lld: null w or g", k);
+    if (((uintptr_t)tensors[k].w | (uintptr_t)tensors[k].g) & 15u)
+      return fail(h->err, APOLLO_EINVAL, "tensor %lld: w / g not 16-byte aligned", k);
+    if (tensors[k].w != h->last[k].w || tensors[k].g != h->last[k].g) changed = true;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (changed) {
+    for (int32_t k = 0; k < n; ++k) {
+      TensorDesc& d = h->desc[h->plan.t[k].desc_index];
+      d.w = static_cast<float*>(tensors[k].w);
+      d.g = tensors[k].g;
+      h->last[k] = tensors[k];
+    }
+    const int rc = upload_descs(h, st);
+    if (rc != APOLLO_OK) return rc;
+    h->have_ptrs = true;
+  }
+  const StepParams sp = make_step_params(h->cfg, step, lr);
+  const TensorDesc* dd = reinterpret_cast<const TensorDesc*>(h->ws);
+  hipError_t e = hipSuccess;
+  const char* what = "";
+  hipEvent_t* pev = nullptr;              // six events around the five phases, when profiling
+  if (h->profiling && h->prof_used + 6 <= 6 * 1024) {
+    while (h->prof_events.size() < h->prof_used + 6 && e == hipSuccess) {
+      hipEvent_t ev;
+      e = hipEventCreate(&ev);
+      if (e == hipSuccess) h->prof_events.push_back(ev);
+    }
+    if (e != hipSuccess) return hip_fail(h->err, e, "hipEventCreate");
+    pev = h->prof_events.data() + h->prof_used;
+    h->prof_used += 6;
+    e = hipEventRecord(pev[0], st);
+  }
+  // (a) the transient copy of P for the groups that read it from scratch
+  for (const Group& g : h->plan.groups) {
+    if (e != hipSuccess) break;
+    if (g.path == Path::kRank1) continue;
+    e = launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, st);
+    what = "projection fill";
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[1], st);
+  // (b) R = P G and the per-channel squared norms of G
+  for (const Group& g : h->plan.groups) {
+    if (e != hipSuccess) break;
+    what = "projection";
+    if (g.path == Path::kRank1)
+      e = launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sp, st);
+    else if (g.path == Path::kMfma)
+      e = launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, sp, st);
+    else
+      e = launch_project_generic(dd + g.first, g.count, g.n, g.bf16, sp, st);
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[2], st);
+  // (c) low-rank Adam moments, channel factors, block partial sums
+  for (const Group& g : h->plan.groups) {
+    if (e != hipSuccess) break;
+    e = launch_adam_norms(dd + g.first, g.count, g.n, sp, st);
+    what = "moment update";
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[3], st);
+  // (d) per-tensor factor, norm and limiter
+  if (e == hipSuccess) {
+    e = launch_finalize(dd, n, sp, st);
+    what = "limiter";
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[4], st);
+  // (e) W update
+  for (const Group& g : h->plan.groups) {
+    if (e != hipSuccess) break;
+    e = launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, sp, st);
+    what = "weight update";
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[5], st);
+  if (e != hipSuccess) return hip_fail(h->err, e, what);
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_profile_enable(apollo_handle_t* h, int32_t on) {
+  if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
+  h->profiling = on != 0;
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_profile_read(apollo_handle_t* h, float* ms, int32_t* n_steps) {
+  if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
+  if (!ms || !n_steps) return fail(h->err, APOLLO_EINVAL, "null output");
+  for (int p = 0; p < 5; ++p) ms[p] = 0.f;
+  *n_steps = (int32_t)(h->prof_used / 6);
+  for (size_t k = 0; k + 6 <= h->prof_used; k += 6) {
+    hipError_t e = hipEventSynchronize(h->prof_events[k + 5]);
+    for (int p = 0; p < 5 && e == hipSuccess; ++p) {
+      float t = 0.f;
+      e = hipEventElapsedTime(&t, h->prof_events[k + p], h->prof_events[k + p + 1]);
+      ms[p] += t;
+    }
+    if (e != hipSuccess) {
+      h->prof_used = 0;
+      return hip_fail(h->err, e, "phase timing");
+    }
+  }
+  h->prof_used = 0;
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_debug_fill_projection(apollo_handle_t* h, int32_t tensor, int64_t step, void* out,
+                                             int32_t dtype, void* hip_stream) {
+  if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
+  if (tensor < 0 || tensor >= (int32_t)h->plan.t.size()) return fail(h->err, APOLLO_EINVAL, "tensor index %lld out of range", tensor);
+  if (!out) return fail(h->err, APOLLO_EINVAL, "null output");
+  if (step < 1) return fail(h->err, APOLLO_EINVAL, "step %lld < 1", step);
+  if (dtype != APOLLO_F32 && dtype != APOLLO_BF16) return fail(h->err, APOLLO_EUNSUPPORTED, "dtype %lld", dtype);
+  const StepParams sp = make_step_params(h->cfg, step, 0.f);
+  const hipError_t e = launch_fill_projection_rowmajor(out, dtype == APOLLO_BF16, h->cfg.rank, h->plan.t[tensor].m,
+                                                       (uint32_t)tensor, sp, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(h->err, e, "projection fill (debug)");
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_debug_get(apollo_handle_t* h, int32_t tensor, int32_t what, void* out, size_t bytes,
+                                 void* hip_stream) {
+  if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
+  if (tensor < 0 || tensor >= (int32_t)h->plan.t.size()) return fail(h->err, APOLLO_EINVAL, "tensor index %lld out of range", tensor);
+  if (!out) return fail(h->err, APOLLO_EINVAL, "null output");
+  const TensorPlan& t = h->plan.t[tensor];
+  const size_t rn = (size_t)h->cfg.rank * t.n * sizeof(float);
+  const void* src = nullptr;
+  size_t need = 0;
+  switch (what) {
+    case APOLLO_DBG_M: src = h->state + t.st_m; need = rn; break;
+    case APOLLO_DBG_V: src = h->state + t.st_v; need = rn; break;
+    case APOLLO_DBG_S:
+      if (h->cfg.mode == APOLLO_TENSOR) { src = h->ws + t.ws_scal + 3 * sizeof(float); need = sizeof(float); }
+      else { src = h->ws + t.ws_s; need = (size_t)t.n * sizeof(float); }
+      break;
+    case APOLLO_DBG_NORM: src = h->state + t.st_norm; need = sizeof(float); break;
+    case APOLLO_DBG_C: src = h->ws + t.ws_scal + sizeof(float); need = sizeof(float); break;
+    case APOLLO_DBG_R: src = h->ws + t.ws_r; need = rn; break;
+    case APOLLO_DBG_COLSQ: src = h->ws + t.ws_colsq; need = (size_t)t.n * sizeof(float); break;
+    default: return fail(h->err, APOLLO_EINVAL, "unknown selector %lld", what);
+  }
+  if (bytes != need) return fail(h->err, APOLLO_EINVAL, "selector %lld holds %lld bytes, %lld given", what, (long long)need, (long long)bytes);
+  const hipError_t e = hipMemcpyAsync(out, src, need, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(h->err, e, "hipMemcpyAsync(debug)");
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_debug_philox(const void* ctr, uint32_t key0, uint32_t key1, void* out, int64_t count,
+                                    void* hip_stream) {
+  if (count < 0 || (count > 0 && (!ctr || !out))) return fail(g_last_error, APOLLO_EINVAL, "bad arguments");
+  const hipError_t e = launch_philox_words(static_cast<const uint32_t*>(ctr), key0, key1, static_cast<uint32_t*>(out),
+                                           count, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(g_last_error, e, "philox (debug)");
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_debug_gauss_parts(uint32_t first, int64_t count, void* radius, void* cosv, void* sinv,
+                                         void* hip_stream) {
+  if (count < 0 || (uint64_t)first + (uint64_t)count > (1ull << 24) || (count > 0 && (!radius || !cosv || !sinv)))
+    return fail(g_last_error, APOLLO_EINVAL, "bad arguments (inputs are 24-bit: first + count <= 2^24)");
+  const hipError_t e = launch_gauss_parts(first, count, static_cast<float*>(radius), static_cast<float*>(cosv),
+                                          static_cast<float*>(sinv), static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(g_last_error, e, "gauss parts (debug)");
+  return APOLLO_OK;
+}
+
+const char* apollo_last_error(const apollo_handle_t* h) { return h ? h->err.c_str() : g_last_error.c_str(); }
+
+void apollo_destroy(apollo_handle_t* h) {
+  if (!h) return;
+  for (int i = 0; i < kRingSlots; ++i) {
+    if (h->ring_used[i]) (void)hipEventSynchronize(h->ring_ev[i]);   // its own pending upload only
+    if (h->ring_ev[i]) (void)hipEventDestroy(h->ring_ev[i]);
+    if (h->ring[i]) (void)hipHostFree(h->ring[i]);
+  }
+  for (hipEvent_t ev : h->prof_events) (void)hipEventDestroy(ev);
+  delete h;
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Host/device shared declarations of the APOLLO step library (internal; the public interface
+// is include/apollo.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "philox_gauss.hpp"
+
+namespace apollo {
+
+// One weight matrix as the kernels see it.  Resident in the workspace; only w and g change
+// between steps.  m = projected (reduced) dimension, n = channel dimension (Algorithm 1 has
+// W in R^{m x n}, m <= n; `left` says whether m runs along the stored rows).
+struct TensorDesc {
+  float* w;            // rows x cols fp32, updated in place
+  const void* g;       // rows x cols, bf16 or fp32
+  float* M;            // state: M^R, r x n
+  float* V;            // state: V^R, r x n
+  float* prev_norm;    // state: stored norm of the scaled gradient (limiter), 1 float
+  void* P;             // scratch: unit-variance projection z, fragment-major (see p_index)
+  float* R;            // scratch: n_slabs partial copies of R, each r x n (slab 0 ends canonical)
+  float* colsq;        // scratch: n_slabs partial copies of sum_i G[i,j]^2, each n
+  float* s;            // scratch: channel factors s_j, n floats
+  float* partials;     // scratch: 4 floats per 64-channel block (sums of a_j, b_j, colsq_j, s_j^2 colsq_j)
+  float* scal;         // scratch: [0] lr*alpha*c(*s for tensor mode) [1] c [2] norm [3] s (tensor mode)
+  int32_t rows, cols;
+  int32_t m, n;
+  int32_t m8;          // m rounded up to a multiple of 8 (row length of P in the scratch)
+  int32_t left;        // 1: m = rows (R = P G), 0: m = cols (R = G P^T)
+  int32_t tensor_id;   // index in the caller's list: part of the generator's counter
+  int32_t n_slabs;     // number of partial sums the projection kernel leaves along m
+  int32_t k2_blocks;   // ceil(n / 64)
+  int32_t pad_;
+};
+
+// Per-step scalars handed to the kernels by value.
+struct StepParams {
+  PhiloxKeySchedule ks;
+  uint32_t epoch;      // (step-1) / T
+  int32_t r;           // rank
+  int32_t tensor_mode; // 1 = one factor per tensor (APOLLO-Mini), 0 = per channel
+  float rsqrt_r;       // 1/sqrt(r): the variance 1/r of P applied to the product
+  float beta1, beta2, omb1, omb2, eps;
+  float inv_bc1, inv_bc2;  // 1/(1-beta^t) or 1
+  float alpha, gamma;
+  float lr, lr_decay;  // lr, lr * lambda
+};
+
+// Element (kk, i) of the scratch projection: eight consecutive i of one row are contiguous, the
+// r rows of such an octet follow each other, octets follow along i.  A matrix-core A fragment
+// (32 or 16 rows x 8 i per lane) is then one contiguous, coalesced 16-byte load per lane.
+__host__ __device__ inline size_t p_index(int kk, int i, int r) {
+  return ((size_t)(i >> 3) * (size_t)r + (size_t)kk) * 8u + (size_t)(i & 7);
+}
+
+// ---- launchers (defined in the .hip files); all enqueue on `st` and return the launch status
+hipError_t launch_fill_projection(const TensorDesc* d_descs, int count, int r, int m8, bool bf16,
+                                  const StepParams& sp, hipStream_t st);
+hipError_t launch_fill_projection_rowmajor(void* out, bool out_bf16, int r, int m, uint32_t tensor_id,
+                                           const StepParams& sp, hipStream_t st);
+hipError_t launch_project_generic(const TensorDesc* d_descs, int count, int n, bool bf16,
+                                  const StepParams& sp, hipStream_t st);
+hipError_t launch_project_rank1(const TensorDesc* d_descs, int count, int rows, int cols, bool left,
+                                bool bf16, int n_slabs, const StepParams& sp, hipStream_t st);
+bool project_rank1_supported(int rows, int cols, bool left, bool bf16);
+hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left,
+                               const StepParams& sp, hipStream_t st);
+bool project_mfma_supported(int rows, int cols, bool left, bool bf16, int r);
+hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, const StepParams& sp,
+                             hipStream_t st);
+hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepParams& sp, hipStream_t st);
+hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
+                         const StepParams& sp, hipStream_t st);
+hipError_t launch_philox_words(const uint32_t* ctr, uint32_t k0, uint32_t k1, uint32_t* out,
+                               int64_t count, hipStream_t st);
+hipError_t launch_gauss_parts(uint32_t first, int64_t count, float* radius, float* cosv, float* sinv,
+                              hipStream_t st);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+
+}  // namespace apollo

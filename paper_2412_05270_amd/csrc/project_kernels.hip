@@ -1,0 +1,293 @@
+// Projection kernels R = P G (Algorithm 1, step 1) with the by-product colsq_j = sum_i G[i,j]^2
+// (needed by the norm-growth limiter, Section 3.2): a general fp32-FMA kernel for any rank,
+// dtype and orientation, and a streaming kernel for rank 1 (APOLLO-Mini, Section 4.2) that
+// generates its row of P on the fly.
+#include "apollo_internal.h"
+
+namespace apollo {
+
+__device__ __forceinline__ float load_g(const void* g, size_t idx, bool bf16) {
+  if (bf16) return bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(g)[idx]);
+  return reinterpret_cast<const float*>(g)[idx];
+}
+
+// ---------------------------------------------------------------------------------------------
+// General projection: block = 64 channels x 32 rows of R, looping over the reduced dimension in
+// steps of 32 through LDS.  P comes from the scratch copy written by fill_projection_kernel.
+// Gm(i, j) is G[i][j] when the rows are projected (left) and G[j][i] otherwise.
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void project_generic_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
+  __shared__ float Gs[32][65];
+  __shared__ float Ps[32][33];
+  const TensorDesc& d = descs[blockIdx.z];
+  const int r = sp.r, m = d.m, n = d.n, cols = d.cols;
+  const int tid = threadIdx.x;
+  const int j0 = blockIdx.x * 64, kk0 = blockIdx.y * 32;
+  const int tx = tid & 15, ty = tid >> 4;
+  float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  float sq = 0.f;
+  for (int i0 = 0; i0 < m; i0 += 32) {
+    if (d.left) {
+      const int jj = tid & 63;
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const int ii = (tid >> 6) + 4 * p;
+        const int i = i0 + ii, j = j0 + jj;
+        Gs[ii][jj] = (i < m && j < n) ? load_g(d.g, (size_t)i * cols + j, BF16) : 0.f;
+      }
+    } else {
+      const int ii = tid & 31;
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const int jj = (tid >> 5) + 8 * p;
+        const int i = i0 + ii, j = j0 + jj;
+        Gs[ii][jj] = (i < m && j < n) ? load_g(d.g, (size_t)j * cols + i, BF16) : 0.f;
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int e = tid + 256 * p;
+      const int i8 = e & 7, kk = (e >> 3) & 31, io = e >> 8;
+      const int ii = io * 8 + i8;
+      const int i = i0 + ii, k = kk0 + kk;
+      float v = 0.f;
+      if (k < r && i < d.m8) {
+        const size_t idx = p_index(k, i, r);
+        v = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(d.P)[idx])
+                 : reinterpret_cast<const float*>(d.P)[idx];
+      }
+      Ps[kk][ii] = v;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int ii = 0; ii < 32; ++ii) {
+      const float p0 = Ps[2 * ty][ii], p1 = Ps[2 * ty + 1][ii];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float gv = Gs[ii][4 * tx + c];
+        acc[0][c] = __builtin_fmaf(p0, gv, acc[0][c]);
+        acc[1][c] = __builtin_fmaf(p1, gv, acc[1][c]);
+      }
+    }
+    if (blockIdx.y == 0 && tid < 64) {
+#pragma unroll 8
+      for (int ii = 0; ii < 32; ++ii) sq = __builtin_fmaf(Gs[ii][tid], Gs[ii][tid], sq);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const int k = kk0 + 2 * ty + a;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int j = j0 + 4 * tx + c;
+      if (k < r && j < n) d.R[(size_t)k * n + j] = acc[a][c] * sp.rsqrt_r;
+    }
+  }
+  if (blockIdx.y == 0 && tid < 64 && j0 + tid < n) d.colsq[j0 + tid] = sq;
+}
+
+hipError_t launch_project_generic(const TensorDesc* d_descs, int count, int n, bool bf16, const StepParams& sp,
+                                  hipStream_t st) {
+  dim3 grid((unsigned)((n + 63) / 64), (unsigned)((sp.r + 31) / 32), (unsigned)count);
+  if (bf16)
+    hipLaunchKernelGGL(project_generic_kernel<true>, grid, dim3(256), 0, st, d_descs, sp);
+  else
+    hipLaunchKernelGGL(project_generic_kernel<false>, grid, dim3(256), 0, st, d_descs, sp);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rank 1 (APOLLO-Mini): R[j] = sum_i z[i] Gm[i, j] is a matrix-vector product, bound by the one
+// pass over G.  z is generated into LDS by the block that needs it; G is read with 16-byte
+// loads (eight bf16).  Requires cols % 8 == 0 and bf16 gradients.
+// ---------------------------------------------------------------------------------------------
+
+// unpack eight bf16 (one 16-byte load) to floats
+__device__ __forceinline__ void unpack8(const uint4& v, float f[8]) {
+  f[0] = __uint_as_float(v.x << 16);
+  f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(v.y << 16);
+  f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(v.z << 16);
+  f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(v.w << 16);
+  f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+
+// Generates z[i0 .. i0+count) (count % 4 == 0 or the tail beyond m ignored) into zs[0 .. count).
+__device__ __forceinline__ void gen_z_to_lds(float* zs, int i0, int count, int m, const StepParams& sp,
+                                             uint32_t tensor_id, bool round_bf16) {
+  const int q0 = i0 >> 2;                      // i0 is a multiple of 4
+  const int nq = (count + 3) >> 2;
+  for (int q = threadIdx.x; q < nq; q += blockDim.x) {
+    float z[4];
+    projection_quad(sp.ks, sp.epoch, tensor_id, (uint64_t)(q0 + q), z);   // row kk = 0
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int li = 4 * q + e;
+      if (li < count) {
+        float v = (i0 + li < m) ? z[e] : 0.f;
+        if (round_bf16) v = bf16_bits_to_f32(f32_to_bf16_bits(v));
+        zs[li] = v;
+      }
+    }
+  }
+}
+
+// LEFT (rows projected): block = 512 columns x one slab of rows; thread (tx = column octet,
+// ty = row lane) accumulates eight column dot products over its rows; the four row lanes are
+// combined through LDS.  Output: partial R and colsq of this slab.
+constexpr int kMiniSlabRowsMax = 1024;
+
+__global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
+                                                                 int slab_rows) {
+  __shared__ float zs[kMiniSlabRowsMax];
+  __shared__ float red[2][3][64][9];
+  const TensorDesc& d = descs[blockIdx.z];
+  const int rows = d.rows, cols = d.cols;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int i0 = blockIdx.y * slab_rows;
+  const int i1 = min(rows, i0 + slab_rows);
+  gen_z_to_lds(zs, i0, i1 - i0, rows, sp, (uint32_t)d.tensor_id, true);
+  __syncthreads();
+  const int cv = blockIdx.x * 64 + tx;          // column octet
+  const bool active = cv * 8 < cols;
+  float acc[8], sq[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = sq[e] = 0.f;
+  if (active) {
+    const uint4* gp = reinterpret_cast<const uint4*>(d.g) + (size_t)cv;
+    const size_t stride = (size_t)(cols >> 3);
+    int i = i0 + ty;
+    for (; i + 12 < i1; i += 16) {
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = gp[(size_t)(i + 4 * u) * stride];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float z = zs[i + 4 * u - i0];
+        float f[8];
+        unpack8(v[u], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          acc[e] = __builtin_fmaf(z, f[e], acc[e]);
+          sq[e] = __builtin_fmaf(f[e], f[e], sq[e]);
+        }
+      }
+    }
+    for (; i < i1; i += 4) {
+      const uint4 v = gp[(size_t)i * stride];
+      const float z = zs[i - i0];
+      float f[8];
+      unpack8(v, f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        acc[e] = __builtin_fmaf(z, f[e], acc[e]);
+        sq[e] = __builtin_fmaf(f[e], f[e], sq[e]);
+      }
+    }
+  }
+  if (ty > 0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      red[0][ty - 1][tx][e] = acc[e];
+      red[1][ty - 1][tx][e] = sq[e];
+    }
+  }
+  __syncthreads();
+  if (ty == 0 && active) {
+    float* Rp = d.R + (size_t)blockIdx.y * d.n + (size_t)cv * 8;
+    float* Cp = d.colsq + (size_t)blockIdx.y * d.n + (size_t)cv * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float a = ((acc[e] + red[0][0][tx][e]) + red[0][1][tx][e]) + red[0][2][tx][e];
+      const float b = ((sq[e] + red[1][0][tx][e]) + red[1][1][tx][e]) + red[1][2][tx][e];
+      Rp[e] = a;            // r = 1: 1/sqrt(r) = 1
+      Cp[e] = b;
+    }
+  }
+}
+
+// RIGHT (columns projected): R[i] = sum_j z[j] G[i][j]; a wave owns whole rows, four at a time,
+// lanes stride the row in 16-byte pieces, then a wave reduction.  z for the whole row (m <= 16384)
+// sits in LDS.
+constexpr int kMiniRightMaxM = 16384;
+constexpr int kMiniRightRowsPerBlock = 128;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__global__ __launch_bounds__(256) void project_rank1_right_kernel(const TensorDesc* __restrict__ descs,
+                                                                  StepParams sp) {
+  extern __shared__ float zs[];
+  const TensorDesc& d = descs[blockIdx.z];
+  const int rows = d.rows, cols = d.cols;
+  gen_z_to_lds(zs, 0, cols, cols, sp, (uint32_t)d.tensor_id, true);
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nv = cols >> 3;
+  const uint4* gbase = reinterpret_cast<const uint4*>(d.g);
+  const int row_begin = blockIdx.x * kMiniRightRowsPerBlock + wave * (kMiniRightRowsPerBlock / 4);
+  const int row_end = min(rows, row_begin + kMiniRightRowsPerBlock / 4);
+  for (int i = row_begin; i < row_end; i += 4) {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f}, sq[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int v0 = lane; v0 < nv; v0 += 64) {
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int ii = min(i + u, rows - 1);
+        v[u] = gbase[(size_t)ii * nv + v0];
+      }
+      const float4 za = reinterpret_cast<const float4*>(zs)[2 * v0];
+      const float4 zb = reinterpret_cast<const float4*>(zs)[2 * v0 + 1];
+      const float z[8] = {za.x, za.y, za.z, za.w, zb.x, zb.y, zb.z, zb.w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float f[8];
+        unpack8(v[u], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          acc[u] = __builtin_fmaf(z[e], f[e], acc[u]);
+          sq[u] = __builtin_fmaf(f[e], f[e], sq[u]);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float a = wave_sum(acc[u]);
+      const float b = wave_sum(sq[u]);
+      if (lane == 0 && i + u < row_end) {
+        d.R[i + u] = a;
+        d.colsq[i + u] = b;
+      }
+    }
+  }
+}
+
+bool project_rank1_supported(int rows, int cols, bool left, bool bf16) {
+  if (!bf16 || (cols & 7) != 0) return false;
+  if (!left && cols > kMiniRightMaxM) return false;
+  (void)rows;
+  return true;
+}
+
+hipError_t launch_project_rank1(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
+                                int n_slabs, const StepParams& sp, hipStream_t st) {
+  (void)bf16;
+  if (left) {
+    const int slab_rows = (((rows + n_slabs - 1) / n_slabs) + 3) & ~3;   // multiple of 4: slabs start on a quad
+    dim3 grid((unsigned)((cols / 8 + 63) / 64), (unsigned)n_slabs, (unsigned)count);
+    hipLaunchKernelGGL(project_rank1_left_kernel, grid, dim3(256), 0, st, d_descs, sp, slab_rows);
+  } else {
+    dim3 grid((unsigned)((rows + kMiniRightRowsPerBlock - 1) / kMiniRightRowsPerBlock), 1, (unsigned)count);
+    hipLaunchKernelGGL(project_rank1_right_kernel, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sp);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace apollo

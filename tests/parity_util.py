@@ -1,0 +1,179 @@
+"""Shared driver of the GPU parity tests: runs the HIP library (through the C ABI) and the fp64
+oracle on the same seeded inputs and compares them quantity by quantity.
+
+Tolerance (the benchmark definition's): an element passes if |x - ref| <= tol * (|ref| + rms(ref))
+with tol = 1e-5 for fp32 gradients and 1e-3 for bf16 gradients; rms over the tensor.  The rms
+term is there because R = P G cancels: single entries can be arbitrarily small relative to the
+products summed.  That bound is applied as it stands to R, colsq, M, V and W.
+
+The factor s_j = ||R~[:,j]|| / ||R[:,j]|| divides by a column norm of R, so a channel whose
+projected gradient (or its history, through V, or its first moment M, which cancels when
+successive projected gradients have opposite signs) happens to be k times smaller than a
+typical one turns the admissible error of R into a k times larger relative error of s_j, and of
+everything that is multiplied by s_j (that channel's dW, and the tensor norm in proportion to
+the channel's weight in it).  condition_factors() computes k per channel from the oracle's own
+R, M and V by first-order error propagation (1 for a typical channel; for the tensor-wise
+factor, a ratio of Frobenius norms, it is 1 in practice); s, dW, norm and c are held to tol * k.
+"""
+import math
+
+import numpy as np
+import torch
+
+import paper_2412_05270_amd as A
+from oracle import apollo as O
+from paper_2412_05270_amd import workloads as WL
+
+TOL_F32 = 1e-5
+TOL_BF16 = 1e-3
+
+
+def f32(v):
+    return float(np.float32(v))
+
+
+def make_configs(wl, seed=0x5EED5EED1234, side="auto", bias_correction=True):
+    """The same hyper-parameters for both sides, rounded to fp32 once (the C ABI carries floats)."""
+    mode = A.APOLLO_TENSOR if wl.mode == "tensor" else A.APOLLO_CHANNEL
+    side_code = {"auto": A.APOLLO_SIDE_AUTO, "left": A.APOLLO_SIDE_LEFT, "right": A.APOLLO_SIDE_RIGHT}[side]
+    cfg = A.ApolloConfig(rank=wl.rank, mode=mode, seed=seed, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
+                         scale=wl.scale, weight_decay=wl.weight_decay, nl_gamma=wl.nl_gamma,
+                         refresh_interval=wl.refresh_interval, bias_correction=1 if bias_correction else 0,
+                         side=side_code, reserved=0)
+    ocfg = O.Config(rank=wl.rank, mode=O.TENSOR if wl.mode == "tensor" else O.CHANNEL, seed=seed,
+                    beta1=f32(wl.beta1), beta2=f32(wl.beta2), eps=f32(wl.eps), scale=f32(wl.scale),
+                    weight_decay=f32(wl.weight_decay), nl_gamma=f32(wl.nl_gamma),
+                    refresh_interval=wl.refresh_interval, bias_correction=bias_correction, side=side)
+    return cfg, ocfg
+
+
+def assert_close(name, got, ref, tol, extra_abs=0.0):
+    """extra_abs (scalar or array): an additional absolute allowance, used for dW = W_after -
+    W_before, which carries the rounding of the fp32 store of W (half an ulp of W) whatever
+    the kernel does."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), name + ": non-finite values"
+    rms = math.sqrt(float(np.mean(ref * ref))) if ref.size else 0.0
+    err = np.abs(got - ref)
+    bound = tol * (np.abs(ref) + rms) + extra_abs
+    bad = err > bound
+    if np.any(bad):
+        k = int(np.argmax(err - bound))
+        raise AssertionError("%s: %d of %d elements off; worst at flat %d: got %.9g ref %.9g (rms %.3g, tol %g)"
+                             % (name, int(bad.sum()), ref.size, k, got.ravel()[k], ref.ravel()[k], rms, tol))
+
+
+def condition_factors(info, state, ocfg, t, tol):
+    """Per-channel amplification k_j >= 1 of the relative error of s_j (see the module text) and
+    its weighted mean for the tensor norm N = alpha sqrt(sum_j s_j^2 colsq_j).
+
+    First-order propagation of the admissible element errors dX = tol (|X| + rms X) of R, M, V
+    through R~ = M^ / (sqrt(V^) + eps), a_j = sum R~^2, b_j = sum R^2, s_j = sqrt(a_j / b_j).
+    For an element of typical size that propagation gives 5 tol (2 + 1 for R~, 2 for R); those
+    typical 4 tol in excess of the stated tolerance are taken off again, so a typical channel is
+    held to tol itself and an ill-conditioned one to its propagated bound.
+    """
+    R, M, V = info["R"], state.M, state.V
+    bc1 = 1.0 - ocfg.beta1 ** t if ocfg.bias_correction else 1.0
+    bc2 = 1.0 - ocfg.beta2 ** t if ocfg.bias_correction else 1.0
+    rms = lambda x: math.sqrt(float(np.mean(x * x)))
+    dR = tol * (np.abs(R) + rms(R))
+    dM = tol * (np.abs(M) + rms(M)) / bc1
+    dV = tol * (np.abs(V) + rms(V)) / bc2
+    Mh, Vh = M / bc1, V / bc2
+    sq = np.sqrt(Vh)
+    den = sq + ocfg.eps
+    with np.errstate(divide="ignore", invalid="ignore"):
+        d_sq = np.where(sq > 0, np.minimum(dV / (2.0 * sq), np.sqrt(dV)), np.sqrt(dV))
+        dRt = dM / den + np.abs(Mh) * d_sq / (den * den)
+    Rt = info["Rt"]
+    dRt = np.minimum(np.nan_to_num(dRt, nan=1.0, posinf=1e30), np.abs(Rt) + 1.0)
+    da = np.sum(2.0 * np.abs(Rt) * dRt + dRt * dRt, axis=0)
+    db = np.sum(2.0 * np.abs(R) * dR + dR * dR, axis=0)
+    a = np.sum(Rt * Rt, axis=0)
+    b = np.sum(R * R, axis=0)
+    n = R.shape[1]
+    if ocfg.mode == O.TENSOR:
+        rel = np.full(n, (da.sum() / (2.0 * a.sum()) if a.sum() > 0 else 0.0)
+                      + (db.sum() / (2.0 * b.sum()) if b.sum() > 0 else 0.0))
+    else:
+        with np.errstate(divide="ignore", invalid="ignore"):
+            rel = np.where(a > 0, da / (2.0 * a), 0.0) + np.where(b > 0, db / (2.0 * b), 0.0)
+    f = np.maximum(1.0, rel / tol - 4.0)
+    w = info["s"] ** 2 * info["colsq"]
+    f_norm = float(np.sum(w * f) / np.sum(w)) if np.sum(w) > 0 else 1.0
+    return f, f_norm
+
+
+def to_host_f64(t):
+    return t.detach().to("cpu").to(torch.float32).to(torch.float64).numpy()
+
+
+def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side="auto", bias_correction=True,
+               boost=None, compare_steps=None, lr=None, progress=None):
+    """Steps the whole workload on the GPU and the tensors `check_ids` in the oracle.
+    boost: {step: factor} multiplies that step's gradients.  Returns the number of limiter hits
+    seen by the oracle (so callers can assert the case was exercised)."""
+    boost = boost or {}
+    lr = wl.lr if lr is None else lr
+    lr32 = f32(lr)
+    bf16 = wl.grad_dtype == torch.bfloat16
+    tol = TOL_BF16 if bf16 else TOL_F32
+    cfg, ocfg = make_configs(wl, seed, side, bias_correction)
+    weights = WL.make_weights(wl, device)
+    grads = [torch.empty(s, dtype=wl.grad_dtype, device=device) for s in wl.shapes]
+    stepper = A.ApolloStepper(cfg, weights, grads, device=device)
+    states = {i: O.init_state(ocfg, *wl.shapes[i]) for i in check_ids}
+    W_or = {i: to_host_f64(weights[i]) for i in check_ids}
+    hits = 0
+    f_norm_prev = {i: 0.0 for i in check_ids}
+    for t in range(1, steps + 1):
+        WL.make_grads(wl, t, device, out=grads, boost=boost.get(t, 1.0))
+        before = {i: to_host_f64(weights[i]) for i in check_ids}
+        stepper.step(t, lr)
+        torch.cuda.synchronize()
+        full = compare_steps is None or t in compare_steps
+        for i in check_ids:
+            G = to_host_f64(grads[i])
+            # every step starts both sides from the same fp32 weights (the GPU's): the weight-decay
+            # term reads W, and the two trajectories differ by the admissible error of earlier steps
+            W_or[i] = before[i].copy()
+            W_prev = before[i]
+            info = O.step(ocfg, states[i], W_or[i], G, t, lr32, tensor_id=i, grad_is_bf16=bf16)
+            hits += info["c"] < 1.0
+            f_chan, f_norm = condition_factors(info, states[i], ocfg, t, tol)
+            f_c = f_norm + f_norm_prev[i]
+            f_norm_prev[i] = f_norm
+            # admissible error of this step's dW: the factors' relative error times |dW|
+            f_dw = f_chan + (f_c if info["c"] < 1.0 else 0.0)
+            f_dw = f_dw[None, :] if info["left"] else f_dw[:, None]
+            dw_ref = W_or[i] - W_prev
+            rms_dw = math.sqrt(float(np.mean(dw_ref * dw_ref)))
+            dw_bound = tol * f_dw * (np.abs(dw_ref) + rms_dw)
+            if not full:
+                continue
+            tag = "%s tensor %d step %d " % (wl.name, i, t)
+            assert_close(tag + "R", to_host_f64(stepper.debug(i, A.APOLLO_DBG_R)), info["R"], tol)
+            assert_close(tag + "colsq", to_host_f64(stepper.debug(i, A.APOLLO_DBG_COLSQ)), info["colsq"], tol)
+            assert_close(tag + "M", to_host_f64(stepper.debug(i, A.APOLLO_DBG_M)), states[i].M, tol)
+            assert_close(tag + "V", to_host_f64(stepper.debug(i, A.APOLLO_DBG_V)), states[i].V, tol)
+            s_gpu = to_host_f64(stepper.debug(i, A.APOLLO_DBG_S))
+            s_ref = info["s"] if wl.mode == "channel" else info["s"][:1]
+            f_s = f_chan if wl.mode == "channel" else f_chan[:1]
+            assert_close(tag + "s", s_gpu, s_ref, 0.0, extra_abs=tol * f_s * np.abs(s_ref))
+            c_gpu = to_host_f64(stepper.debug(i, A.APOLLO_DBG_C))
+            assert_close(tag + "c", c_gpu, [info["c"]], tol * f_c)
+            assert_close(tag + "norm", to_host_f64(stepper.debug(i, A.APOLLO_DBG_NORM)), [info["norm"]],
+                         tol * f_norm)
+            after = to_host_f64(weights[i])
+            if float(c_gpu[0]) < 1.0 and not info["c"] < 1.0:         # only the GPU side limited (c ~ 1)
+                dw_bound = dw_bound + tol * f_c * (np.abs(dw_ref) + rms_dw)
+            assert_close(tag + "dW", after - before[i], dw_ref, 0.0,
+                         extra_abs=dw_bound + np.abs(after) * 2.0 ** -24)
+            assert_close(tag + "W", after, W_or[i], tol, extra_abs=dw_bound)
+        if progress:
+            print("%s: step %d/%d compared" % (wl.name, t, steps), flush=True)
+    stepper.close()
+    return hits

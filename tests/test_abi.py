@@ -1,0 +1,98 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes the state as Table 1 of the paper says, and rejects bad arguments before
+anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2412_05270_amd as A
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _cfg(**kw):
+    base = dict(rank=4, mode=A.APOLLO_CHANNEL, seed=1, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0,
+                weight_decay=0.0, nl_gamma=1.01, refresh_interval=200, bias_correction=1,
+                side=A.APOLLO_SIDE_AUTO, reserved=0)
+    base.update(kw)
+    return A.ApolloConfig(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = A.load_library()
+    header = open(os.path.join(ROOT, "include", "apollo.h")).read()
+    names = set(re.findall(r"\b(apollo_[a-z_]+)\s*\(", header))
+    assert {"apollo_init", "apollo_step", "apollo_state_bytes", "apollo_workspace_bytes", "apollo_destroy",
+            "apollo_debug_fill_projection", "apollo_debug_get", "apollo_state_offsets", "apollo_last_error",
+            "apollo_debug_philox", "apollo_debug_gauss_parts"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_sizes_match_the_header_layout():
+    assert C.sizeof(A.ApolloShape) == 24
+    assert C.sizeof(A.ApolloConfig) == 56
+    assert C.sizeof(A.ApolloTensor) == 16
+
+
+def test_state_bytes_follow_table_1():
+    # 2 n r moments + 1 norm per tensor, n the larger dimension; blocks 256-byte aligned
+    shapes = [(8, 20, A.APOLLO_F32), (20, 8, A.APOLLO_BF16)]
+    cfg = _cfg(rank=4)
+    per = (2 * 4 * 20 + 1) * 4
+    per_aligned = (per + 255) // 256 * 256
+    assert A.apollo_state_bytes(cfg, shapes) == 2 * per_aligned
+    rc, m, v, nm = A.apollo_state_offsets(cfg, shapes, 1)
+    assert (rc, m, v, nm) == (0, per_aligned, per_aligned + 4 * 20 * 4, per_aligned + 2 * 4 * 20 * 4)
+    # LLaMA-7B at r = 256: 809 500 672 moment elements (the paper's 1.6G in bf16)
+    llama = ([(4096, 4096, 1)] * 4 + [(11008, 4096, 1)] * 2 + [(4096, 11008, 1)]) * 32
+    sb = A.apollo_state_bytes(_cfg(rank=256), llama)
+    assert sb >= 4 * (809_500_672 + 224) and sb < 4 * (809_500_672 + 224) + 256 * 224
+    # forcing the side changes which dimension carries the channels
+    assert A.apollo_state_bytes(_cfg(rank=4, side=A.APOLLO_SIDE_RIGHT), [(8, 20, 0)]) == \
+        ((2 * 4 * 8 + 1) * 4 + 255) // 256 * 256
+
+
+@pytest.mark.parametrize("kw,shapes,code", [
+    (dict(rank=0), [(8, 8, 0)], A.APOLLO_EINVAL),
+    (dict(rank=9), [(8, 16, 0)], A.APOLLO_EINVAL),            # rank above the projected dimension
+    (dict(rank=9, side=A.APOLLO_SIDE_RIGHT), [(16, 8, 0)], A.APOLLO_EINVAL),
+    (dict(refresh_interval=0), [(8, 8, 0)], A.APOLLO_EINVAL),
+    (dict(mode=7), [(8, 8, 0)], A.APOLLO_EINVAL),
+    (dict(side=5), [(8, 8, 0)], A.APOLLO_EINVAL),
+    (dict(beta1=1.0), [(8, 8, 0)], A.APOLLO_EINVAL),
+    (dict(eps=-1.0), [(8, 8, 0)], A.APOLLO_EINVAL),
+    (dict(), [(0, 8, 0)], A.APOLLO_EINVAL),
+    (dict(), [(8, 8, 3)], A.APOLLO_EUNSUPPORTED),             # fp16 / fp8 gradients are not supported
+    (dict(), [(8, (1 << 20) + 1, 0)], A.APOLLO_EUNSUPPORTED),
+    (dict(), [], A.APOLLO_EINVAL),
+])
+def test_bad_arguments_are_rejected_before_any_launch(kw, shapes, code):
+    cfg = _cfg(**kw)
+    assert A.apollo_state_bytes(cfg, shapes) == 0
+    assert A.apollo_workspace_bytes(cfg, shapes) == 0
+    rc, h = A.apollo_init(cfg, shapes, 256, 1 << 30, 512, 1 << 30)      # fake aligned pointers: never touched
+    assert rc == code and h is None
+    assert A.apollo_last_error() != ""
+
+
+def test_init_rejects_small_or_misaligned_buffers_without_touching_them():
+    cfg = _cfg()
+    shapes = [(8, 8, 0)]
+    sb, wb = A.apollo_state_bytes(cfg, shapes), A.apollo_workspace_bytes(cfg, shapes)
+    assert sb > 0 and wb > 0
+    assert A.apollo_init(cfg, shapes, 256, sb - 1, 512, wb)[0] == A.APOLLO_ESTATE
+    assert A.apollo_init(cfg, shapes, 256, sb, 512, wb - 1)[0] == A.APOLLO_ESTATE
+    assert A.apollo_init(cfg, shapes, 264, sb, 512, wb)[0] == A.APOLLO_ESTATE
+    assert A.apollo_init(cfg, shapes, None, sb, 512, wb)[0] == A.APOLLO_EINVAL
+    assert A.apollo_init(None, shapes, 256, sb, 512, wb)[0] == A.APOLLO_EINVAL
+
+
+def test_null_handle_calls_fail_cleanly():
+    assert A.apollo_step(None, [(16, 32)], 1, 0.1) == A.APOLLO_EINVAL
+    assert A.apollo_debug_get(None, 0, A.APOLLO_DBG_M, 16, 4) == A.APOLLO_EINVAL
+    assert A.apollo_debug_fill_projection(None, 0, 1, 16, A.APOLLO_F32) == A.APOLLO_EINVAL
+    assert A.apollo_debug_gauss_parts(1 << 24, 1, 16, 16, 16) == A.APOLLO_EINVAL
+    A.apollo_destroy(None)

@@ -1,0 +1,143 @@
+"""GPU parity of the whole step against the fp64 oracle, through the C ABI, on the benchmark's
+configurations (all tensors stepped on the GPU in the launch configuration the benchmark uses;
+the oracle follows a subset where the full set does not fit the host) and on edge cases."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2412_05270_amd as A
+from paper_2412_05270_amd import workloads as WL
+from parity_util import assert_close, make_configs, run_parity, to_host_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _first_and_last_layer(wl):
+    """One tensor of each distinct shape from the first and from the last layer."""
+    ids, seen = [], set()
+    for i, s in enumerate(wl.shapes[:7]):
+        if s not in seen:
+            seen.add(s)
+            ids.append(i)
+    n = len(wl.shapes)
+    return ids + [n - 7 + (i % 7) for i in ids]
+
+
+def test_single256_fp32_all_steps():
+    wl = WL.workload("single256")
+    run_parity(wl, [0], wl.steps)                      # T = 5: crosses two refreshes
+
+
+def test_llama60m_bf16_rank128():
+    wl = WL.workload("llama60m")
+    ids = list(range(len(wl.shapes)))
+    run_parity(wl, ids, 12, compare_steps={1, 2, 7, 12})
+
+
+def test_llama60m_long_run_subset():
+    wl = WL.workload("llama60m")
+    run_parity(wl, _first_and_last_layer(wl), wl.steps, compare_steps={1, 50, 100})
+
+
+RAGGED = [(100, 36), (36, 100), (77, 130), (130, 77), (8, 8), (64, 2056), (300, 520), (1100, 264),
+          (1500, 2056), (33, 33)]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("mode,rank,scale", [("channel", 1, 1.0), ("tensor", 1, math.sqrt(128.0)),
+                                             ("channel", 7, 1.0), ("tensor", 8, 2.0)])
+def test_ragged_shapes_both_sides_with_weight_decay_and_limiter(dtype, mode, rank, scale):
+    wl = WL.Workload("ragged", 7, RAGGED, dtype, "normal", 1e-2, rank=rank, mode=mode, scale=scale,
+                     refresh_interval=3, steps=7, lr=1e-2, weight_decay=0.05)
+    run_parity(wl, list(range(len(RAGGED))), wl.steps, boost={4: 3.0})
+
+
+@pytest.mark.parametrize("side", ["left", "right"])
+def test_forced_side_and_no_bias_correction(side):
+    shapes = [(48, 96), (96, 48), (64, 64)]
+    wl = WL.Workload("forced", 8, shapes, torch.bfloat16, "normal", 1e-2, rank=6, refresh_interval=2,
+                     steps=5, lr=1e-2)
+    run_parity(wl, [0, 1, 2], wl.steps, side=side, bias_correction=False)
+
+
+def test_limiter_is_exercised_and_matches():
+    """A gradient, its negative, then its negative again: the moment nearly cancels and builds up
+    again, so the scaled-gradient norm grows by far more than gamma at step 3."""
+    shapes = [(64, 128), (128, 64)]
+    for mode, rank in (("channel", 8), ("tensor", 1)):
+        wl = WL.Workload("limiter", 9, shapes, torch.bfloat16, "normal", 1e-2, rank=rank, mode=mode,
+                         refresh_interval=100, steps=4, lr=1e-2)
+        cfg, ocfg = make_configs(wl)
+        from oracle import apollo as O
+        weights = WL.make_weights(wl, DEV)
+        g0 = WL.make_grads(wl, 1, DEV)
+        grads = [g.clone() for g in g0]
+        st = A.ApolloStepper(cfg, weights, grads, device=DEV)
+        ost = [O.init_state(ocfg, *s) for s in shapes]
+        W = [to_host_f64(w) for w in weights]
+        hits = 0
+        for t, sign in enumerate((1.0, -1.0, -1.0, 1.0), start=1):
+            for g, src in zip(grads, g0):
+                g.copy_((src.float() * sign).to(torch.bfloat16))
+            st.step(t, wl.lr)
+            torch.cuda.synchronize()
+            for i in range(len(shapes)):
+                info = O.step(ocfg, ost[i], W[i], to_host_f64(grads[i]), t, float(np.float32(wl.lr)), tensor_id=i,
+                              grad_is_bf16=True)
+                hits += info["c"] < 1.0
+                assert_close("c", to_host_f64(st.debug(i, A.APOLLO_DBG_C)), [info["c"]], 1e-3)
+                assert_close("norm", to_host_f64(st.debug(i, A.APOLLO_DBG_NORM)), [info["norm"]], 1e-3)
+                assert_close("W", to_host_f64(weights[i]), W[i], 1e-3)
+        assert hits >= 2
+        st.close()
+
+
+def test_zero_gradient_and_zero_channels():
+    shapes = [(64, 128), (128, 64)]
+    wl = WL.Workload("zeros", 10, shapes, torch.bfloat16, "colscale", 1.0, rank=4, refresh_interval=100,
+                     steps=3, lr=1e-2, extra={"along": "channel"})
+    run_parity(wl, [0, 1], wl.steps)
+    # an all-zero gradient: no NaN, W unchanged, stored norm 0
+    cfg, _ = make_configs(wl)
+    weights = WL.make_weights(wl, DEV)
+    w0 = [w.clone() for w in weights]
+    grads = [torch.zeros(s, dtype=torch.bfloat16, device=DEV) for s in shapes]
+    st = A.ApolloStepper(cfg, weights, grads, device=DEV)
+    st.step(1, 0.01)
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert torch.equal(weights[i], w0[i])
+        assert float(st.debug(i, A.APOLLO_DBG_NORM)[0]) == 0.0
+        assert torch.all(st.debug(i, A.APOLLO_DBG_S) == 0)
+    st.close()
+
+
+def test_run_to_run_determinism_and_resume():
+    wl = WL.Workload("resume", 11, [(96, 200), (200, 96), (512, 512)], torch.bfloat16, "normal", 1e-2, rank=16,
+                     refresh_interval=4, steps=10, lr=1e-2)
+    cfg, _ = make_configs(wl)
+
+    def run(split):
+        weights = WL.make_weights(wl, DEV)
+        grads = [torch.empty(s, dtype=wl.grad_dtype, device=DEV) for s in wl.shapes]
+        st = A.ApolloStepper(cfg, weights, grads, device=DEV)
+        for t in range(1, wl.steps + 1):
+            if t == split:                      # checkpoint: state buffer out, new handle, state back in
+                saved = st.state.clone()
+                st.close()
+                st = A.ApolloStepper(cfg, weights, grads, device=DEV, zero_state=False)
+                st.state.copy_(saved)
+            WL.make_grads(wl, t, DEV, out=grads)
+            st.step(t, wl.lr)
+        torch.cuda.synchronize()
+        out = [w.clone() for w in weights] + [st.state.clone()]
+        st.close()
+        return out
+
+    a, b, c = run(None), run(None), run(6)
+    for x, y, z in zip(a, b, c):
+        assert torch.equal(x, y)                # same inputs twice: bit-identical (no atomics)
+        assert torch.equal(x, z)                # 10 steps == 5 + save/restore + 5
