@@ -1,0 +1,201 @@
+"""Benchmark of the APOLLO / APOLLO-Mini optimizer step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b_mini] [--also llama7b_r256]
+
+A "step" is one pass of the whole hot path (projection scratch fill, projection, low-rank Adam +
+factors, limiter, weight update) over every matrix of a synthetic LLaMA-shaped parameter set
+whose weights, gradients and optimizer state are already resident in HBM.  Prints ONE JSON line:
+value = parameters updated per second over exactly K timed steps; "roofline" describes the
+kernel phase that takes the most time (algorithmic bytes or flops per step divided by that
+phase's HIP-event time, against the MI355X peak); "cpu_baseline" is the fp64 oracle timed on
+the host cores on a bounded sample of the same workload; "also" carries the same measurement
+for the second variant the benchmark definition asks for on the same shapes.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores, published
+PHASES = ["projection_fill", "projection", "adam_norms", "limiter", "update"]
+KERNEL_OF_PHASE = {"projection_fill": "fill_projection_kernel", "projection": "project_*_kernel",
+                   "adam_norms": "adam_norms_kernel", "limiter": "finalize_kernel", "update": "update_tiled_kernel"}
+
+
+def make_cfg(A, wl, seed=20241205):
+    mode = A.APOLLO_TENSOR if wl.mode == "tensor" else A.APOLLO_CHANNEL
+    return A.ApolloConfig(rank=wl.rank, mode=mode, seed=seed, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
+                          scale=wl.scale, weight_decay=wl.weight_decay, nl_gamma=wl.nl_gamma,
+                          refresh_interval=wl.refresh_interval, bias_correction=1, side=A.APOLLO_SIDE_AUTO, reserved=0)
+
+
+def algorithmic_work(wl):
+    """Per step and per phase: bytes the method itself has to move (and matrix-core flops)."""
+    import torch
+    gb = 2 if wl.grad_dtype == torch.bfloat16 else 4
+    params = wl.n_params
+    chan = sum(max(s) for s in wl.shapes)                 # sum of channel counts n
+    return {
+        "projection": {"bytes": gb * params, "flops": 2.0 * wl.rank * params},
+        "adam_norms": {"bytes": 16.0 * wl.rank * chan, "flops": 0.0},
+        "update": {"bytes": (gb + 8.0) * params, "flops": 0.0},
+        "total_bytes": (2 * gb + 8.0) * params + 16.0 * wl.rank * chan,
+    }
+
+
+def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev):
+    cfg = make_cfg(A, wl)
+    st = A.ApolloStepper(cfg, weights, grads, device=dev)
+    for t in range(1, warmup + 1):
+        st.step(t, wl.lr)
+    torch.cuda.synchronize()
+    A.apollo_profile_enable(st.handle, True)
+    t0 = time.perf_counter()
+    for t in range(warmup + 1, warmup + steps + 1):
+        st.step(t, wl.lr)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    rc, ms, n = A.apollo_profile_read(st.handle)
+    assert rc == 0 and n == steps, (rc, n)
+    A.apollo_profile_enable(st.handle, False)
+    finite = all(bool(torch.isfinite(w).all()) for w in weights[:7])
+    state_bytes, ws_bytes = st.state.numel(), st.workspace.numel()
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    sec = (t1 - t0) / steps
+    phase_ms = {p: ms[i] / steps for i, p in enumerate(PHASES)}
+    work = algorithmic_work(wl)
+    dom = max(("projection", "adam_norms", "update"), key=lambda p: phase_ms[p])
+    w = work[dom]
+    t_dom = phase_ms[dom] * 1e-3
+    hbm_frac = w["bytes"] / t_dom / 1e9 / HBM_PEAK_GBS
+    mfma_frac = w["flops"] / t_dom / 1e12 / MFMA_BF16_PEAK_TFLOPS
+    if dom == "projection" and mfma_frac > hbm_frac:
+        roof = {"bound": "mfma", "achieved": w["flops"] / t_dom / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": mfma_frac, "traffic": None}
+    else:
+        roof = {"bound": "hbm", "achieved": w["bytes"] / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": hbm_frac, "traffic": None}
+    roof["kernel"] = KERNEL_OF_PHASE[dom]
+    roof["phase"] = dom
+    roof["ms_per_step"] = phase_ms[dom]
+    roof["launches_per_step"] = len(set(wl.shapes))
+    res = {
+        "value": wl.n_params / sec, "ms_per_step": sec * 1e3, "phase_ms": phase_ms, "roofline": roof,
+        "whole_step_hbm_frac": work["total_bytes"] / sec / 1e9 / HBM_PEAK_GBS,
+        "projection_tflops": work["projection"]["flops"] / (phase_ms["projection"] * 1e-3) / 1e12,
+        "finite": finite, "state_gb": state_bytes / 1e9, "workspace_gb": ws_bytes / 1e9,
+    }
+    return res
+
+
+def cpu_baseline(A, WL, torch, wl, weights, grads, budget_s=20.0):
+    """The oracle as it stands, timed on the host: one tensor of each distinct shape of the first
+    layer, as many steps as fit the budget (at least one)."""
+    import numpy as np
+    from oracle import apollo as O
+    f32 = lambda v: float(np.float32(v))
+    ocfg = O.Config(rank=wl.rank, mode=wl.mode, seed=20241205, beta1=f32(wl.beta1), beta2=f32(wl.beta2),
+                    eps=f32(wl.eps), scale=f32(wl.scale), nl_gamma=f32(wl.nl_gamma),
+                    refresh_interval=wl.refresh_interval)
+    ids, seen = [], set()
+    for i, s in enumerate(wl.shapes[:7]):
+        if s not in seen:
+            seen.add(s)
+            ids.append(i)
+    Ws = [weights[i].cpu().double().numpy() for i in ids]
+    Gs = [grads[i].cpu().float().double().numpy() for i in ids]
+    sts = [O.init_state(ocfg, *wl.shapes[i]) for i in ids]
+    bf16 = wl.grad_dtype == torch.bfloat16
+    params = 0
+    t0 = time.perf_counter()
+    step = 0
+    while True:
+        step += 1
+        for k, i in enumerate(ids):
+            O.step(ocfg, sts[k], Ws[k], Gs[k], step, f32(wl.lr), tensor_id=i, grad_is_bf16=bf16)
+            params += Ws[k].size
+        el = time.perf_counter() - t0
+        if el > budget_s or step >= 8 or el * (step + 1) / step > 1.5 * budget_s:
+            break
+    el = time.perf_counter() - t0
+    try:
+        import threadpoolctl
+        threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    return {"value": params / el, "unit": "params/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d step(s) on %d tensors (one per distinct shape of layer 0: %s), %.1f s, "
+                      "projection generation included" % (step, len(ids), [wl.shapes[i] for i in ids], el)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama7b_mini")
+    ap.add_argument("--also", default="llama7b_r256", help="second variant on the same shapes ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the optimizer step needs no communication under data "
+              "parallelism (every rank repeats it), so --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2412_05270_amd as A
+    from paper_2412_05270_amd import workloads as WL
+    if not os.path.exists(A.library_path()):
+        from paper_2412_05270_amd import build as _b
+        _b.build(verbose=False)
+    A.load_library()
+    dev = "cuda:0"
+    wl = WL.workload(args.workload)
+    weights = WL.make_weights(wl, dev)
+    grads = WL.make_grads(wl, 1, dev)
+    torch.cuda.synchronize()
+    main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev)
+    also = None
+    if args.also:
+        wl2 = WL.workload(args.also)
+        assert wl2.shapes == wl.shapes and wl2.grad_dtype == wl.grad_dtype
+        r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev)
+        also = {"workload": describe(wl2), "value": r2["value"], "unit": "params/s", "ms_per_step": r2["ms_per_step"],
+                "phase_ms": r2["phase_ms"], "roofline": r2["roofline"],
+                "whole_step_hbm_frac": r2["whole_step_hbm_frac"], "projection_tflops": r2["projection_tflops"],
+                "finite": r2["finite"]}
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(A, WL, torch, wl, weights, grads)
+    out = {
+        "metric": "APOLLO step params/s + % of HBM/MFMA roofline, LLaMA-7B-shaped params",
+        "value": main_res["value"], "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": describe(wl), "params": wl.n_params, "tensors": len(wl.shapes),
+                   "grad_dtype": str(wl.grad_dtype).replace("torch.", ""), "state_gb": main_res["state_gb"],
+                   "workspace_gb": main_res["workspace_gb"]},
+        "roofline": main_res["roofline"], "cpu_baseline": cpu, "phase_ms": main_res["phase_ms"],
+        "whole_step_hbm_frac": main_res["whole_step_hbm_frac"], "finite": main_res["finite"], "also": also,
+    }
+    print(json.dumps(out))
+
+
+def describe(wl):
+    return ("%s: %d matrices (%s), %s gradients ~ %s(%g), fp32 W/M/V, %s rank %d, alpha %.4g, T %d"
+            % (wl.name, len(wl.shapes), ", ".join("%dx%d" % s for s in sorted(set(wl.shapes))),
+               str(wl.grad_dtype).replace("torch.", ""), wl.grad_kind, wl.grad_scale,
+               "APOLLO-Mini tensor-wise" if wl.mode == "tensor" else "APOLLO channel-wise", wl.rank, wl.scale,
+               wl.refresh_interval))
+
+
+if __name__ == "__main__":
+    main()
