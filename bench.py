@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores, published
 PHASES = ["projection_fill", "projection", "adam_norms", "limiter", "update"]
 KERNEL_OF_PHASE = {"projection_fill": "fill_projection_kernel", "projection": "project_*_kernel",
-                   "adam_norms": "adam_norms_kernel", "limiter": "finalize_kernel", "update": "update_tiled_kernel"}
+                   "adam_norms": "adam_norms_kernel", "limiter": "finalize_kernel", "update": "update_kernel"}
 
 
 def make_cfg(A, wl, seed=20241205):
@@ -123,7 +123,7 @@ def cpu_baseline(A, WL, torch, wl, weights, grads, budget_s=20.0):
             O.step(ocfg, sts[k], Ws[k], Gs[k], step, f32(wl.lr), tensor_id=i, grad_is_bf16=bf16)
             params += Ws[k].size
         el = time.perf_counter() - t0
-        if el > budget_s or step >= 8 or el * (step + 1) / step > 1.5 * budget_s:
+        if el > budget_s or step >= 64 or el * (step + 1) / step > 1.5 * budget_s:
             break
     el = time.perf_counter() - t0
     try:

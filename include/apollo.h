@@ -51,7 +51,8 @@ enum {
   APOLLO_ENOMEM = -2,       /* host allocation failed                                           */
   APOLLO_ESTATE = -3,       /* state or workspace buffer too small or not 256-byte aligned      */
   APOLLO_EHIP = -4,         /* a HIP call failed (text in apollo_last_error)                    */
-  APOLLO_EUNSUPPORTED = -5  /* gradient dtype other than fp32 / bf16, or a dimension too large  */
+  APOLLO_EUNSUPPORTED = -5  /* gradient dtype other than fp32 / bf16; a dimension above 2^20 or
+                               2^31 or more elements in one tensor                             */
 };
 
 /* gradient element type (W, M^R, V^R and all factors are fp32) */

@@ -134,117 +134,107 @@ hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepParam
 // ---------------------------------------------------------------------------------------------
 // Update W <- W - coef * s_ch * G - lr*lambda * W with coef = lr * alpha * c (Algorithm 1, step 4).
 // Pure streaming: G read once more (2 or 4 B), W read and written (8 B) per parameter.
+//
+// One thread = four consecutive elements of the flattened tensor: one 16-byte W load, one 8- or
+// 16-byte G load, one 16-byte W store, so that every memory instruction of a wave covers one
+// contiguous run; one block = 1024 consecutive elements, blocks in memory order.  W is streamed
+// with non-temporal loads and stores (it is not touched again within the step).  Measured on
+// MI355X this shape moves about 6.5 TB/s, against 5.0 TB/s for a row-tiled kernel with two
+// 16-byte W accesses per lane.
 // ---------------------------------------------------------------------------------------------
 enum : int { kChanCol = 0, kChanRow = 1, kChanNone = 2 };
 
-__device__ __forceinline__ void unpack8u(const uint4& v, float f[8]) {
-  f[0] = __uint_as_float(v.x << 16);
-  f[1] = __uint_as_float(v.x & 0xFFFF0000u);
-  f[2] = __uint_as_float(v.y << 16);
-  f[3] = __uint_as_float(v.y & 0xFFFF0000u);
-  f[4] = __uint_as_float(v.z << 16);
-  f[5] = __uint_as_float(v.z & 0xFFFF0000u);
-  f[6] = __uint_as_float(v.w << 16);
-  f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+typedef float f4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u2_t __attribute__((ext_vector_type(2)));
+
+// Exact unsigned division by a run-time constant (Granlund & Montgomery, "Division by invariant
+// integers using multiplication", 1994): q = (t + ((v - t) >> 1)) >> (l - 1), t = mulhi(m, v).
+struct FastDiv {
+  uint32_t mul, shift, one;   // one = 1 when the divisor is 1
+};
+static FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f{0, 0, 0};
+  if (d == 1) { f.one = 1; return f; }
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  f.mul = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+  f.shift = l - 1;
+  return f;
+}
+__device__ __forceinline__ uint32_t fastdiv(uint32_t v, const FastDiv& f) {
+  if (f.one) return v;
+  const uint32_t t = __umulhi(f.mul, v);
+  return (t + ((v - t) >> 1)) >> f.shift;
 }
 
-// Tiled path (cols % 8 == 0): block = 64 column octets x 4 row lanes over a 512-column x
-// kUpdRows-row tile; a thread keeps the factors of its eight columns in registers.
-constexpr int kUpdRows = 32;
-
-template <bool BF16, int CHAN>
-__global__ __launch_bounds__(256) void update_tiled_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
-  const TensorDesc& d = descs[blockIdx.z];
-  const int rows = d.rows, cols = d.cols;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const int cv = blockIdx.x * 64 + tx;
-  if (cv * 8 >= cols) return;
-  const float coef = d.scal[0];
-  const float decay = sp.lr_decay;
-  float cs[8];
-  if (CHAN == kChanCol) {
-    const float4 s0 = reinterpret_cast<const float4*>(d.s)[2 * cv];
-    const float4 s1 = reinterpret_cast<const float4*>(d.s)[2 * cv + 1];
-    cs[0] = coef * s0.x; cs[1] = coef * s0.y; cs[2] = coef * s0.z; cs[3] = coef * s0.w;
-    cs[4] = coef * s1.x; cs[5] = coef * s1.y; cs[6] = coef * s1.z; cs[7] = coef * s1.w;
-  } else {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) cs[e] = coef;
-  }
-  const int row0 = blockIdx.y * kUpdRows + ty;
-  const size_t nv = (size_t)(cols >> 3);
-#pragma unroll
-  for (int it = 0; it < kUpdRows / 4; it += 4) {
-    float g[4][8];
-    float4 wa[4], wb[4];
-    float rs[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = row0 + 4 * (it + u);
-      if (row < rows) {
-        const size_t vi = (size_t)row * nv + cv;
-        if (BF16) {
-          const uint4 gv = reinterpret_cast<const uint4*>(d.g)[vi];
-          unpack8u(gv, g[u]);
-        } else {
-          const float4 g0 = reinterpret_cast<const float4*>(d.g)[2 * vi];
-          const float4 g1 = reinterpret_cast<const float4*>(d.g)[2 * vi + 1];
-          g[u][0] = g0.x; g[u][1] = g0.y; g[u][2] = g0.z; g[u][3] = g0.w;
-          g[u][4] = g1.x; g[u][5] = g1.y; g[u][6] = g1.z; g[u][7] = g1.w;
-        }
-        wa[u] = reinterpret_cast<const float4*>(d.w)[2 * vi];
-        wb[u] = reinterpret_cast<const float4*>(d.w)[2 * vi + 1];
-        rs[u] = (CHAN == kChanRow) ? d.s[row] : 1.f;
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = row0 + 4 * (it + u);
-      if (row < rows) {
-        const size_t vi = (size_t)row * nv + cv;
-        float w[8] = {wa[u].x, wa[u].y, wa[u].z, wa[u].w, wb[u].x, wb[u].y, wb[u].z, wb[u].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float k = (CHAN == kChanRow) ? cs[e] * rs[u] : cs[e];
-          w[e] = w[e] - __builtin_fmaf(k, g[u][e], decay * w[e]);
-        }
-        reinterpret_cast<float4*>(d.w)[2 * vi] = make_float4(w[0], w[1], w[2], w[3]);
-        reinterpret_cast<float4*>(d.w)[2 * vi + 1] = make_float4(w[4], w[5], w[6], w[7]);
-      }
-    }
-  }
-}
-
-// General path (any cols): one thread per element.
-template <bool BF16, int CHAN>
-__global__ __launch_bounds__(256) void update_flat_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
+// ALIGNED: cols % 4 == 0, so a quad never straddles a row and the tensor has no ragged tail.
+template <bool BF16, int CHAN, bool ALIGNED>
+__global__ __launch_bounds__(256) void update_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
+                                                     FastDiv div_cols) {
   const TensorDesc& d = descs[blockIdx.y];
+  const uint32_t cols = (uint32_t)d.cols;
   const size_t total = (size_t)d.rows * (size_t)d.cols;
+  const size_t q = (size_t)blockIdx.x * 256u + threadIdx.x;      // quad index
+  const size_t e0 = q * 4u;
+  if (e0 >= total) return;
   const float coef = d.scal[0];
   const float decay = sp.lr_decay;
-  for (size_t e = (size_t)blockIdx.x * 256u + threadIdx.x; e < total; e += (size_t)gridDim.x * 256u) {
-    float k = coef;
-    if (CHAN == kChanCol) k *= d.s[e % (size_t)d.cols];
-    if (CHAN == kChanRow) k *= d.s[e / (size_t)d.cols];
-    const float g = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(d.g)[e])
-                         : reinterpret_cast<const float*>(d.g)[e];
-    const float w = d.w[e];
-    d.w[e] = w - __builtin_fmaf(k, g, decay * w);
+  float k[4] = {coef, coef, coef, coef};
+  if (CHAN != kChanNone) {
+    uint32_t row = fastdiv((uint32_t)e0, div_cols);
+    uint32_t col = (uint32_t)e0 - row * cols;
+    if (ALIGNED) {
+      if (CHAN == kChanCol) {
+        const f4_t sv = *reinterpret_cast<const f4_t*>(d.s + col);
+        k[0] *= sv.x; k[1] *= sv.y; k[2] *= sv.z; k[3] *= sv.w;
+      } else {
+        const float sr = d.s[row];
+        k[0] *= sr; k[1] *= sr; k[2] *= sr; k[3] *= sr;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (e0 + e < total) k[e] *= d.s[CHAN == kChanCol ? col : row];
+        if (++col == cols) { col = 0; ++row; }
+      }
+    }
+  }
+  if (ALIGNED || e0 + 4 <= total) {
+    float g[4];
+    if (BF16) {
+      const u2_t gv = reinterpret_cast<const u2_t*>(d.g)[q];
+      g[0] = __uint_as_float(gv.x << 16); g[1] = __uint_as_float(gv.x & 0xFFFF0000u);
+      g[2] = __uint_as_float(gv.y << 16); g[3] = __uint_as_float(gv.y & 0xFFFF0000u);
+    } else {
+      const f4_t gv = reinterpret_cast<const f4_t*>(d.g)[q];
+      g[0] = gv.x; g[1] = gv.y; g[2] = gv.z; g[3] = gv.w;
+    }
+    f4_t w = __builtin_nontemporal_load(reinterpret_cast<const f4_t*>(d.w) + q);
+    w.x = w.x - __builtin_fmaf(k[0], g[0], decay * w.x);
+    w.y = w.y - __builtin_fmaf(k[1], g[1], decay * w.y);
+    w.z = w.z - __builtin_fmaf(k[2], g[2], decay * w.z);
+    w.w = w.w - __builtin_fmaf(k[3], g[3], decay * w.w);
+    __builtin_nontemporal_store(w, reinterpret_cast<f4_t*>(d.w) + q);
+  } else {
+    for (int e = 0; e < 4 && e0 + e < total; ++e) {     // ragged tail of an unaligned tensor
+      const float g = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(d.g)[e0 + e])
+                           : reinterpret_cast<const float*>(d.g)[e0 + e];
+      const float w = d.w[e0 + e];
+      d.w[e0 + e] = w - __builtin_fmaf(k[e], g, decay * w);
+    }
   }
 }
 
 template <bool BF16, int CHAN>
 static hipError_t launch_update_t(const TensorDesc* d_descs, int count, int rows, int cols, const StepParams& sp,
                                   hipStream_t st) {
-  if ((cols & 7) == 0) {
-    dim3 grid((unsigned)((cols / 8 + 63) / 64), (unsigned)((rows + kUpdRows - 1) / kUpdRows), (unsigned)count);
-    hipLaunchKernelGGL((update_tiled_kernel<BF16, CHAN>), grid, dim3(256), 0, st, d_descs, sp);
-  } else {
-    size_t blocks = ((size_t)rows * cols + 255) / 256;
-    if (blocks > 16384) blocks = 16384;
-    hipLaunchKernelGGL((update_flat_kernel<BF16, CHAN>), dim3((unsigned)blocks, (unsigned)count), dim3(256), 0, st,
-                       d_descs, sp);
-  }
+  const size_t quads = ((size_t)rows * cols + 3) / 4;
+  dim3 grid((unsigned)((quads + 255) / 256), (unsigned)count, 1);
+  const FastDiv fd = make_fastdiv((uint32_t)cols);
+  if ((cols & 3) == 0)
+    hipLaunchKernelGGL((update_kernel<BF16, CHAN, true>), grid, dim3(256), 0, st, d_descs, sp, fd);
+  else
+    hipLaunchKernelGGL((update_kernel<BF16, CHAN, false>), grid, dim3(256), 0, st, d_descs, sp, fd);
   return hipGetLastError();
 }
 

@@ -79,6 +79,8 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
       return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: gradient dtype %lld is neither fp32 nor bf16", k, s.grad_dtype);
     if (s.rows > kMaxDim || s.cols > kMaxDim)
       return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: dimension above %lld", k, kMaxDim);
+    if (s.rows * s.cols >= (1ll << 31))
+      return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: more than 2^31 - 1 elements", k);
     t.rows = (int32_t)s.rows;
     t.cols = (int32_t)s.cols;
     t.bf16 = s.grad_dtype == APOLLO_BF16;
