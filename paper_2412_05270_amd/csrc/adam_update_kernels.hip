@@ -15,7 +15,7 @@ namespace apollo {
 __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
   __shared__ float red_a[3][64], red_b[3][64];
   __shared__ float blk[4][64];
-  const TensorDesc& d = descs[blockIdx.y];
+  const TensorView d(descs[blockIdx.y]);
   const int r = sp.r, n = d.n, n_slabs = d.n_slabs;
   const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + c;
@@ -88,11 +88,11 @@ hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, const 
 // rescaled to norm gamma N_prev, which is also what is remembered.  One wave per tensor.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void finalize_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
-  const TensorDesc& d = descs[blockIdx.x];
+  const TensorView d(descs[blockIdx.x]);
   const int lane = threadIdx.x;
   float t[4] = {0.f, 0.f, 0.f, 0.f};
   for (int b = lane; b < d.k2_blocks; b += 64) {
-    const float4 p = reinterpret_cast<const float4*>(d.partials)[b];
+    const f32x4_t p = reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(d.partials)[b];
     t[0] += p.x;
     t[1] += p.y;
     t[2] += p.z;
@@ -144,8 +144,6 @@ hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepParam
 // ---------------------------------------------------------------------------------------------
 enum : int { kChanCol = 0, kChanRow = 1, kChanNone = 2 };
 
-typedef float f4_t __attribute__((ext_vector_type(4)));
-typedef unsigned u2_t __attribute__((ext_vector_type(2)));
 
 // Exact unsigned division by a run-time constant (Granlund & Montgomery, "Division by invariant
 // integers using multiplication", 1994): q = (t + ((v - t) >> 1)) >> (l - 1), t = mulhi(m, v).
@@ -171,7 +169,7 @@ __device__ __forceinline__ uint32_t fastdiv(uint32_t v, const FastDiv& f) {
 template <bool BF16, int CHAN, bool ALIGNED>
 __global__ __launch_bounds__(256) void update_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
                                                      FastDiv div_cols) {
-  const TensorDesc& d = descs[blockIdx.y];
+  const TensorView d(descs[blockIdx.y]);
   const uint32_t cols = (uint32_t)d.cols;
   const size_t total = (size_t)d.rows * (size_t)d.cols;
   const size_t q = (size_t)blockIdx.x * 256u + threadIdx.x;      // quad index
@@ -185,7 +183,7 @@ __global__ __launch_bounds__(256) void update_kernel(const TensorDesc* __restric
     uint32_t col = (uint32_t)e0 - row * cols;
     if (ALIGNED) {
       if (CHAN == kChanCol) {
-        const f4_t sv = *reinterpret_cast<const f4_t*>(d.s + col);
+        const f32x4_t sv = *reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(d.s + col);
         k[0] *= sv.x; k[1] *= sv.y; k[2] *= sv.z; k[3] *= sv.w;
       } else {
         const float sr = d.s[row];
@@ -202,23 +200,23 @@ __global__ __launch_bounds__(256) void update_kernel(const TensorDesc* __restric
   if (ALIGNED || e0 + 4 <= total) {
     float g[4];
     if (BF16) {
-      const u2_t gv = reinterpret_cast<const u2_t*>(d.g)[q];
+      const u32x2_t gv = reinterpret_cast<const APOLLO_GLOBAL u32x2_t*>(d.g)[q];
       g[0] = __uint_as_float(gv.x << 16); g[1] = __uint_as_float(gv.x & 0xFFFF0000u);
       g[2] = __uint_as_float(gv.y << 16); g[3] = __uint_as_float(gv.y & 0xFFFF0000u);
     } else {
-      const f4_t gv = reinterpret_cast<const f4_t*>(d.g)[q];
+      const f32x4_t gv = reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(d.g)[q];
       g[0] = gv.x; g[1] = gv.y; g[2] = gv.z; g[3] = gv.w;
     }
-    f4_t w = __builtin_nontemporal_load(reinterpret_cast<const f4_t*>(d.w) + q);
+    f32x4_t w = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(d.w) + q);
     w.x = w.x - __builtin_fmaf(k[0], g[0], decay * w.x);
     w.y = w.y - __builtin_fmaf(k[1], g[1], decay * w.y);
     w.z = w.z - __builtin_fmaf(k[2], g[2], decay * w.z);
     w.w = w.w - __builtin_fmaf(k[3], g[3], decay * w.w);
-    __builtin_nontemporal_store(w, reinterpret_cast<f4_t*>(d.w) + q);
+    __builtin_nontemporal_store(w, reinterpret_cast<APOLLO_GLOBAL f32x4_t*>(d.w) + q);
   } else {
     for (int e = 0; e < 4 && e0 + e < total; ++e) {     // ragged tail of an unaligned tensor
-      const float g = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(d.g)[e0 + e])
-                           : reinterpret_cast<const float*>(d.g)[e0 + e];
+      const float g = BF16 ? bf16_bits_to_f32(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(d.g)[e0 + e])
+                           : reinterpret_cast<const APOLLO_GLOBAL float*>(d.g)[e0 + e];
       const float w = d.w[e0 + e];
       d.w[e0 + e] = w - __builtin_fmaf(k[e], g, decay * w);
     }

@@ -46,6 +46,48 @@ struct StepParams {
   float lr, lr_decay;  // lr, lr * lambda
 };
 
+// Pointers read from a TensorDesc are generic to the compiler; every buffer they name is device
+// global memory.  Saying so turns flat_load / flat_store into global_load / global_store, which
+// do not tie up the LDS counter (a flat access makes every later LDS wait also wait for it).
+#define APOLLO_GLOBAL __attribute__((address_space(1)))
+// Clang vector types (usable in any address space, unlike the HIP uint4 / float4 classes).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__host__ __device__ __forceinline__ u32x4_t mk_u4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  u32x4_t v = {a, b, c, d};
+  return v;
+}
+__host__ __device__ __forceinline__ f32x4_t mk_f4(float a, float b, float c, float d) {
+  f32x4_t v = {a, b, c, d};
+  return v;
+}
+template <class T>
+__device__ __forceinline__ APOLLO_GLOBAL T* gptr(T* p) {
+  return (APOLLO_GLOBAL T*)p;
+}
+
+// A TensorDesc with its pointers typed as global memory; kernels build one from the table entry.
+struct TensorView {
+  APOLLO_GLOBAL float* w;
+  APOLLO_GLOBAL const void* g;
+  APOLLO_GLOBAL float* M;
+  APOLLO_GLOBAL float* V;
+  APOLLO_GLOBAL float* prev_norm;
+  APOLLO_GLOBAL void* P;
+  APOLLO_GLOBAL float* R;
+  APOLLO_GLOBAL float* colsq;
+  APOLLO_GLOBAL float* s;
+  APOLLO_GLOBAL float* partials;
+  APOLLO_GLOBAL float* scal;
+  int32_t rows, cols, m, n, m8, left, tensor_id, n_slabs, k2_blocks;
+  __device__ __forceinline__ explicit TensorView(const TensorDesc& d)
+      : w(gptr(d.w)), g(gptr(d.g)), M(gptr(d.M)), V(gptr(d.V)), prev_norm(gptr(d.prev_norm)), P(gptr(d.P)),
+        R(gptr(d.R)), colsq(gptr(d.colsq)), s(gptr(d.s)), partials(gptr(d.partials)), scal(gptr(d.scal)),
+        rows(d.rows), cols(d.cols), m(d.m), n(d.n), m8(d.m8), left(d.left), tensor_id(d.tensor_id),
+        n_slabs(d.n_slabs), k2_blocks(d.k2_blocks) {}
+};
+
 // Element (kk, i) of the scratch projection: eight consecutive i of one row are contiguous, the
 // r rows of such an octet follow each other, octets follow along i.  A matrix-core A fragment
 // (32 or 16 rows x 8 i per lane) is then one contiguous, coalesced 16-byte load per lane.

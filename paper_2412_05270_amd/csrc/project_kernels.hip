@@ -6,9 +6,9 @@
 
 namespace apollo {
 
-__device__ __forceinline__ float load_g(const void* g, size_t idx, bool bf16) {
-  if (bf16) return bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(g)[idx]);
-  return reinterpret_cast<const float*>(g)[idx];
+__device__ __forceinline__ float load_g(const APOLLO_GLOBAL void* g, size_t idx, bool bf16) {
+  if (bf16) return bf16_bits_to_f32(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(g)[idx]);
+  return reinterpret_cast<const APOLLO_GLOBAL float*>(g)[idx];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -20,7 +20,7 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void project_generic_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
   __shared__ float Gs[32][65];
   __shared__ float Ps[32][33];
-  const TensorDesc& d = descs[blockIdx.z];
+  const TensorView d(descs[blockIdx.z]);
   const int r = sp.r, m = d.m, n = d.n, cols = d.cols;
   const int tid = threadIdx.x;
   const int j0 = blockIdx.x * 64, kk0 = blockIdx.y * 32;
@@ -54,8 +54,8 @@ __global__ __launch_bounds__(256) void project_generic_kernel(const TensorDesc* 
       float v = 0.f;
       if (k < r && i < d.m8) {
         const size_t idx = p_index(k, i, r);
-        v = BF16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(d.P)[idx])
-                 : reinterpret_cast<const float*>(d.P)[idx];
+        v = BF16 ? bf16_bits_to_f32(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(d.P)[idx])
+                 : reinterpret_cast<const APOLLO_GLOBAL float*>(d.P)[idx];
       }
       Ps[kk][ii] = v;
     }
@@ -105,7 +105,7 @@ hipError_t launch_project_generic(const TensorDesc* d_descs, int count, int n, b
 // ---------------------------------------------------------------------------------------------
 
 // unpack eight bf16 (one 16-byte load) to floats
-__device__ __forceinline__ void unpack8(const uint4& v, float f[8]) {
+__device__ __forceinline__ void unpack8(const u32x4_t& v, float f[8]) {
   f[0] = __uint_as_float(v.x << 16);
   f[1] = __uint_as_float(v.x & 0xFFFF0000u);
   f[2] = __uint_as_float(v.y << 16);
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
                                                                  int slab_rows) {
   __shared__ float zs[kMiniSlabRowsMax];
   __shared__ float red[2][3][64][9];
-  const TensorDesc& d = descs[blockIdx.z];
+  const TensorView d(descs[blockIdx.z]);
   const int rows = d.rows, cols = d.cols;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int i0 = blockIdx.y * slab_rows;
@@ -158,11 +158,11 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = sq[e] = 0.f;
   if (active) {
-    const uint4* gp = reinterpret_cast<const uint4*>(d.g) + (size_t)cv;
+    const APOLLO_GLOBAL u32x4_t* gp = reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(d.g) + (size_t)cv;
     const size_t stride = (size_t)(cols >> 3);
     int i = i0 + ty;
     for (; i + 12 < i1; i += 16) {
-      uint4 v[4];
+      u32x4_t v[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) v[u] = gp[(size_t)(i + 4 * u) * stride];
 #pragma unroll
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
       }
     }
     for (; i < i1; i += 4) {
-      const uint4 v = gp[(size_t)i * stride];
+      const u32x4_t v = gp[(size_t)i * stride];
       const float z = zs[i - i0];
       float f[8];
       unpack8(v, f);
@@ -198,8 +198,8 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
   }
   __syncthreads();
   if (ty == 0 && active) {
-    float* Rp = d.R + (size_t)blockIdx.y * d.n + (size_t)cv * 8;
-    float* Cp = d.colsq + (size_t)blockIdx.y * d.n + (size_t)cv * 8;
+    APOLLO_GLOBAL float* Rp = d.R + (size_t)blockIdx.y * d.n + (size_t)cv * 8;
+    APOLLO_GLOBAL float* Cp = d.colsq + (size_t)blockIdx.y * d.n + (size_t)cv * 8;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float a = ((acc[e] + red[0][0][tx][e]) + red[0][1][tx][e]) + red[0][2][tx][e];
@@ -225,26 +225,26 @@ __device__ __forceinline__ float wave_sum(float v) {
 __global__ __launch_bounds__(256) void project_rank1_right_kernel(const TensorDesc* __restrict__ descs,
                                                                   StepParams sp) {
   extern __shared__ float zs[];
-  const TensorDesc& d = descs[blockIdx.z];
+  const TensorView d(descs[blockIdx.z]);
   const int rows = d.rows, cols = d.cols;
   gen_z_to_lds(zs, 0, cols, cols, sp, (uint32_t)d.tensor_id, true);
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nv = cols >> 3;
-  const uint4* gbase = reinterpret_cast<const uint4*>(d.g);
+  const APOLLO_GLOBAL u32x4_t* gbase = reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(d.g);
   const int row_begin = blockIdx.x * kMiniRightRowsPerBlock + wave * (kMiniRightRowsPerBlock / 4);
   const int row_end = min(rows, row_begin + kMiniRightRowsPerBlock / 4);
   for (int i = row_begin; i < row_end; i += 4) {
     float acc[4] = {0.f, 0.f, 0.f, 0.f}, sq[4] = {0.f, 0.f, 0.f, 0.f};
     for (int v0 = lane; v0 < nv; v0 += 64) {
-      uint4 v[4];
+      u32x4_t v[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int ii = min(i + u, rows - 1);
         v[u] = gbase[(size_t)ii * nv + v0];
       }
-      const float4 za = reinterpret_cast<const float4*>(zs)[2 * v0];
-      const float4 zb = reinterpret_cast<const float4*>(zs)[2 * v0 + 1];
+      const f32x4_t za = reinterpret_cast<const f32x4_t*>(zs)[2 * v0];
+      const f32x4_t zb = reinterpret_cast<const f32x4_t*>(zs)[2 * v0 + 1];
       const float z[8] = {za.x, za.y, za.z, za.w, zb.x, zb.y, zb.z, zb.w};
 #pragma unroll
       for (int u = 0; u < 4; ++u) {

@@ -38,7 +38,7 @@ struct MfmaCfg {
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-__device__ __forceinline__ void sq_accum8(const uint4& v, float sq[8]) {
+__device__ __forceinline__ void sq_accum8(const u32x4_t& v, float sq[8]) {
   float f;
   f = bf_lo(v.x); sq[0] = __builtin_fmaf(f, f, sq[0]);
   f = bf_hi(v.x); sq[1] = __builtin_fmaf(f, f, sq[1]);
@@ -54,15 +54,15 @@ template <int MT, int WM, bool LEFT>
 __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
   using C = MfmaCfg<MT, WM>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const TensorDesc& d = descs[blockIdx.z];
+  const TensorView d(descs[blockIdx.z]);
   const int r = sp.r, m = d.m, n = d.n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int n0 = blockIdx.x * kNT;
   const int rbase = blockIdx.y * C::RT;
   const bool do_sq = blockIdx.y == 0;
-  const uint4* __restrict__ Pg = reinterpret_cast<const uint4*>(d.P);     // one uint4 = (octet, row)
-  const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(d.g);
+  const APOLLO_GLOBAL u32x4_t* __restrict__ Pg = reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(d.P);     // one u32x4_t = (octet, row)
+  const APOLLO_GLOBAL uint16_t* __restrict__ G = reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(d.g);
 
   f32x16_t acc[MT][C::NTW];
 #pragma unroll
@@ -73,12 +73,12 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
   float sq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  uint4 areg[C::A_CHUNKS];
-  uint4 breg[8];
+  u32x4_t areg[C::A_CHUNKS];
+  u32x4_t breg[8];
   // loader coordinates
   const int br = tid >> 5, bc = tid & 31;           // LEFT: k-octet of the stage, channel octet
   const int ko_r = tid & 7, jl_r = tid >> 3;        // RIGHT: k-octet, channel (plus 32 u)
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  const u32x4_t zero4 = mk_u4(0, 0, 0, 0);
 
   auto load_stage = [&](int s) {
 #pragma unroll
@@ -92,13 +92,13 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int row = kKT * s + 8 * br + u;
-        breg[u] = (col < n) ? *reinterpret_cast<const uint4*>(G + (size_t)row * n + col) : zero4;
+        breg[u] = (col < n) ? *reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(G + (size_t)row * n + col) : zero4;
       }
     } else {
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int j = n0 + jl_r + 32 * u;
-        breg[u] = (j < n) ? *reinterpret_cast<const uint4*>(G + (size_t)j * m + kKT * s + 8 * ko_r) : zero4;
+        breg[u] = (j < n) ? *reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(G + (size_t)j * m + kKT * s + 8 * ko_r) : zero4;
       }
     }
   };
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
     unsigned char* A = lds + buf * C::STAGE_BYTES;
     unsigned char* B = A + C::A_BYTES;
 #pragma unroll
-    for (int u = 0; u < C::A_CHUNKS; ++u) *reinterpret_cast<uint4*>(A + (size_t)(tid + 256 * u) * 16) = areg[u];
+    for (int u = 0; u < C::A_CHUNKS; ++u) *reinterpret_cast<u32x4_t*>(A + (size_t)(tid + 256 * u) * 16) = areg[u];
     if (LEFT) {
       if (do_sq) {
 #pragma unroll
@@ -121,12 +121,12 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-        uint4 o;
+        u32x4_t o;
         o.x = __builtin_amdgcn_perm(in[1][c >> 1], in[0][c >> 1], sel);
         o.y = __builtin_amdgcn_perm(in[3][c >> 1], in[2][c >> 1], sel);
         o.z = __builtin_amdgcn_perm(in[5][c >> 1], in[4][c >> 1], sel);
         o.w = __builtin_amdgcn_perm(in[7][c >> 1], in[6][c >> 1], sel);
-        *reinterpret_cast<uint4*>(B + br * kBKO + (c * 32 + bc) * 16) = o;
+        *reinterpret_cast<u32x4_t*>(B + br * kBKO + (c * 32 + bc) * 16) = o;
       }
     } else {
 #pragma unroll
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
           sq_accum8(breg[u], t);
           sq[u] += ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
         }
-        *reinterpret_cast<uint4*>(B + ko_r * kBKO + (jl_r + 32 * u) * 16) = breg[u];
+        *reinterpret_cast<u32x4_t*>(B + ko_r * kBKO + (jl_r + 32 * u) * 16) = breg[u];
       }
     }
   };
@@ -156,11 +156,11 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
       bf16x8_t af[MT], bfr[C::NTW];
 #pragma unroll
       for (int a = 0; a < MT; ++a)
-        af[a] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(
+        af[a] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(
                                                  A + (size_t)(oct * C::RT + wm * 32 * MT + a * 32 + (lane & 31)) * 16));
 #pragma unroll
       for (int b = 0; b < C::NTW; ++b)
-        bfr[b] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(
+        bfr[b] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(
                                                   B + oct * kBKO + ((wn * C::NTW + b) * 32 + (lane & 31)) * 16));
 #pragma unroll
       for (int a = 0; a < MT; ++a)

@@ -11,7 +11,7 @@ namespace apollo {
 template <bool BF16>
 __global__ __launch_bounds__(256) void fill_projection_kernel(const TensorDesc* __restrict__ descs,
                                                               StepParams sp, int m8) {
-  const TensorDesc& d = descs[blockIdx.y];
+  const TensorView d(descs[blockIdx.y]);
   const int r = sp.r;
   const size_t total = (size_t)r * (size_t)(m8 >> 2);
   const size_t t = (size_t)blockIdx.x * 256u + threadIdx.x;
@@ -31,12 +31,12 @@ __global__ __launch_bounds__(256) void fill_projection_kernel(const TensorDesc* 
       if (4 * q + e >= m) z[e] = 0.f;
   }
   if (BF16) {
-    uint2 v;
+    u32x2_t v;
     v.x = f32_to_bf16_bits(z[0]) | (f32_to_bf16_bits(z[1]) << 16);
     v.y = f32_to_bf16_bits(z[2]) | (f32_to_bf16_bits(z[3]) << 16);
-    reinterpret_cast<uint2*>(d.P)[t] = v;
+    reinterpret_cast<APOLLO_GLOBAL u32x2_t*>(d.P)[t] = v;
   } else {
-    reinterpret_cast<float4*>(d.P)[t] = make_float4(z[0], z[1], z[2], z[3]);
+    reinterpret_cast<APOLLO_GLOBAL f32x4_t*>(d.P)[t] = mk_f4(z[0], z[1], z[2], z[3]);
   }
 }
 
@@ -128,8 +128,8 @@ hipError_t launch_gauss_parts(uint32_t first, int64_t count, float* radius, floa
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, size_t n16) {
-  const uint4 z = make_uint4(0, 0, 0, 0);
+__global__ __launch_bounds__(256) void fill_zero_kernel(u32x4_t* __restrict__ p, size_t n16) {
+  const u32x4_t z = mk_u4(0, 0, 0, 0);
   for (size_t i = (size_t)blockIdx.x * 256u + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256u) p[i] = z;
 }
 
@@ -139,7 +139,7 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
   if (n16 == 0) return hipSuccess;
   size_t blocks = (n16 + 255) / 256;
   if (blocks > 65536) blocks = 65536;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<uint4*>(p), n16);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, reinterpret_cast<u32x4_t*>(p), n16);
   return hipGetLastError();
 }
 
