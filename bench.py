@@ -144,6 +144,9 @@ def main():
     ap.add_argument("--workload", default="llama7b_mini")
     ap.add_argument("--also", default="llama7b_r256", help="second variant on the same shapes ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run the library's plain copy kernel on 4 GiB a few times (known traffic: "
+                         "4 GiB read + 4 GiB written per launch), for scaling rocprofv3 byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the optimizer step needs no communication under data "
@@ -158,6 +161,17 @@ def main():
         _b.build(verbose=False)
     A.load_library()
     dev = "cuda:0"
+    if args.copy_calibration:
+        nbytes = 4 << 30
+        src = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            assert A.apollo_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes,
+                                       torch.cuda.current_stream(dev).cuda_stream) == 0
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"kernel": "copy_kernel", "launches": 5, "bytes_read": nbytes,
+                                               "bytes_written": nbytes}}))
+        return
     wl = WL.workload(args.workload)
     weights = WL.make_weights(wl, dev)
     grads = WL.make_grads(wl, 1, dev)

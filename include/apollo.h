@@ -155,6 +155,11 @@ apollo_status_t apollo_debug_philox(const void* ctr, uint32_t key0, uint32_t key
 apollo_status_t apollo_debug_gauss_parts(uint32_t first, int64_t count, void* radius, void* cosv,
                                          void* sinv, void* hip_stream);
 
+/* Plain device-to-device copy of `bytes` (a multiple of 16; both pointers DEVICE, 16-byte
+ * aligned) by a one-thread-per-16-bytes kernel: a kernel of exactly known traffic, used to
+ * calibrate hardware byte counters when profiling. */
+apollo_status_t apollo_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
 /* Phase timing for benchmarks.  After apollo_profile_enable(h, 1) every apollo_step records
  * HIP events on its stream around its five phases: [0] P scratch fill, [1] projection R = P G,
  * [2] low-rank moments + factors, [3] limiter scalars, [4] weight update.  apollo_profile_read

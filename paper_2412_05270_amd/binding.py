@@ -77,6 +77,8 @@ def load_library():
     lib.apollo_debug_philox.argtypes = [vp, u32, u32, vp, i64, vp]
     lib.apollo_debug_gauss_parts.restype = i32
     lib.apollo_debug_gauss_parts.argtypes = [u32, i64, vp, vp, vp, vp]
+    lib.apollo_debug_copy.restype = i32
+    lib.apollo_debug_copy.argtypes = [vp, vp, sz, vp]
     lib.apollo_profile_enable.restype = i32
     lib.apollo_profile_enable.argtypes = [vp, i32]
     lib.apollo_profile_read.restype = i32
@@ -154,6 +156,10 @@ def apollo_debug_philox(ctr_ptr, key0, key1, out_ptr, count, stream=None):
 
 def apollo_debug_gauss_parts(first, count, radius_ptr, cos_ptr, sin_ptr, stream=None):
     return load_library().apollo_debug_gauss_parts(first, count, radius_ptr, cos_ptr, sin_ptr, stream)
+
+
+def apollo_debug_copy(dst_ptr, src_ptr, nbytes, stream=None):
+    return load_library().apollo_debug_copy(dst_ptr, src_ptr, nbytes, stream)
 
 
 def apollo_profile_enable(handle, on):

@@ -493,6 +493,14 @@ apollo_status_t apollo_debug_gauss_parts(uint32_t first, int64_t count, void* ra
   return APOLLO_OK;
 }
 
+apollo_status_t apollo_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!dst || !src || (bytes & 15) || (((uintptr_t)dst | (uintptr_t)src) & 15) || bytes >= (1ull << 40))
+    return fail(g_last_error, APOLLO_EINVAL, "bad arguments (16-byte aligned pointers, bytes a multiple of 16)");
+  const hipError_t e = launch_copy(dst, src, bytes, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(g_last_error, e, "copy (debug)");
+  return APOLLO_OK;
+}
+
 const char* apollo_last_error(const apollo_handle_t* h) { return h ? h->err.c_str() : g_last_error.c_str(); }
 
 void apollo_destroy(apollo_handle_t* h) {

@@ -118,5 +118,6 @@ hipError_t launch_philox_words(const uint32_t* ctr, uint32_t k0, uint32_t k1, ui
 hipError_t launch_gauss_parts(uint32_t first, int64_t count, float* radius, float* cosv, float* sinv,
                               hipStream_t st);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 
 }  // namespace apollo

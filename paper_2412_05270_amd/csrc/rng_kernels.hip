@@ -143,4 +143,20 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Plain copy of n16 16-byte words, one per thread (reference kernel of known traffic for
+// calibrating hardware byte counters).
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst,
+                                                   size_t n16) {
+  const size_t i = (size_t)blockIdx.x * 256u + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st,
+                     reinterpret_cast<const u32x4_t*>(src), reinterpret_cast<u32x4_t*>(dst), n16);
+  return hipGetLastError();
+}
+
 }  // namespace apollo
