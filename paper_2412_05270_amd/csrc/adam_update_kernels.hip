@@ -6,59 +6,80 @@
 namespace apollo {
 
 // ---------------------------------------------------------------------------------------------
-// Moments and norms.  Block = 64 channels x 4 rank lanes: thread (c, q) walks rows q, q+4, ...
-// of column j of R, M^R, V^R (coalesced along j), accumulating a_j = sum R~^2 and b_j = sum R^2
-// in registers; the four lanes are combined through LDS in a fixed order, then the 64 channels
-// of the block are reduced to four block partials.  No atomics: results are run-to-run
-// identical.
+// Moments and norms.  Block = 64 channel groups x 4 rank lanes; a channel group is VEC (4, or 1
+// when n is not a multiple of 4) consecutive channels, so a wave touches 1 KB contiguous per row
+// of R, M^R, V^R.  Thread (c, q) walks rows q, q+4, ... of its channels, accumulating
+// a_j = sum R~^2 and b_j = sum R^2 in registers; the four rank lanes are combined through LDS in
+// a fixed order, then the channels of the block are reduced to four block partials.  No
+// atomics: results are run-to-run identical.  M^R, V^R and R are streamed (non-temporal).
 // ---------------------------------------------------------------------------------------------
+template <int VEC>
 __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
-  __shared__ float red_a[3][64], red_b[3][64];
+  typedef float vec_t __attribute__((ext_vector_type(VEC)));
+  __shared__ float red_a[3][64 * VEC], red_b[3][64 * VEC];
   __shared__ float blk[4][64];
   const TensorView d(descs[blockIdx.y]);
   const int r = sp.r, n = d.n, n_slabs = d.n_slabs;
   const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int j = blockIdx.x * 64 + c;
+  const int j0 = (blockIdx.x * 64 + c) * VEC;
   const size_t slab_stride = (size_t)r * (size_t)n;
-  float a = 0.f, b = 0.f;
-  if (j < n) {
+  float a[VEC], b[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) a[e] = b[e] = 0.f;
+  if (j0 < n) {
     for (int kk = q; kk < r; kk += 4) {
-      const size_t idx = (size_t)kk * n + j;
-      float Rv = d.R[idx];
+      const size_t idx = (size_t)kk * n + j0;
+      vec_t Rv = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx));
       if (n_slabs > 1) {
-        for (int sl = 1; sl < n_slabs; ++sl) Rv += d.R[sl * slab_stride + idx];
-        d.R[idx] = Rv;
+        for (int sl = 1; sl < n_slabs; ++sl)
+          Rv += *reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + sl * slab_stride + idx);
+        *reinterpret_cast<APOLLO_GLOBAL vec_t*>(d.R + idx) = Rv;
       }
-      const float mo = d.M[idx], vo = d.V[idx];
-      const float mn = __builtin_fmaf(sp.beta1, mo, sp.omb1 * Rv);
-      const float vn = __builtin_fmaf(sp.beta2, vo, sp.omb2 * (Rv * Rv));
-      d.M[idx] = mn;
-      d.V[idx] = vn;
-      const float rt = (mn * sp.inv_bc1) / (__builtin_sqrtf(vn * sp.inv_bc2) + sp.eps);
-      a = __builtin_fmaf(rt, rt, a);
-      b = __builtin_fmaf(Rv, Rv, b);
+      const vec_t mo = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.M + idx));
+      const vec_t vo = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.V + idx));
+      vec_t mn, vn;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float Re = Rv[e];
+        const float me = __builtin_fmaf(sp.beta1, mo[e], sp.omb1 * Re);
+        const float ve = __builtin_fmaf(sp.beta2, vo[e], sp.omb2 * (Re * Re));
+        const float rt = (me * sp.inv_bc1) / (__builtin_sqrtf(ve * sp.inv_bc2) + sp.eps);
+        a[e] = __builtin_fmaf(rt, rt, a[e]);
+        b[e] = __builtin_fmaf(Re, Re, b[e]);
+        mn[e] = me;
+        vn[e] = ve;
+      }
+      __builtin_nontemporal_store(mn, reinterpret_cast<APOLLO_GLOBAL vec_t*>(d.M + idx));
+      __builtin_nontemporal_store(vn, reinterpret_cast<APOLLO_GLOBAL vec_t*>(d.V + idx));
     }
   }
   if (q > 0) {
-    red_a[q - 1][c] = a;
-    red_b[q - 1][c] = b;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      red_a[q - 1][c * VEC + e] = a[e];
+      red_b[q - 1][c * VEC + e] = b[e];
+    }
   }
   __syncthreads();
   float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
-  if (q == 0 && j < n) {
-    a = ((a + red_a[0][c]) + red_a[1][c]) + red_a[2][c];
-    b = ((b + red_b[0][c]) + red_b[1][c]) + red_b[2][c];
-    float csq = d.colsq[j];
-    if (n_slabs > 1) {
-      for (int sl = 1; sl < n_slabs; ++sl) csq += d.colsq[(size_t)sl * n + j];
-      d.colsq[j] = csq;
+  if (q == 0 && j0 < n) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const int j = j0 + e;
+      const float ae = ((a[e] + red_a[0][c * VEC + e]) + red_a[1][c * VEC + e]) + red_a[2][c * VEC + e];
+      const float be = ((b[e] + red_b[0][c * VEC + e]) + red_b[1][c * VEC + e]) + red_b[2][c * VEC + e];
+      float csq = d.colsq[j];
+      if (n_slabs > 1) {
+        for (int sl = 1; sl < n_slabs; ++sl) csq += d.colsq[(size_t)sl * n + j];
+        d.colsq[j] = csq;
+      }
+      const float sj = (be > 0.f) ? __builtin_sqrtf(ae) / __builtin_sqrtf(be) : 0.f;
+      d.s[j] = sj;                   // per-channel factor (Eq. 4); unused in tensor mode
+      t0 += ae;
+      t1 += be;
+      t2 += csq;
+      t3 += sj * sj * csq;
     }
-    const float sj = (b > 0.f) ? __builtin_sqrtf(a) / __builtin_sqrtf(b) : 0.f;
-    d.s[j] = sj;                     // per-channel factor (Eq. 4); unused in tensor mode
-    t0 = a;
-    t1 = b;
-    t2 = csq;
-    t3 = sj * sj * csq;
   }
   if (q == 0) {
     blk[0][c] = t0;
@@ -67,7 +88,7 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
     blk[3][c] = t3;
   }
   __syncthreads();
-  // four waves: wave w reduces quantity w over the 64 channels (fixed butterfly order)
+  // four waves: wave w reduces quantity w over the 64 channel groups (fixed butterfly order)
   {
     float v = blk[q][c];
 #pragma unroll
@@ -77,8 +98,13 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
 }
 
 hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, const StepParams& sp, hipStream_t st) {
-  dim3 grid((unsigned)((n + 63) / 64), (unsigned)count, 1);
-  hipLaunchKernelGGL(adam_norms_kernel, grid, dim3(256), 0, st, d_descs, sp);
+  if ((n & 3) == 0) {
+    dim3 grid((unsigned)((n / 4 + 63) / 64), (unsigned)count, 1);
+    hipLaunchKernelGGL(adam_norms_kernel<4>, grid, dim3(256), 0, st, d_descs, sp);
+  } else {
+    dim3 grid((unsigned)((n + 63) / 64), (unsigned)count, 1);
+    hipLaunchKernelGGL(adam_norms_kernel<1>, grid, dim3(256), 0, st, d_descs, sp);
+  }
   return hipGetLastError();
 }
 

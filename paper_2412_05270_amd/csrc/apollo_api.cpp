@@ -103,7 +103,7 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
       if ((t.rows + sl - 1) / sl > 1020) sl = (t.rows + 1019) / 1020;
       t.n_slabs = sl;
     }
-    t.k2_blocks = (t.n + 63) / 64;
+    t.k2_blocks = (t.n & 3) == 0 ? (t.n / 4 + 63) / 64 : (t.n + 63) / 64;   // blocks of adam_norms_kernel
     const size_t rn = (size_t)cfg->rank * (size_t)t.n * sizeof(float);
     st = align_up(st);
     t.st_m = st;

@@ -21,7 +21,7 @@ struct TensorDesc {
   float* R;            // scratch: n_slabs partial copies of R, each r x n (slab 0 ends canonical)
   float* colsq;        // scratch: n_slabs partial copies of sum_i G[i,j]^2, each n
   float* s;            // scratch: channel factors s_j, n floats
-  float* partials;     // scratch: 4 floats per 64-channel block (sums of a_j, b_j, colsq_j, s_j^2 colsq_j)
+  float* partials;     // scratch: 4 floats per block of the moment kernel (sums of a_j, b_j, colsq_j, s_j^2 colsq_j)
   float* scal;         // scratch: [0] lr*alpha*c(*s for tensor mode) [1] c [2] norm [3] s (tensor mode)
   int32_t rows, cols;
   int32_t m, n;
@@ -29,7 +29,7 @@ struct TensorDesc {
   int32_t left;        // 1: m = rows (R = P G), 0: m = cols (R = G P^T)
   int32_t tensor_id;   // index in the caller's list: part of the generator's counter
   int32_t n_slabs;     // number of partial sums the projection kernel leaves along m
-  int32_t k2_blocks;   // ceil(n / 64)
+  int32_t k2_blocks;   // blocks of the moment kernel (256 or 64 channels each)
   int32_t pad_;
 };
 

@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
     for (; i + 12 < i1; i += 16) {
       u32x4_t v[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) v[u] = gp[(size_t)(i + 4 * u) * stride];
+      for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(gp + (size_t)(i + 4 * u) * stride);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const float z = zs[i + 4 * u - i0];
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
       }
     }
     for (; i < i1; i += 4) {
-      const u32x4_t v = gp[(size_t)i * stride];
+      const u32x4_t v = __builtin_nontemporal_load(gp + (size_t)i * stride);
       const float z = zs[i - i0];
       float f[8];
       unpack8(v, f);
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(256) void project_rank1_right_kernel(const TensorDe
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int ii = min(i + u, rows - 1);
-        v[u] = gbase[(size_t)ii * nv + v0];
+        v[u] = __builtin_nontemporal_load(gbase + (size_t)ii * nv + v0);
       }
       const f32x4_t za = reinterpret_cast<const f32x4_t*>(zs)[2 * v0];
       const f32x4_t zb = reinterpret_cast<const f32x4_t*>(zs)[2 * v0 + 1];
