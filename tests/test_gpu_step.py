@@ -55,6 +55,20 @@ def test_ragged_shapes_both_sides_with_weight_decay_and_limiter(dtype, mode, ran
     run_parity(wl, list(range(len(RAGGED))), wl.steps, boost={4: 3.0})
 
 
+# shapes chosen so that the matrix-core projection runs with 1, 2, 3 and 5 pipeline stages (m = 64,
+# 128, 192, 320), a ragged (shifted) last channel tile (n = 264, 520, 1376), exactly one tile
+# (n = 256), and both orientations
+MFMA_SHAPES = [(64, 264), (264, 64), (128, 520), (520, 128), (192, 256), (256, 192), (320, 1376), (1376, 320)]
+
+
+@pytest.mark.parametrize("rank", [32, 64, 96, 128, 256])
+def test_matrix_core_projection_tile_configurations(rank):
+    shapes = [s for s in MFMA_SHAPES if min(s) >= rank]
+    wl = WL.Workload("mfma_cfg_r%d" % rank, 12, shapes, torch.bfloat16, "normal", 1e-2, rank=rank,
+                     refresh_interval=2, steps=3, lr=1e-2)
+    run_parity(wl, list(range(len(shapes))), wl.steps)
+
+
 @pytest.mark.parametrize("side", ["left", "right"])
 def test_forced_side_and_no_bias_correction(side):
     shapes = [(48, 96), (96, 48), (64, 64)]
