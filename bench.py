@@ -24,8 +24,23 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores, published
 PHASES = ["projection_fill", "projection", "adam_norms", "limiter", "update"]
-KERNEL_OF_PHASE = {"projection_fill": "fill_projection_kernel", "projection": "project_*_kernel",
+KERNEL_OF_PHASE = {"projection_fill": "fill_projection_kernel", "projection": "project_mfma_kernel",
                    "adam_norms": "adam_norms_kernel", "limiter": "finalize_kernel", "update": "update_kernel"}
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per step of `kernel` from the committed rocprofv3 FETCH_SIZE + WRITE_SIZE summary of
+    this workload (profiles/<workload>_hbm_traffic.txt, counters scaled by the copy-kernel
+    calibration), or None when there is no such summary."""
+    path = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % workload)
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith("traffic_bytes_per_step %s:" % kernel):
+                    return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def make_cfg(A, wl, seed=20241205):
@@ -84,10 +99,25 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev):
         roof = {"bound": "hbm", "achieved": w["bytes"] / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": hbm_frac, "traffic": None}
     roof["kernel"] = KERNEL_OF_PHASE[dom]
+    if dom == "projection" and wl.rank == 1:
+        roof["kernel"] = "project_rank1_left_kernel + project_rank1_right_kernel"
+    roof["traffic"] = measured_traffic(wl.name, KERNEL_OF_PHASE[dom])
+    roof["traffic_note"] = "HBM bytes read + written per step (all launches of the kernel), rocprofv3 counters, profiles/"
+    roof["algorithmic"] = w["bytes"]
     roof["phase"] = dom
     roof["ms_per_step"] = phase_ms[dom]
     roof["launches_per_step"] = len(set(wl.shapes))
+    pw = work["projection"]
+    t_proj = phase_ms["projection"] * 1e-3
+    proj = {"kernel": "project_mfma_kernel" if wl.rank > 1 else "project_rank1_{left,right}_kernel",
+            "ms_per_step": phase_ms["projection"],
+            "hbm": {"achieved": pw["bytes"] / t_proj / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": pw["bytes"] / t_proj / 1e9 / HBM_PEAK_GBS},
+            "mfma": {"achieved": pw["flops"] / t_proj / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": pw["flops"] / t_proj / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+            "traffic": measured_traffic(wl.name, "project_mfma_kernel") if wl.rank > 1 else None}
     res = {
+        "projection_roofline": proj,
         "value": wl.n_params / sec, "ms_per_step": sec * 1e3, "phase_ms": phase_ms, "roofline": roof,
         "whole_step_hbm_frac": work["total_bytes"] / sec / 1e9 / HBM_PEAK_GBS,
         "projection_tflops": work["projection"]["flops"] / (phase_ms["projection"] * 1e-3) / 1e12,
@@ -184,7 +214,7 @@ def main():
         r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev)
         also = {"workload": describe(wl2), "value": r2["value"], "unit": "params/s", "ms_per_step": r2["ms_per_step"],
                 "phase_ms": r2["phase_ms"], "roofline": r2["roofline"],
-                "whole_step_hbm_frac": r2["whole_step_hbm_frac"], "projection_tflops": r2["projection_tflops"],
+                "whole_step_hbm_frac": r2["whole_step_hbm_frac"], "projection_roofline": r2["projection_roofline"],
                 "finite": r2["finite"]}
     cpu = None
     if not args.no_cpu_baseline:
@@ -198,7 +228,8 @@ def main():
                    "grad_dtype": str(wl.grad_dtype).replace("torch.", ""), "state_gb": main_res["state_gb"],
                    "workspace_gb": main_res["workspace_gb"]},
         "roofline": main_res["roofline"], "cpu_baseline": cpu, "phase_ms": main_res["phase_ms"],
-        "whole_step_hbm_frac": main_res["whole_step_hbm_frac"], "finite": main_res["finite"], "also": also,
+        "whole_step_hbm_frac": main_res["whole_step_hbm_frac"], "projection_roofline": main_res["projection_roofline"],
+        "finite": main_res["finite"], "also": also,
     }
     print(json.dumps(out))
 
