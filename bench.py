@@ -33,14 +33,21 @@ def measured_traffic(workload, kernel):
     this workload (profiles/<workload>_hbm_traffic.txt, counters scaled by the copy-kernel
     calibration), or None when there is no such summary."""
     path = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % workload)
+    names = [kernel]
+    if "{" in kernel:  # "a_{x,y}_b" names the kernels a_x_b and a_y_b: their bytes add
+        head, rest = kernel.split("{", 1)
+        alts, tail = rest.split("}", 1)
+        names = [head + a + tail for a in alts.split(",")]
+    found = {}
     try:
         with open(path) as fh:
             for line in fh:
-                if line.startswith("traffic_bytes_per_step %s:" % kernel):
-                    return int(line.split(":")[1])
+                for nm in names:
+                    if line.startswith("traffic_bytes_per_step %s:" % nm):
+                        found[nm] = int(line.split(":")[1])
     except OSError:
-        pass
-    return None
+        return None
+    return sum(found.values()) if len(found) == len(names) else None
 
 
 def make_cfg(A, wl, seed=20241205):
