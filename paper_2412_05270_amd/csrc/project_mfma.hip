@@ -47,11 +47,15 @@ struct Cfg {
   static constexpr int LOADS = A_LOADS + 4;                // per wave and stage
 };
 
-__device__ __forceinline__ void dma16(const APOLLO_GLOBAL void* src, uint32_t lds_dst_uniform) {
+// One direct-to-LDS load: lane i fetches the 16 bytes at (uniform base) + (its own 32-bit byte
+// offset) and they land at LDS address (uniform dst) + 16 i.  Base and destination live in scalar
+// registers, so a stage's loads cost scalar arithmetic only; the per-lane offsets are loop
+// invariants.
+__device__ __forceinline__ void dma16(const APOLLO_GLOBAL void* base_uniform, uint32_t lane_off, uint32_t lds_dst_uniform) {
   uint32_t saved_m0;   // M0 is restored: the compiler may hold a value of its own there
-  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
                : "=&s"(saved_m0)
-               : "s"(lds_dst_uniform), "v"(src)
+               : "s"(lds_dst_uniform), "v"(lane_off), "s"(base_uniform)
                : "memory");
 }
 
@@ -60,19 +64,15 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-
-__device__ __forceinline__ float sq_sum8(const bf16x8_t& f) {
-  const u32x4_t v = __builtin_bit_cast(u32x4_t, f);
-  float t0 = bf_lo(v.x) * bf_lo(v.x), t1 = bf_hi(v.x) * bf_hi(v.x);
-  t0 = __builtin_fmaf(bf_lo(v.y), bf_lo(v.y), t0);
-  t1 = __builtin_fmaf(bf_hi(v.y), bf_hi(v.y), t1);
-  t0 = __builtin_fmaf(bf_lo(v.z), bf_lo(v.z), t0);
-  t1 = __builtin_fmaf(bf_hi(v.z), bf_hi(v.z), t1);
-  t0 = __builtin_fmaf(bf_lo(v.w), bf_lo(v.w), t0);
-  t1 = __builtin_fmaf(bf_hi(v.w), bf_hi(v.w), t1);
-  return t0 + t1;
+// acc + sum of the squares of a fragment's eight bf16 values: four packed dot products
+// (v_dot2c_f32_bf16: acc += a.lo b.lo + a.hi b.hi), no unpacking.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float sq_accum8(const bf16x8_t& f, float acc) {
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(f, f, 0, 1), __builtin_shufflevector(f, f, 0, 1), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(f, f, 2, 3), __builtin_shufflevector(f, f, 2, 3), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(f, f, 4, 5), __builtin_shufflevector(f, f, 4, 5), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(f, f, 6, 7), __builtin_shufflevector(f, f, 6, 7), acc, false);
+  return acc;
 }
 
 template <int MT, int WM, bool LEFT>
@@ -83,43 +83,59 @@ struct Ctx {
   unsigned char* lds;
   uint32_t lds_base;     // LDS byte address of `lds`
   int r, m, n, n0, rbase, tid, lane, wave, wm, wn, last_stage;
+  uint32_t a_off, b_off[2];   // per-lane byte offsets of the loads (loop invariants, see setup_loads)
+
+  // Split every load address into a wave-uniform base and a per-lane offset.
+  //   P slot q = tid + 256 u of a stage holds word ((4 s + q / RT) r + rbase + q % RT) of the scratch.
+  //   G, rows projected: wave-load u covers rows k = 8 wave + 2 u + (lane >> 5), lane fetching chunk
+  //     (lane & 31) ^ (4 (k & 3)); k & 3 depends on the parity of u only.
+  //   G, columns projected: wave-load u covers channels j = 64 wave + 16 u + (lane >> 2), lane
+  //     fetching octet (lane & 3) ^ ((j >> 2) & 3), and (j >> 2) & 3 = (lane >> 4) & 3.
+  __device__ __forceinline__ void setup_loads() {
+    if (C::A_CHUNKS > 0) {
+      a_off = (uint32_t)((tid / C::RT) * r + tid % C::RT) * 16u;
+    } else {
+      const int w2 = min(wave, 1);
+      a_off = (uint32_t)((2 * w2 + (lane >> 5)) * r + (lane & 31)) * 16u;
+    }
+    if (LEFT) {
+#pragma unroll
+      for (int par = 0; par < 2; ++par) {
+        const int chunk = (lane & 31) ^ (4 * ((2 * par + (lane >> 5)) & 3));
+        b_off[par] = (uint32_t)((lane >> 5) * n + 8 * chunk) * 2u;
+      }
+    } else {
+      const int oct = (lane & 3) ^ ((lane >> 4) & 3);
+      b_off[0] = b_off[1] = (uint32_t)((lane >> 2) * m + 8 * oct) * 2u;
+    }
+  }
 
   // all loads of stage s (clamped) into ring buffer `buf`: P tile first, then the G tile
   __device__ __forceinline__ void issue(int s, int buf) const {
     s = min(s, last_stage);
     const uint32_t a_base = lds_base + (uint32_t)(buf * C::STAGE_BYTES);
     const uint32_t b_base = a_base + (uint32_t)C::A_BYTES;
+    const APOLLO_GLOBAL u32x4_t* a_src = Pg + (size_t)((kKT / 8) * s) * r + rbase;
     if (C::A_CHUNKS > 0) {
+      constexpr int kOctsPerChunk = 256 / C::RT > 0 ? 256 / C::RT : 1;   // octets of P rows per 256 slots
 #pragma unroll
-      for (int u = 0; u < C::A_CHUNKS; ++u) {
-        const int q = tid + 256 * u;
-        const APOLLO_GLOBAL u32x4_t* src = Pg + (size_t)((kKT / 8) * s + q / C::RT) * r + rbase + (q % C::RT);
-        dma16(src, __builtin_amdgcn_readfirstlane(a_base + (uint32_t)(wave * 64 + 256 * u) * 16u));
-      }
+      for (int u = 0; u < C::A_CHUNKS; ++u)
+        dma16(a_src + (size_t)(u * kOctsPerChunk) * r, a_off, a_base + (uint32_t)(wave * 64 + 256 * u) * 16u);
     } else {
       // RT = 32: the P tile is 128 slots; waves 0 and 1 load it, waves 2 and 3 repeat wave 1's
       // load (same data to the same place) so that every wave issues the same number of loads
-      const int w2 = min(wave, 1);
-      const int q = w2 * 64 + lane;
-      const APOLLO_GLOBAL u32x4_t* src = Pg + (size_t)((kKT / 8) * s + q / C::RT) * r + rbase + (q % C::RT);
-      dma16(src, __builtin_amdgcn_readfirstlane(a_base + (uint32_t)(w2 * 64) * 16u));
+      dma16(a_src, a_off, a_base + (uint32_t)(min(wave, 1) * 64) * 16u);
     }
     if (LEFT) {
+      const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(kKT * s + 8 * wave) * n + n0;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int k = 8 * wave + 2 * u + (lane >> 5);
-        const int chunk = (lane & 31) ^ (2 * (k & 3));
-        const APOLLO_GLOBAL uint16_t* src = G + (size_t)(kKT * s + k) * n + n0 + 8 * chunk;
-        dma16(src, __builtin_amdgcn_readfirstlane(b_base + (uint32_t)(8 * wave + 2 * u) * 512u));
-      }
+      for (int u = 0; u < 4; ++u)
+        dma16(b_src + (size_t)(2 * u) * n, b_off[u & 1], b_base + (uint32_t)(8 * wave + 2 * u) * 512u);
     } else {
+      const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(n0 + 64 * wave) * m + kKT * s;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int j = 64 * wave + 16 * u + (lane >> 2);
-        const int oct = (lane & 3) ^ ((j >> 1) & 3);
-        const APOLLO_GLOBAL uint16_t* src = G + (size_t)(n0 + j) * m + kKT * s + 8 * oct;
-        dma16(src, __builtin_amdgcn_readfirstlane(b_base + (uint32_t)(4 * wave + u) * 1024u));
-      }
+      for (int u = 0; u < 4; ++u)
+        dma16(b_src + (size_t)(16 * u) * m, b_off[0], b_base + (uint32_t)(4 * wave + u) * 1024u);
     }
   }
 
@@ -141,7 +157,7 @@ struct Ctx {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const int k = 16 * ks + 8 * (q >> 1) + 4 * t + e_s;
-          const unsigned char* p = B + k * 512 + (((col0 >> 3) ^ (2 * (k & 3))) * 16) + ((col0 >> 2) & 1) * 8;
+          const unsigned char* p = B + k * 512 + (((col0 >> 3) ^ (4 * (k & 3))) * 16) + ((col0 >> 2) & 1) * 8;
           h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((APOLLO_LDS s16x4_t*)(p));
         }
         typedef short s16x8_t __attribute__((ext_vector_type(8)));
@@ -152,7 +168,7 @@ struct Ctx {
 #pragma unroll
       for (int b = 0; b < C::NTW; ++b) {
         const int j = 32 * (wn * C::NTW + b) + (lane & 31);
-        bf[b] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(B + j * 64 + ((oct ^ ((j >> 1) & 3)) * 16)));
+        bf[b] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(B + j * 64 + ((oct ^ ((j >> 2) & 3)) * 16)));
       }
     }
   }
@@ -169,20 +185,24 @@ __device__ __forceinline__ void mfma_block(f32x16_t (&acc)[MT][NTW], const bf16x
 template <int NTW>
 __device__ __forceinline__ void sq_block(float (&sq)[NTW], const bf16x8_t (&bf)[NTW]) {
 #pragma unroll
-  for (int b = 0; b < NTW; ++b) sq[b] += sq_sum8(bf[b]);
+  for (int b = 0; b < NTW; ++b) sq[b] = sq_accum8(bf[b], sq[b]);
 }
 
-// Scheduling hint for one k-step region: first the LDS fragment reads of the next k-step, then
-// the MFMAs with the norm arithmetic spread between them (the compiler otherwise sinks the reads
-// below the MFMAs, exposing their latency at the next k-step).
+// Scheduling hint for one k-step region: the LDS fragment reads of the next k-step are spread over
+// the first MFMAs, one group of reads behind each, and the norm arithmetic over all of them.  A
+// wave issues in order and its LDS reads take tens of cycles each to issue: bunched at the head of
+// the k-step they would leave the matrix core idle; placed behind an MFMA they issue while it runs,
+// and the last of them still has half a k-step to land.
 //   masks of sched_group_barrier: 0x2 VALU, 0x8 MFMA, 0x100 LDS read
-template <int READS, int MFMAS, int VALU_PER>
+template <int READS, int MFMAS, int VALU_PER, int G = 0>
 __device__ __forceinline__ void sched_kstep() {
-  __builtin_amdgcn_sched_group_barrier(0x100, READS, 0);
-#pragma unroll
-  for (int g = 0; g < MFMAS; ++g) {
+  if constexpr (G < MFMAS) {
+    constexpr int kSpread = MFMAS > 1 ? (MFMAS + 1) / 2 : 1;   // MFMAs that carry reads
+    constexpr int nr = G < kSpread ? (G + 1) * READS / kSpread - G * READS / kSpread : 0;
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    if (VALU_PER > 0) __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, 0);
+    if constexpr (nr > 0) __builtin_amdgcn_sched_group_barrier(0x100, nr, 0);
+    if constexpr (VALU_PER > 0) __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, 0);
+    sched_kstep<READS, MFMAS, VALU_PER, G + 1>();
   }
 }
 
@@ -204,10 +224,11 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
   cx.r = sp.r; cx.m = d.m; cx.n = d.n;
   cx.n0 = min((slot % tiles) * kNT, d.n - kNT);   // ragged last tile overlaps its neighbour
   cx.rbase = blockIdx.y * C::RT;
-  cx.tid = threadIdx.x; cx.lane = cx.tid & 63; cx.wave = cx.tid >> 6;
+  cx.tid = threadIdx.x; cx.lane = cx.tid & 63; cx.wave = __builtin_amdgcn_readfirstlane(cx.tid >> 6);
   cx.wm = cx.wave / C::WN; cx.wn = cx.wave % C::WN;
   const int stages = cx.m / kKT;
   cx.last_stage = stages - 1;
+  cx.setup_loads();
   const bool sq_wave = cx.wm == 0;     // these waves write the norms (every wave sums them: branch-free loop)
 
   f32x16_t acc[MT][C::NTW];
@@ -235,7 +256,7 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
     cx.read_frags(cur, 1, af1, bf1);
     mfma_block<MT, C::NTW>(acc, af0, bf0);
     sq_block<C::NTW>(sq, bf0);
-    sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (18 * C::NTW + MT * C::NTW - 1) / (MT * C::NTW)>();
+    sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (4 * C::NTW + MT * C::NTW - 1) / (MT * C::NTW)>();
     __builtin_amdgcn_sched_barrier(0);
     // stage s+1 has landed once only the loads of stage s+2 are outstanding; after the barrier
     // every wave is past stage s-1, whose buffer then receives stage s+3
@@ -247,7 +268,7 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
     cx.read_frags((s + 1) % kRing, 0, af0, bf0);
     mfma_block<MT, C::NTW>(acc, af1, bf1);
     sq_block<C::NTW>(sq, bf1);
-    sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (18 * C::NTW + MT * C::NTW - 1) / (MT * C::NTW)>();
+    sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (4 * C::NTW + MT * C::NTW - 1) / (MT * C::NTW)>();
     __builtin_amdgcn_sched_barrier(0);
   }
   wait_vmcnt<0>();      // drain the (clamped, redundant) loads still in flight before LDS is reused
