@@ -2,16 +2,20 @@
 // operands reach LDS by direct-to-LDS loads (global_load_lds_dwordx4) and never pass through
 // registers; per-channel squared norms of G (limiter, Section 3.2) come from the fragments.
 //
-// Block = 256 threads (four waves) = an RT x 256 tile of R, RT = 32 MT WM.  The reduced dimension
+// Block = 512 threads (eight waves, two per SIMD) = an RT x 256 tile of R, RT = 32 MT WM; a wave
+// owns a (32 MT) x (32 WM) sub-tile.  A wave issues at most one instruction every four cycles, so
+// with a single wave per SIMD every address, wait and load instruction is time the matrix core
+// idles; with two, one wave's bookkeeping hides behind the other's MFMAs.  The reduced dimension
 // is walked in stages of 32 through a ring of kRing LDS buffers; the loads of stage s+3 are in
 // flight while stage s is multiplied.  A direct-to-LDS load puts lane i's 16 bytes at (uniform
 // base) + 16 i, so the LDS image of a wave's load is fixed to "64 consecutive 16-byte slots";
-// which global 16 bytes a lane fetches is free, and that freedom is used to swizzle:
+// which global 16 bytes a lane fetches is free, and that freedom is used to swizzle (the LDS has
+// 64 banks of 4 bytes; a b128 read is served 16 lanes at a time, a b64 read 32 lanes at a time):
 //   A (P from the scratch, fragment-major): slot (octet, row), already fragment order.
 //   B, columns projected (G channel-major, reduction index contiguous): slot (channel j, p) holds
-//     octet p ^ ((j >> 1) & 3) of channel j; a fragment is one ds_read_b128, conflict-free.
+//     octet p ^ ((j >> 2) & 3) of channel j; a fragment is one ds_read_b128, conflict-free.
 //   B, rows projected (reduction index strided): the tile is stored as it is in memory, row k =
-//     32 chunks of 8 channels, slot (k, p) holding chunk p ^ (2 (k & 3)); fragments are read with
+//     32 chunks of 8 channels, slot (k, p) holding chunk p ^ (4 (k & 3)); fragments are read with
 //     the LDS transpose read ds_read_b64_tr_b16 (within 16 lanes, result lane i, element e =
 //     element i % 4 of the 8 bytes addressed by lane 4 e + i / 4), two reads per fragment.
 // All vector-memory operations of the main loop are inline assembly (the compiler would wait
@@ -35,16 +39,21 @@ constexpr int kRing = 4;     // LDS buffers; kRing - 1 stages of loads in flight
 constexpr int kXcds = 8;
 constexpr int kBBytes = kKT * kNT * 2;   // 16 KB
 
+constexpr int kWaves = 8;
+constexpr int kThreads = 64 * kWaves;
+
 template <int MT, int WM>
 struct Cfg {
   static constexpr int RT = 32 * MT * WM;
-  static constexpr int WN = 4 / WM;
-  static constexpr int NTW = 8 / WN;
+  static constexpr int WN = kWaves / WM;
+  static constexpr int NTW = 8 / WN;                          // = WM
   static constexpr int A_BYTES = (kKT / 8) * RT * 16;
   static constexpr int STAGE_BYTES = A_BYTES + kBBytes;
-  static constexpr int A_CHUNKS = A_BYTES / 16 / 256;      // loads per thread per stage (0 if RT < 64)
+  static constexpr int A_SLOTS = A_BYTES / 16;
+  static constexpr int A_CHUNKS = A_SLOTS / kThreads;         // loads per thread per stage (0 if RT < 128)
   static constexpr int A_LOADS = A_CHUNKS > 0 ? A_CHUNKS : 1;
-  static constexpr int LOADS = A_LOADS + 4;                // per wave and stage
+  static constexpr int B_LOADS = kBBytes / 16 / kThreads;     // 2
+  static constexpr int LOADS = A_LOADS + B_LOADS;             // per wave and stage
 };
 
 // One direct-to-LDS load: lane i fetches the 16 bytes at (uniform base) + (its own 32-bit byte
@@ -83,30 +92,37 @@ struct Ctx {
   unsigned char* lds;
   uint32_t lds_base;     // LDS byte address of `lds`
   int r, m, n, n0, rbase, tid, lane, wave, wm, wn, last_stage;
-  uint32_t a_off, b_off[2];   // per-lane byte offsets of the loads (loop invariants, see setup_loads)
+  uint32_t a_off[C::A_LOADS], b_off[C::B_LOADS];   // per-lane byte offsets of the loads (loop invariants)
 
-  // Split every load address into a wave-uniform base and a per-lane offset.
-  //   P slot q = tid + 256 u of a stage holds word ((4 s + q / RT) r + rbase + q % RT) of the scratch.
-  //   G, rows projected: wave-load u covers rows k = 8 wave + 2 u + (lane >> 5), lane fetching chunk
-  //     (lane & 31) ^ (4 (k & 3)); k & 3 depends on the parity of u only.
-  //   G, columns projected: wave-load u covers channels j = 64 wave + 16 u + (lane >> 2), lane
+  // Split every load address into a wave-uniform base (one per operand and stage) and a per-lane
+  // offset that also carries the position of the load within the stage.
+  //   P slot q = tid + 512 u of a stage holds word ((4 s + q / RT) r + rbase + q % RT) of the
+  //     scratch (tiles of fewer than 512 slots: the first waves load, the rest repeat the last one's
+  //     load, same data to the same place, so that every wave issues the same number of loads).
+  //   G, rows projected: wave-load u covers rows k = 4 wave + 2 u + (lane >> 5), lane fetching chunk
+  //     (lane & 31) ^ (4 (k & 3)), and k & 3 = (2 u + (lane >> 5)) & 3.
+  //   G, columns projected: wave-load u covers channels j = 32 wave + 16 u + (lane >> 2), lane
   //     fetching octet (lane & 3) ^ ((j >> 2) & 3), and (j >> 2) & 3 = (lane >> 4) & 3.
   __device__ __forceinline__ void setup_loads() {
     if (C::A_CHUNKS > 0) {
-      a_off = (uint32_t)((tid / C::RT) * r + tid % C::RT) * 16u;
-    } else {
-      const int w2 = min(wave, 1);
-      a_off = (uint32_t)((2 * w2 + (lane >> 5)) * r + (lane & 31)) * 16u;
-    }
-    if (LEFT) {
 #pragma unroll
-      for (int par = 0; par < 2; ++par) {
-        const int chunk = (lane & 31) ^ (4 * ((2 * par + (lane >> 5)) & 3));
-        b_off[par] = (uint32_t)((lane >> 5) * n + 8 * chunk) * 2u;
+      for (int u = 0; u < C::A_LOADS; ++u) {
+        const int q = tid + kThreads * u;
+        a_off[u] = (uint32_t)((q / C::RT) * r + q % C::RT) * 16u;
       }
     } else {
-      const int oct = (lane & 3) ^ ((lane >> 4) & 3);
-      b_off[0] = b_off[1] = (uint32_t)((lane >> 2) * m + 8 * oct) * 2u;
+      const int q = min(wave, C::A_SLOTS / 64 - 1) * 64 + lane;
+      a_off[0] = (uint32_t)((q / C::RT) * r + q % C::RT) * 16u;
+    }
+#pragma unroll
+    for (int u = 0; u < C::B_LOADS; ++u) {
+      if (LEFT) {
+        const int chunk = (lane & 31) ^ (4 * ((2 * u + (lane >> 5)) & 3));
+        b_off[u] = (uint32_t)((2 * u + (lane >> 5)) * n + 8 * chunk) * 2u;
+      } else {
+        const int oct = (lane & 3) ^ ((lane >> 4) & 3);
+        b_off[u] = (uint32_t)((16 * u + (lane >> 2)) * m + 8 * oct) * 2u;
+      }
     }
   }
 
@@ -117,27 +133,26 @@ struct Ctx {
     const uint32_t b_base = a_base + (uint32_t)C::A_BYTES;
     const APOLLO_GLOBAL u32x4_t* a_src = Pg + (size_t)((kKT / 8) * s) * r + rbase;
     if (C::A_CHUNKS > 0) {
-      constexpr int kOctsPerChunk = 256 / C::RT > 0 ? 256 / C::RT : 1;   // octets of P rows per 256 slots
 #pragma unroll
-      for (int u = 0; u < C::A_CHUNKS; ++u)
-        dma16(a_src + (size_t)(u * kOctsPerChunk) * r, a_off, a_base + (uint32_t)(wave * 64 + 256 * u) * 16u);
+      for (int u = 0; u < C::A_LOADS; ++u) dma16(a_src, a_off[u], a_base + (uint32_t)(wave * 64 + kThreads * u) * 16u);
     } else {
-      // RT = 32: the P tile is 128 slots; waves 0 and 1 load it, waves 2 and 3 repeat wave 1's
-      // load (same data to the same place) so that every wave issues the same number of loads
-      dma16(a_src, a_off, a_base + (uint32_t)(min(wave, 1) * 64) * 16u);
+      dma16(a_src, a_off[0], a_base + (uint32_t)(min(wave, C::A_SLOTS / 64 - 1) * 64) * 16u);
     }
     if (LEFT) {
-      const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(kKT * s + 8 * wave) * n + n0;
+      const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(kKT * s + 4 * wave) * n + n0;
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        dma16(b_src + (size_t)(2 * u) * n, b_off[u & 1], b_base + (uint32_t)(8 * wave + 2 * u) * 512u);
+      for (int u = 0; u < C::B_LOADS; ++u) dma16(b_src, b_off[u], b_base + (uint32_t)(4 * wave + 2 * u) * 512u);
     } else {
-      const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(n0 + 64 * wave) * m + kKT * s;
+      const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(n0 + 32 * wave) * m + kKT * s;
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        dma16(b_src + (size_t)(16 * u) * m, b_off[0], b_base + (uint32_t)(4 * wave + u) * 1024u);
+      for (int u = 0; u < C::B_LOADS; ++u) dma16(b_src, b_off[u], b_base + (uint32_t)(2 * wave + u) * 1024u);
     }
   }
+
+  // n-tile (32 channels) of the block that this wave's fragment b covers.  The order is rotated
+  // by wm so that fragment 0 is a different tile in each of the WM waves sharing the same
+  // channels: every wave then sums the norms of its fragment 0 only, and together they cover all.
+  __device__ __forceinline__ int tile_of(int b) const { return wn * C::NTW + (b ^ wm); }
 
   __device__ __forceinline__ void read_frags(int buf, int ks, bf16x8_t (&af)[MT], bf16x8_t (&bf)[C::NTW]) const {
     const unsigned char* A = lds + buf * C::STAGE_BYTES;
@@ -152,7 +167,7 @@ struct Ctx {
       const int e_s = s16 >> 2, g_s = s16 & 3;
 #pragma unroll
       for (int b = 0; b < C::NTW; ++b) {
-        const int col0 = 32 * (wn * C::NTW + b) + 16 * (q & 1) + 4 * g_s;
+        const int col0 = 32 * tile_of(b) + 16 * (q & 1) + 4 * g_s;
         s16x4_t h[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -167,7 +182,7 @@ struct Ctx {
     } else {
 #pragma unroll
       for (int b = 0; b < C::NTW; ++b) {
-        const int j = 32 * (wn * C::NTW + b) + (lane & 31);
+        const int j = 32 * tile_of(b) + (lane & 31);
         bf[b] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(B + j * 64 + ((oct ^ ((j >> 2) & 3)) * 16)));
       }
     }
@@ -180,12 +195,6 @@ __device__ __forceinline__ void mfma_block(f32x16_t (&acc)[MT][NTW], const bf16x
   for (int a = 0; a < MT; ++a)
 #pragma unroll
     for (int b = 0; b < NTW; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
-}
-
-template <int NTW>
-__device__ __forceinline__ void sq_block(float (&sq)[NTW], const bf16x8_t (&bf)[NTW]) {
-#pragma unroll
-  for (int b = 0; b < NTW; ++b) sq[b] = sq_accum8(bf[b], sq[b]);
 }
 
 // Scheduling hint for one k-step region: the LDS fragment reads of the next k-step are spread over
@@ -207,7 +216,7 @@ __device__ __forceinline__ void sched_kstep() {
 }
 
 template <int MT, int WM, bool LEFT>
-__global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
+__global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
                                                                int tiles, int count) {
   using C = Cfg<MT, WM>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -229,7 +238,6 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
   const int stages = cx.m / kKT;
   cx.last_stage = stages - 1;
   cx.setup_loads();
-  const bool sq_wave = cx.wm == 0;     // these waves write the norms (every wave sums them: branch-free loop)
 
   f32x16_t acc[MT][C::NTW];
 #pragma unroll
@@ -238,9 +246,7 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
     for (int b = 0; b < C::NTW; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-  float sq[C::NTW];
-#pragma unroll
-  for (int b = 0; b < C::NTW; ++b) sq[b] = 0.f;
+  float sq = 0.f;    // squared norm of this wave's fragment-0 channels (see tile_of)
   bf16x8_t af0[MT], bf0[C::NTW], af1[MT], bf1[C::NTW];
 
   // prologue: three stages requested, wait for the first
@@ -255,8 +261,8 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
     // k-step 0 of stage s, fragments of k-step 1 on their way
     cx.read_frags(cur, 1, af1, bf1);
     mfma_block<MT, C::NTW>(acc, af0, bf0);
-    sq_block<C::NTW>(sq, bf0);
-    sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (4 * C::NTW + MT * C::NTW - 1) / (MT * C::NTW)>();
+    sq = sq_accum8(bf0[0], sq);
+    sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (4 + MT * C::NTW - 1) / (MT * C::NTW)>();
     __builtin_amdgcn_sched_barrier(0);
     // stage s+1 has landed once only the loads of stage s+2 are outstanding; after the barrier
     // every wave is past stage s-1, whose buffer then receives stage s+3
@@ -267,8 +273,8 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
     // k-step 1 of stage s, fragments of k-step 0 of stage s+1 on their way
     cx.read_frags((s + 1) % kRing, 0, af0, bf0);
     mfma_block<MT, C::NTW>(acc, af1, bf1);
-    sq_block<C::NTW>(sq, bf1);
-    sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (4 * C::NTW + MT * C::NTW - 1) / (MT * C::NTW)>();
+    sq = sq_accum8(bf1[0], sq);
+    sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (4 + MT * C::NTW - 1) / (MT * C::NTW)>();
     __builtin_amdgcn_sched_barrier(0);
   }
   wait_vmcnt<0>();      // drain the (clamped, redundant) loads still in flight before LDS is reused
@@ -280,7 +286,7 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
   for (int a = 0; a < MT; ++a) {
 #pragma unroll
     for (int b = 0; b < C::NTW; ++b) {
-      const int j = cx.n0 + 32 * (cx.wn * C::NTW + b) + (lane & 31);
+      const int j = cx.n0 + 32 * cx.tile_of(b) + (lane & 31);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int i = cx.rbase + cx.wm * 32 * MT + a * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
@@ -288,13 +294,10 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const TensorDesc* __r
       }
     }
   }
-  if (blockIdx.y == 0 && sq_wave) {
+  if (blockIdx.y == 0) {
     // lanes l and l + 32 hold the two k-halves of channel (tile, l % 32)
-#pragma unroll
-    for (int b = 0; b < C::NTW; ++b) {
-      const float t = sq[b] + __shfl_xor(sq[b], 32, 64);
-      if (lane < 32) d.colsq[cx.n0 + 32 * (cx.wn * C::NTW + b) + lane] = t;
-    }
+    const float t = sq + __shfl_xor(sq, 32, 64);
+    if (lane < 32) d.colsq[cx.n0 + 32 * cx.tile_of(0) + lane] = t;
   }
 }
 
@@ -312,7 +315,7 @@ hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, const StepPar
   const int tiles = (n + kNT - 1) / kNT;
   const int per_xcd = (count + kXcds - 1) / kXcds;
   dim3 grid((unsigned)(kXcds * per_xcd * tiles), (unsigned)(sp.r / C::RT), 1);
-  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, LEFT>), grid, dim3(256), lds_bytes, st, d_descs, sp, tiles, count);
+  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, LEFT>), grid, dim3(kThreads), lds_bytes, st, d_descs, sp, tiles, count);
   return hipGetLastError();
 }
 
@@ -320,8 +323,8 @@ template <bool LEFT>
 hipError_t launch_side(const TensorDesc* d_descs, int count, int n, const StepParams& sp, hipStream_t st) {
   const int r = sp.r;
   if (r % 256 == 0) return launch_cfg<4, 2, LEFT>(d_descs, count, n, sp, st);
-  if (r % 128 == 0) return launch_cfg<4, 1, LEFT>(d_descs, count, n, sp, st);
-  if (r % 64 == 0) return launch_cfg<2, 1, LEFT>(d_descs, count, n, sp, st);
+  if (r % 128 == 0) return launch_cfg<2, 2, LEFT>(d_descs, count, n, sp, st);
+  if (r % 64 == 0) return launch_cfg<1, 2, LEFT>(d_descs, count, n, sp, st);
   return launch_cfg<1, 1, LEFT>(d_descs, count, n, sp, st);
 }
 
