@@ -112,7 +112,8 @@ apollo_status_t apollo_state_offsets(const apollo_config_t* cfg, const apollo_sh
                                      size_t* v_offset, size_t* norm_offset);
 
 /* Bytes of per-step scratch (the transient P tiles, R, per-channel sums, factors, per-tensor
- * scalars and the device descriptor table); contents are meaningless between steps except for
+ * scalars, the device descriptor table and, for a bf16 tensor whose rows are projected and whose
+ * row length is not a multiple of 8, a copy of its gradient with rows padded to 16 bytes); contents are meaningless between steps except for
  * apollo_debug_get.  0 on invalid arguments. */
 size_t apollo_workspace_bytes(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n_tensors);
 

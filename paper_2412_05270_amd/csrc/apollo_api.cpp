@@ -30,6 +30,9 @@ struct TensorPlan {
   bool left, bf16;
   Path path;
   int32_t n_slabs, k2_blocks;
+  bool pad_g;                                                   // projection reads a row-padded copy of g
+  int32_t ldg;                                                  // row pitch (elements) of what it reads
+  size_t ws_gpad;
   size_t st_m, st_v, st_norm;                                   // offsets into the state buffer
   size_t ws_p, ws_r, ws_colsq, ws_s, ws_partials, ws_scal;       // offsets into the workspace
   int32_t desc_index;                                           // position in the grouped descriptor table
@@ -41,6 +44,8 @@ struct Group {
   bool left, bf16;
   Path path;
   int32_t n_slabs;
+  bool pad_g;
+  int32_t ldg;
 };
 
 struct Plan {
@@ -96,6 +101,8 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
       t.path = Path::kMfma;
     else
       t.path = Path::kGeneric;
+    t.pad_g = t.path == Path::kMfma && project_mfma_needs_padding(t.rows, t.cols, t.left);
+    t.ldg = t.pad_g ? (t.cols + 7) & ~7 : t.cols;
     t.n_slabs = 1;
     if (t.path == Path::kRank1 && t.left) {
       int32_t sl = (t.rows + 511) / 512;
@@ -120,7 +127,7 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     const TensorPlan& a = plan.t[k];
     Group g{};
     g.rows = a.rows; g.cols = a.cols; g.m = a.m; g.n = a.n; g.m8 = a.m8;
-    g.left = a.left; g.bf16 = a.bf16; g.path = a.path; g.n_slabs = a.n_slabs;
+    g.left = a.left; g.bf16 = a.bf16; g.path = a.path; g.n_slabs = a.n_slabs; g.pad_g = a.pad_g; g.ldg = a.ldg;
     g.count = 0;
     const int32_t gi = (int32_t)plan.groups.size();
     for (int32_t j = k; j < n; ++j) {
@@ -139,7 +146,7 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
       if (group_of[k] == (int32_t)gi) plan.t[k].desc_index = pos++;
   }
 
-  // workspace: descriptor table, then per tensor P, R, colsq, s, partials, scalars
+  // workspace: descriptor table, then per tensor P, padded gradient copy, R, colsq, s, partials, scalars
   size_t ws = 0;
   plan.desc_bytes = (size_t)n * sizeof(TensorDesc);
   ws = align_up(plan.desc_bytes);
@@ -147,6 +154,8 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     TensorPlan& t = plan.t[k];
     t.ws_p = ws;
     if (t.path != Path::kRank1) ws = align_up(ws + (size_t)cfg->rank * t.m8 * (t.bf16 ? 2 : 4));
+    t.ws_gpad = ws;
+    if (t.pad_g) ws = align_up(ws + (size_t)t.rows * t.ldg * 2);
     t.ws_r = ws;
     ws = align_up(ws + (size_t)t.n_slabs * cfg->rank * t.n * sizeof(float));
     t.ws_colsq = ws;
@@ -294,6 +303,8 @@ apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg, c
     d.V = reinterpret_cast<float*>(h->state + t.st_v);
     d.prev_norm = reinterpret_cast<float*>(h->state + t.st_norm);
     d.P = t.path == Path::kRank1 ? nullptr : static_cast<void*>(h->ws + t.ws_p);
+    d.gpad = t.pad_g ? static_cast<void*>(h->ws + t.ws_gpad) : nullptr;
+    d.ldg = t.ldg;
     d.R = reinterpret_cast<float*>(h->ws + t.ws_r);
     d.colsq = reinterpret_cast<float*>(h->ws + t.ws_colsq);
     d.s = reinterpret_cast<float*>(h->ws + t.ws_s);
@@ -367,6 +378,10 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
     if (g.path == Path::kRank1) continue;
     e = launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, st);
     what = "projection fill";
+    if (e == hipSuccess && g.pad_g) {
+      e = launch_pad_gradient(dd + g.first, g.count, g.rows, g.cols, g.ldg, st);
+      what = "gradient padding";
+    }
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[1], st);
   // (b) R = P G and the per-channel squared norms of G
@@ -376,7 +391,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
     if (g.path == Path::kRank1)
       e = launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sp, st);
     else if (g.path == Path::kMfma)
-      e = launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, sp, st);
+      e = launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, g.pad_g, sp, st);
     else
       e = launch_project_generic(dd + g.first, g.count, g.n, g.bf16, sp, st);
   }

@@ -18,6 +18,7 @@ struct TensorDesc {
   float* V;            // state: V^R, r x n
   float* prev_norm;    // state: stored norm of the scaled gradient (limiter), 1 float
   void* P;             // scratch: unit-variance projection z, fragment-major (see p_index)
+  void* gpad;          // scratch: copy of g with rows padded to ldg elements (16-byte aligned rows), or null
   float* R;            // scratch: n_slabs partial copies of R, each r x n (slab 0 ends canonical)
   float* colsq;        // scratch: n_slabs partial copies of sum_i G[i,j]^2, each n
   float* s;            // scratch: channel factors s_j, n floats
@@ -30,7 +31,7 @@ struct TensorDesc {
   int32_t tensor_id;   // index in the caller's list: part of the generator's counter
   int32_t n_slabs;     // number of partial sums the projection kernel leaves along m
   int32_t k2_blocks;   // blocks of the moment kernel (256 or 64 channels each)
-  int32_t pad_;
+  int32_t ldg;         // row pitch, in elements, of the gradient the matrix-core projection reads (gpad or g)
 };
 
 // Per-step scalars handed to the kernels by value.
@@ -75,17 +76,18 @@ struct TensorView {
   APOLLO_GLOBAL float* V;
   APOLLO_GLOBAL float* prev_norm;
   APOLLO_GLOBAL void* P;
+  APOLLO_GLOBAL void* gpad;
   APOLLO_GLOBAL float* R;
   APOLLO_GLOBAL float* colsq;
   APOLLO_GLOBAL float* s;
   APOLLO_GLOBAL float* partials;
   APOLLO_GLOBAL float* scal;
-  int32_t rows, cols, m, n, m8, left, tensor_id, n_slabs, k2_blocks;
+  int32_t rows, cols, m, n, m8, left, tensor_id, n_slabs, k2_blocks, ldg;
   __device__ __forceinline__ explicit TensorView(const TensorDesc& d)
-      : w(gptr(d.w)), g(gptr(d.g)), M(gptr(d.M)), V(gptr(d.V)), prev_norm(gptr(d.prev_norm)), P(gptr(d.P)),
+      : w(gptr(d.w)), g(gptr(d.g)), M(gptr(d.M)), V(gptr(d.V)), prev_norm(gptr(d.prev_norm)), P(gptr(d.P)), gpad(gptr(d.gpad)),
         R(gptr(d.R)), colsq(gptr(d.colsq)), s(gptr(d.s)), partials(gptr(d.partials)), scal(gptr(d.scal)),
         rows(d.rows), cols(d.cols), m(d.m), n(d.n), m8(d.m8), left(d.left), tensor_id(d.tensor_id),
-        n_slabs(d.n_slabs), k2_blocks(d.k2_blocks) {}
+        n_slabs(d.n_slabs), k2_blocks(d.k2_blocks), ldg(d.ldg) {}
 };
 
 // Element (kk, i) of the scratch projection: eight consecutive i of one row are contiguous, the
@@ -105,8 +107,10 @@ hipError_t launch_project_generic(const TensorDesc* d_descs, int count, int n, b
 hipError_t launch_project_rank1(const TensorDesc* d_descs, int count, int rows, int cols, bool left,
                                 bool bf16, int n_slabs, const StepParams& sp, hipStream_t st);
 bool project_rank1_supported(int rows, int cols, bool left, bool bf16);
-hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left,
+hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool padded,
                                const StepParams& sp, hipStream_t st);
+bool project_mfma_needs_padding(int rows, int cols, bool left);
+hipError_t launch_pad_gradient(const TensorDesc* d_descs, int count, int rows, int cols, int ldg, hipStream_t st);
 bool project_mfma_supported(int rows, int cols, bool left, bool bf16, int r);
 hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, const StepParams& sp,
                              hipStream_t st);

@@ -91,7 +91,7 @@ struct Ctx {
   const APOLLO_GLOBAL uint16_t* G;
   unsigned char* lds;
   uint32_t lds_base;     // LDS byte address of `lds`
-  int r, m, n, n0, rbase, tid, lane, wave, wm, wn, last_stage;
+  int r, m, n, ldg, n0, rbase, tid, lane, wave, wm, wn, last_stage;   // ldg: row pitch of G in elements
   uint32_t a_off[C::A_LOADS], b_off[C::B_LOADS];   // per-lane byte offsets of the loads (loop invariants)
 
   // Split every load address into a wave-uniform base (one per operand and stage) and a per-lane
@@ -118,7 +118,7 @@ struct Ctx {
     for (int u = 0; u < C::B_LOADS; ++u) {
       if (LEFT) {
         const int chunk = (lane & 31) ^ (4 * ((2 * u + (lane >> 5)) & 3));
-        b_off[u] = (uint32_t)((2 * u + (lane >> 5)) * n + 8 * chunk) * 2u;
+        b_off[u] = (uint32_t)((2 * u + (lane >> 5)) * ldg + 8 * chunk) * 2u;
       } else {
         const int oct = (lane & 3) ^ ((lane >> 4) & 3);
         b_off[u] = (uint32_t)((16 * u + (lane >> 2)) * m + 8 * oct) * 2u;
@@ -139,7 +139,7 @@ struct Ctx {
       dma16(a_src, a_off[0], a_base + (uint32_t)(min(wave, C::A_SLOTS / 64 - 1) * 64) * 16u);
     }
     if (LEFT) {
-      const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(kKT * s + 4 * wave) * n + n0;
+      const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(kKT * s + 4 * wave) * ldg + n0;
 #pragma unroll
       for (int u = 0; u < C::B_LOADS; ++u) dma16(b_src, b_off[u], b_base + (uint32_t)(4 * wave + 2 * u) * 512u);
     } else {
@@ -217,7 +217,7 @@ __device__ __forceinline__ void sched_kstep() {
 
 template <int MT, int WM, bool LEFT>
 __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
-                                                               int tiles, int count) {
+                                                                    int tiles, int count, int padded) {
   using C = Cfg<MT, WM>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   // XCD-aware numbering: block w runs on XCD w % 8; XCD x works through tensors x, x+8, ...
@@ -227,11 +227,15 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
   const TensorView d(descs[tensor]);
   Ctx<MT, WM, LEFT> cx;
   cx.Pg = reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(d.P);
-  cx.G = reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(d.g);
+  cx.G = reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(padded ? (const APOLLO_GLOBAL void*)d.gpad : d.g);
   cx.lds = lds;
   cx.lds_base = (uint32_t)(uintptr_t)(APOLLO_LDS unsigned char*)lds;
-  cx.r = sp.r; cx.m = d.m; cx.n = d.n;
-  cx.n0 = min((slot % tiles) * kNT, d.n - kNT);   // ragged last tile overlaps its neighbour
+  cx.r = sp.r; cx.m = d.m; cx.n = d.n; cx.ldg = d.ldg;
+  // the ragged last tile overlaps its neighbour.  With rows projected its start stays a multiple
+  // of 8 channels (16-byte loads), so with padded rows it may reach up to 7 channels past n: those
+  // read the zero padding and are not stored.  With columns projected a channel is a stored row
+  // and the tile ends exactly at n.
+  cx.n0 = min((slot % tiles) * kNT, LEFT ? (d.n - kNT + 7) & ~7 : d.n - kNT);
   cx.rbase = blockIdx.y * C::RT;
   cx.tid = threadIdx.x; cx.lane = cx.tid & 63; cx.wave = __builtin_amdgcn_readfirstlane(cx.tid >> 6);
   cx.wm = cx.wave / C::WN; cx.wn = cx.wave % C::WN;
@@ -287,22 +291,25 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
 #pragma unroll
     for (int b = 0; b < C::NTW; ++b) {
       const int j = cx.n0 + 32 * cx.tile_of(b) + (lane & 31);
+      if (j < n) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = cx.rbase + cx.wm * 32 * MT + a * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        d.R[(size_t)i * n + j] = acc[a][b][v] * scale;
+        for (int v = 0; v < 16; ++v) {
+          const int i = cx.rbase + cx.wm * 32 * MT + a * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          d.R[(size_t)i * n + j] = acc[a][b][v] * scale;
+        }
       }
     }
   }
   if (blockIdx.y == 0) {
     // lanes l and l + 32 hold the two k-halves of channel (tile, l % 32)
     const float t = sq + __shfl_xor(sq, 32, 64);
-    if (lane < 32) d.colsq[cx.n0 + 32 * cx.tile_of(0) + lane] = t;
+    const int j = cx.n0 + 32 * cx.tile_of(0) + lane;
+    if (lane < 32 && j < n) d.colsq[j] = t;
   }
 }
 
 template <int MT, int WM, bool LEFT>
-hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, const StepParams& sp, hipStream_t st) {
+hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, bool padded, const StepParams& sp, hipStream_t st) {
   using C = Cfg<MT, WM>;
   const int lds_bytes = kRing * C::STAGE_BYTES;
   static bool attr_done = false;
@@ -315,17 +322,18 @@ hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, const StepPar
   const int tiles = (n + kNT - 1) / kNT;
   const int per_xcd = (count + kXcds - 1) / kXcds;
   dim3 grid((unsigned)(kXcds * per_xcd * tiles), (unsigned)(sp.r / C::RT), 1);
-  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, LEFT>), grid, dim3(kThreads), lds_bytes, st, d_descs, sp, tiles, count);
+  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, LEFT>), grid, dim3(kThreads), lds_bytes, st, d_descs, sp, tiles, count,
+                     padded ? 1 : 0);
   return hipGetLastError();
 }
 
 template <bool LEFT>
-hipError_t launch_side(const TensorDesc* d_descs, int count, int n, const StepParams& sp, hipStream_t st) {
+hipError_t launch_side(const TensorDesc* d_descs, int count, int n, bool padded, const StepParams& sp, hipStream_t st) {
   const int r = sp.r;
-  if (r % 256 == 0) return launch_cfg<4, 2, LEFT>(d_descs, count, n, sp, st);
-  if (r % 128 == 0) return launch_cfg<2, 2, LEFT>(d_descs, count, n, sp, st);
-  if (r % 64 == 0) return launch_cfg<1, 2, LEFT>(d_descs, count, n, sp, st);
-  return launch_cfg<1, 1, LEFT>(d_descs, count, n, sp, st);
+  if (r % 256 == 0) return launch_cfg<4, 2, LEFT>(d_descs, count, n, padded, sp, st);
+  if (r % 128 == 0) return launch_cfg<2, 2, LEFT>(d_descs, count, n, padded, sp, st);
+  if (r % 64 == 0) return launch_cfg<1, 2, LEFT>(d_descs, count, n, padded, sp, st);
+  return launch_cfg<1, 1, LEFT>(d_descs, count, n, padded, sp, st);
 }
 
 }  // namespace
@@ -334,16 +342,23 @@ bool project_mfma_supported(int rows, int cols, bool left, bool bf16, int r) {
   if (!bf16 || (r & 31) != 0) return false;
   const int m = left ? rows : cols;
   if ((m % 64) != 0) return false;          // whole stages, and P's octets full
-  if ((cols & 7) != 0) return false;        // 16-byte aligned gradient loads
   const int n = left ? cols : rows;
   if (n < kNT) return false;                // a block needs a full tile of channels
   return true;
 }
 
-hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left,
+// Rows of the stored gradient must start on 16-byte boundaries.  With columns projected the row
+// length is m (a multiple of 64); with rows projected it is n, and a row length that is not a
+// multiple of 8 elements needs the padded scratch copy (launch_pad_gradient).
+bool project_mfma_needs_padding(int rows, int cols, bool left) {
+  (void)rows;
+  return left && (cols & 7) != 0;
+}
+
+hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool padded,
                                const StepParams& sp, hipStream_t st) {
   const int n = left ? cols : rows;
-  return left ? launch_side<true>(d_descs, count, n, sp, st) : launch_side<false>(d_descs, count, n, sp, st);
+  return left ? launch_side<true>(d_descs, count, n, padded, sp, st) : launch_side<false>(d_descs, count, n, padded, sp, st);
 }
 
 }  // namespace apollo

@@ -51,6 +51,33 @@ hipError_t launch_fill_projection(const TensorDesc* d_descs, int count, int r, i
   return hipGetLastError();
 }
 
+// Copy of a bf16 gradient whose row length is not a multiple of eight elements into a scratch
+// matrix with rows padded (zeros) to ldg elements, so that every row starts on a 16-byte boundary
+// as the direct-to-LDS loads of the matrix-core projection need.  One thread per eight output
+// elements; the source is read element by element because its rows have no common alignment.
+__global__ __launch_bounds__(256) void pad_gradient_kernel(const TensorDesc* __restrict__ descs, int rows, int cols,
+                                                           int ldg) {
+  const TensorView d(descs[blockIdx.y]);
+  const int oct_per_row = ldg >> 3;
+  const size_t t = (size_t)blockIdx.x * 256u + threadIdx.x;
+  if (t >= (size_t)rows * (size_t)oct_per_row) return;
+  const int row = (int)(t / (size_t)oct_per_row);
+  const int c0 = 8 * (int)(t % (size_t)oct_per_row);
+  const APOLLO_GLOBAL uint16_t* src = reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(d.g) + (size_t)row * cols;
+  uint32_t h[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) h[e] = c0 + e < cols ? (uint32_t)src[c0 + e] : 0u;
+  reinterpret_cast<APOLLO_GLOBAL u32x4_t*>(d.gpad)[t] =
+      mk_u4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+}
+
+hipError_t launch_pad_gradient(const TensorDesc* d_descs, int count, int rows, int cols, int ldg, hipStream_t st) {
+  const size_t total = (size_t)rows * (size_t)(ldg >> 3);
+  dim3 grid((unsigned)((total + 255) / 256), (unsigned)count, 1);
+  hipLaunchKernelGGL(pad_gradient_kernel, grid, dim3(256), 0, st, d_descs, rows, cols, ldg);
+  return hipGetLastError();
+}
+
 // Row-major r x m view of the same stream (debug).
 template <bool BF16>
 __global__ __launch_bounds__(256) void fill_projection_rowmajor_kernel(void* __restrict__ out, int r, int m,

@@ -69,6 +69,20 @@ def test_matrix_core_projection_tile_configurations(rank):
     run_parity(wl, list(range(len(shapes))), wl.steps)
 
 
+@pytest.mark.parametrize("rank", [32, 128])
+def test_matrix_core_projection_rows_not_multiple_of_eight(rank):
+    """Rows projected and a row length that is odd / not a multiple of 8 (LLaMA-1B's 2048 x 5461
+    has this): the projection reads a row-padded copy of the gradient, and the shifted last channel
+    tile reaches past n into the padding (n = 333: 2 channels, n = 259: 5, n = 1001: 7)."""
+    shapes = [(128, 333), (192, 259), (128, 1001), (256, 262)]
+    # and, with columns projected, channel counts that are not multiples of 8 (5461 x 2048 has this):
+    # no padding there, the last tile ends exactly at n
+    shapes += [(333, 128), (259, 192)]
+    wl = WL.Workload("mfma_pad_r%d" % rank, 13, shapes, torch.bfloat16, "normal", 1e-2, rank=rank,
+                     refresh_interval=2, steps=3, lr=1e-2)
+    run_parity(wl, list(range(len(shapes))), wl.steps)
+
+
 @pytest.mark.parametrize("side", ["left", "right"])
 def test_forced_side_and_no_bias_correction(side):
     shapes = [(48, 96), (96, 48), (64, 64)]
