@@ -178,6 +178,66 @@ const char* apollo_last_error(const apollo_handle_t* h);
 /* Frees the host-side handle.  Does not touch device memory or synchronise. */
 void apollo_destroy(apollo_handle_t* h);
 
+/* ------------------------------------------------------------------------------------------
+ * Element-wise AdamW for the parameters that are not projected (embeddings, norm gains, the
+ * output head; the paper applies APOLLO to the attention and MLP matrices only and its step
+ * times cover the whole model).  Section 3.1, Eq. 1: M <- beta1 M + (1 - beta1) G,
+ * V <- beta2 V + (1 - beta2) G^2, W <- W - lr * M^ / (sqrt(V^) + eps) - lr * lambda * W, with
+ * the decoupled decay term of Algorithm 1 (step 4) and Adam's bias correction M^ = M / (1 -
+ * beta1^t), V^ = V / (1 - beta2^t) (bias_correction = 0: Eq. 1 literally).  One kernel launch
+ * covers the whole tensor list.  Same conventions as above: DEVICE buffers owned by the
+ * caller, nothing allocated, nothing synchronised, status codes, apollo_last_error(NULL) for
+ * calls without a handle.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct apollo_adamw_handle apollo_adamw_handle_t; /* opaque, host-side */
+
+typedef struct {
+  int64_t numel;        /* elements of the tensor (any shape, handled flat), 1 .. 2^40         */
+  int32_t grad_dtype;   /* APOLLO_F32 or APOLLO_BF16                                           */
+  int32_t reserved;     /* set to 0                                                            */
+} apollo_flat_shape_t;
+
+typedef struct {
+  float beta1, beta2;       /* in [0, 1)                                                        */
+  float eps;                /* >= 0, added after the bias-corrected square root                 */
+  float weight_decay;       /* lambda                                                           */
+  int32_t bias_correction;  /* 1 (default) or 0                                                 */
+  int32_t reserved;         /* set to 0                                                         */
+} apollo_adamw_config_t;
+
+/* Bytes of state: per tensor, in list order, each block on a 256-byte boundary: M[numel] fp32,
+ * V[numel] fp32 (V starts on a 256-byte boundary too).  0 on invalid arguments. */
+size_t apollo_adamw_state_bytes(const apollo_flat_shape_t* shapes, int32_t n_tensors);
+
+/* Byte offsets of one tensor's M and V in the state buffer (either output may be NULL). */
+apollo_status_t apollo_adamw_state_offsets(const apollo_flat_shape_t* shapes, int32_t n_tensors,
+                                           int32_t tensor, size_t* m_offset, size_t* v_offset);
+
+/* Bytes of scratch (descriptor table and the block-to-tensor table of the single launch).
+ * 0 on invalid arguments. */
+size_t apollo_adamw_workspace_bytes(const apollo_flat_shape_t* shapes, int32_t n_tensors);
+
+/* Creates a handle for a fixed tensor list.  `state` and `workspace` are DEVICE buffers of at
+ * least the sizes above, 256-byte aligned; the state is zero-filled on `hip_stream` unless
+ * `zero_state` is 0 (resume).  Blocks the host until the block table is on the device. */
+apollo_status_t apollo_adamw_init(apollo_adamw_handle_t** out, const apollo_adamw_config_t* cfg,
+                                  const apollo_flat_shape_t* shapes, int32_t n_tensors,
+                                  void* state, size_t state_bytes, void* workspace,
+                                  size_t workspace_bytes, int32_t zero_state, void* hip_stream);
+
+/* One AdamW step of every tensor at 1-based step `step` with learning rate `lr`: tensors[k].w
+ * (DEVICE fp32, updated in place) and tensors[k].g (DEVICE, grad_dtype, read only), both with
+ * numel elements and 16-byte aligned.  Enqueues on `hip_stream`, does not synchronise. */
+apollo_status_t apollo_adamw_step(apollo_adamw_handle_t* h, const apollo_tensor_t* tensors,
+                                  int32_t n_tensors, int64_t step, float lr, void* hip_stream);
+
+/* Text of the last error on this handle; with h == NULL, of the last failed AdamW call of this
+ * thread that had no handle (apollo_adamw_init, the size queries). */
+const char* apollo_adamw_last_error(const apollo_adamw_handle_t* h);
+
+/* Frees the host-side handle.  Does not touch device memory. */
+void apollo_adamw_destroy(apollo_adamw_handle_t* h);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,4 +1,5 @@
-"""MI355X-native APOLLO / APOLLO-Mini optimizer step (arXiv 2412.05270, Algorithm 1).
+"""MI355X-native APOLLO / APOLLO-Mini optimizer step (arXiv 2412.05270, Algorithm 1), and the
+element-wise AdamW (Section 3.1) for the parameters APOLLO does not project.
 
 Thin ctypes binding over the C-ABI library built from csrc/ (see include/apollo.h for the
 contract of every call).  Everything numerical happens in the HIP kernels; this package only
@@ -11,4 +12,7 @@ from .binding import (  # noqa: F401
     APOLLO_SIDE_RIGHT, APOLLO_TENSOR, ApolloConfig, ApolloError, ApolloShape, ApolloStepper,
     ApolloTensor, apollo_debug_fill_projection, apollo_debug_gauss_parts, apollo_debug_get,
     apollo_debug_copy, apollo_debug_philox, apollo_destroy, apollo_profile_enable, apollo_profile_read, apollo_init, apollo_last_error, apollo_state_bytes,
-    apollo_state_offsets, apollo_step, apollo_workspace_bytes, library_path, load_library)
+    apollo_state_offsets, apollo_step, apollo_workspace_bytes, library_path, load_library,
+    AdamwStepper, ApolloAdamwConfig, ApolloFlatShape, apollo_adamw_destroy, apollo_adamw_init,
+    apollo_adamw_last_error, apollo_adamw_state_bytes, apollo_adamw_state_offsets, apollo_adamw_step,
+    apollo_adamw_workspace_bytes)

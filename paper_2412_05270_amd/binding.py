@@ -34,6 +34,15 @@ class ApolloTensor(C.Structure):
     _fields_ = [("w", C.c_void_p), ("g", C.c_void_p)]
 
 
+class ApolloFlatShape(C.Structure):
+    _fields_ = [("numel", C.c_int64), ("grad_dtype", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ApolloAdamwConfig(C.Structure):
+    _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("weight_decay", C.c_float),
+                ("bias_correction", C.c_int32), ("reserved", C.c_int32)]
+
+
 class ApolloError(RuntimeError):
     def __init__(self, status, message):
         super().__init__("apollo status %d: %s" % (status, message))
@@ -87,6 +96,21 @@ def load_library():
     lib.apollo_last_error.argtypes = [vp]
     lib.apollo_destroy.restype = None
     lib.apollo_destroy.argtypes = [vp]
+    fsp, acp = C.POINTER(ApolloFlatShape), C.POINTER(ApolloAdamwConfig)
+    lib.apollo_adamw_state_bytes.restype = sz
+    lib.apollo_adamw_state_bytes.argtypes = [fsp, i32]
+    lib.apollo_adamw_workspace_bytes.restype = sz
+    lib.apollo_adamw_workspace_bytes.argtypes = [fsp, i32]
+    lib.apollo_adamw_state_offsets.restype = i32
+    lib.apollo_adamw_state_offsets.argtypes = [fsp, i32, i32, C.POINTER(sz), C.POINTER(sz)]
+    lib.apollo_adamw_init.restype = i32
+    lib.apollo_adamw_init.argtypes = [C.POINTER(vp), acp, fsp, i32, vp, sz, vp, sz, i32, vp]
+    lib.apollo_adamw_step.restype = i32
+    lib.apollo_adamw_step.argtypes = [vp, C.POINTER(ApolloTensor), i32, i64, f32, vp]
+    lib.apollo_adamw_last_error.restype = C.c_char_p
+    lib.apollo_adamw_last_error.argtypes = [vp]
+    lib.apollo_adamw_destroy.restype = None
+    lib.apollo_adamw_destroy.argtypes = [vp]
     _lib = lib
     return lib
 
@@ -176,6 +200,111 @@ def apollo_profile_read(handle):
 
 def apollo_destroy(handle):
     load_library().apollo_destroy(handle)
+
+
+def _flat_shape_array(shapes):
+    arr = (ApolloFlatShape * len(shapes))()
+    for i, s in enumerate(shapes):
+        arr[i] = s if isinstance(s, ApolloFlatShape) else ApolloFlatShape(s[0], s[1], 0)
+    return arr
+
+
+def apollo_adamw_last_error(handle=None):
+    return (load_library().apollo_adamw_last_error(handle) or b"").decode()
+
+
+def apollo_adamw_state_bytes(shapes):
+    return load_library().apollo_adamw_state_bytes(_flat_shape_array(shapes) if shapes is not None else None,
+                                                   len(shapes) if shapes is not None else 0)
+
+
+def apollo_adamw_workspace_bytes(shapes):
+    return load_library().apollo_adamw_workspace_bytes(_flat_shape_array(shapes) if shapes is not None else None,
+                                                       len(shapes) if shapes is not None else 0)
+
+
+def apollo_adamw_state_offsets(shapes, tensor):
+    m, v = C.c_size_t(), C.c_size_t()
+    rc = load_library().apollo_adamw_state_offsets(_flat_shape_array(shapes), len(shapes), tensor, C.byref(m), C.byref(v))
+    return rc, m.value, v.value
+
+
+def apollo_adamw_init(cfg, shapes, state_ptr, state_bytes, workspace_ptr, workspace_bytes, zero_state=1, stream=None):
+    """Returns (status, handle)."""
+    h = C.c_void_p()
+    rc = load_library().apollo_adamw_init(C.byref(h), C.byref(cfg) if cfg is not None else None,
+                                          _flat_shape_array(shapes) if shapes is not None else None,
+                                          len(shapes) if shapes is not None else 0,
+                                          state_ptr, state_bytes, workspace_ptr, workspace_bytes, zero_state, stream)
+    return rc, (h if h.value else None)
+
+
+def apollo_adamw_step(handle, tensors, step, lr, stream=None, n_tensors=None):
+    if tensors is not None and not isinstance(tensors, C.Array):
+        arr = (ApolloTensor * len(tensors))()
+        for i, (w, g) in enumerate(tensors):
+            arr[i] = ApolloTensor(w, g)
+        tensors = arr
+    n = n_tensors if n_tensors is not None else (len(tensors) if tensors is not None else 0)
+    return load_library().apollo_adamw_step(handle, tensors, n, step, lr, stream)
+
+
+def apollo_adamw_destroy(handle):
+    load_library().apollo_adamw_destroy(handle)
+
+
+class AdamwStepper:
+    """Owner of the device buffers (torch tensors) around one AdamW handle; calls go to the C ABI."""
+
+    def __init__(self, cfg, weights, grads, device="cuda:0", zero_state=True):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.weights, self.grads = list(weights), list(grads)
+        self.shapes = []
+        for w, g in zip(self.weights, self.grads):
+            assert w.dtype == torch.float32 and w.is_contiguous() and g.is_contiguous()
+            assert g.shape == w.shape and g.dtype in (torch.float32, torch.bfloat16)
+            self.shapes.append((w.numel(), APOLLO_BF16 if g.dtype == torch.bfloat16 else APOLLO_F32))
+        sb = apollo_adamw_state_bytes(self.shapes)
+        wb = apollo_adamw_workspace_bytes(self.shapes)
+        if sb == 0 or wb == 0:
+            raise ApolloError(APOLLO_EINVAL, apollo_adamw_last_error())
+        self.state = torch.empty(sb, dtype=torch.uint8, device=device)
+        self.workspace = torch.empty(wb, dtype=torch.uint8, device=device)
+        self.stream = torch.cuda.current_stream(device)
+        rc, self.handle = apollo_adamw_init(cfg, self.shapes, self.state.data_ptr(), sb, self.workspace.data_ptr(), wb,
+                                            1 if zero_state else 0, self.stream.cuda_stream)
+        if rc != APOLLO_OK:
+            raise ApolloError(rc, apollo_adamw_last_error())
+        self._tensors = (ApolloTensor * len(self.weights))()
+        for i, (w, g) in enumerate(zip(self.weights, self.grads)):
+            self._tensors[i] = ApolloTensor(w.data_ptr(), g.data_ptr())
+
+    def step(self, step, lr):
+        rc = apollo_adamw_step(self.handle, self._tensors, step, lr, self.stream.cuda_stream)
+        if rc != APOLLO_OK:
+            raise ApolloError(rc, apollo_adamw_last_error(self.handle))
+
+    def moments(self, tensor):
+        """(M, V) of one tensor as fp32 views into the state buffer."""
+        rc, mo, vo = apollo_adamw_state_offsets(self.shapes, tensor)
+        if rc != APOLLO_OK:
+            raise ApolloError(rc, apollo_adamw_last_error())
+        n = self.shapes[tensor][0]
+        f = self.state.view(self.torch.float32)
+        return f[mo // 4: mo // 4 + n], f[vo // 4: vo // 4 + n]
+
+    def close(self):
+        if self.handle is not None:
+            apollo_adamw_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class ApolloStepper:

@@ -15,7 +15,7 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libapollo_mi355x.so")
 
 SOURCES = ["apollo_api.cpp", "rng_kernels.hip", "project_kernels.hip", "project_mfma.hip",
-           "adam_update_kernels.hip"]
+           "adam_update_kernels.hip", "adamw_api.cpp", "adamw_kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

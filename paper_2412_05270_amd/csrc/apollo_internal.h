@@ -97,6 +97,28 @@ __host__ __device__ inline size_t p_index(int kk, int i, int r) {
   return ((size_t)(i >> 3) * (size_t)r + (size_t)kk) * 8u + (size_t)(i & 7);
 }
 
+// One flat parameter tensor of the element-wise AdamW path (Section 3.1, Eq. 1).
+struct AdamwDesc {
+  float* w;              // numel fp32, updated in place
+  const void* g;         // numel, bf16 or fp32
+  float* m;              // state: first moment
+  float* v;              // state: second moment
+  uint64_t numel;
+  uint32_t first_block;  // index of the tensor's first block in the launch
+  uint32_t bf16;         // gradient is bf16
+};
+
+struct AdamwParams {
+  float beta1, beta2, omb1, omb2, eps;
+  float inv_bc1, inv_bc2;   // 1/(1-beta^t) or 1
+  float lr, lr_decay;       // lr, lr * lambda
+};
+
+constexpr int kAdamwBlockElems = 1024;   // 256 threads x 4 consecutive elements
+
+hipError_t launch_adamw(const AdamwDesc* d_descs, const uint32_t* d_block_tensor, uint32_t n_blocks,
+                        const AdamwParams& p, hipStream_t st);
+
 // ---- launchers (defined in the .hip files); all enqueue on `st` and return the launch status
 hipError_t launch_fill_projection(const TensorDesc* d_descs, int count, int r, int m8, bool bf16,
                                   const StepParams& sp, hipStream_t st);

@@ -27,7 +27,9 @@ def test_library_exports_every_declared_symbol():
     assert {"apollo_init", "apollo_step", "apollo_state_bytes", "apollo_workspace_bytes", "apollo_destroy",
             "apollo_debug_fill_projection", "apollo_debug_get", "apollo_state_offsets", "apollo_last_error",
             "apollo_debug_philox", "apollo_debug_gauss_parts", "apollo_debug_copy", "apollo_profile_enable",
-            "apollo_profile_read"} <= names
+            "apollo_profile_read", "apollo_adamw_state_bytes", "apollo_adamw_state_offsets",
+            "apollo_adamw_workspace_bytes", "apollo_adamw_init", "apollo_adamw_step", "apollo_adamw_last_error",
+            "apollo_adamw_destroy"} <= names
     for n in names:
         assert hasattr(lib, n), n
 
@@ -36,6 +38,8 @@ def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(A.ApolloShape) == 24
     assert C.sizeof(A.ApolloConfig) == 56
     assert C.sizeof(A.ApolloTensor) == 16
+    assert C.sizeof(A.ApolloFlatShape) == 16
+    assert C.sizeof(A.ApolloAdamwConfig) == 24
 
 
 def test_state_bytes_follow_table_1():
@@ -97,3 +101,44 @@ def test_null_handle_calls_fail_cleanly():
     assert A.apollo_debug_fill_projection(None, 0, 1, 16, A.APOLLO_F32) == A.APOLLO_EINVAL
     assert A.apollo_debug_gauss_parts(1 << 24, 1, 16, 16, 16) == A.APOLLO_EINVAL
     A.apollo_destroy(None)
+
+
+# ------------------------------------------------------------------ element-wise AdamW entry points
+def _acfg(**kw):
+    base = dict(beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, bias_correction=1, reserved=0)
+    base.update(kw)
+    return A.ApolloAdamwConfig(**base)
+
+
+def test_adamw_state_layout():
+    # per tensor M then V, each starting on a 256-byte boundary
+    shapes = [(100, A.APOLLO_F32), (5, A.APOLLO_BF16), (64, A.APOLLO_BF16)]
+    assert A.apollo_adamw_state_bytes(shapes) == 512 + 512 + 256 + 256 + 256 + 256
+    assert A.apollo_adamw_state_offsets(shapes, 0) == (0, 0, 512)
+    assert A.apollo_adamw_state_offsets(shapes, 1) == (0, 1024, 1280)
+    assert A.apollo_adamw_state_offsets(shapes, 2) == (0, 1536, 1792)
+    assert A.apollo_adamw_state_offsets(shapes, 3)[0] == A.APOLLO_EINVAL
+    # workspace: descriptor table (48 bytes per tensor) and one table entry per block of 1024 elements
+    assert A.apollo_adamw_workspace_bytes([(1024, 0)]) == 256 + 256
+    assert A.apollo_adamw_workspace_bytes([(1025, 0)] * 7) == 512 + 256
+    assert A.apollo_adamw_workspace_bytes([(1024 * 200, 1)]) == 256 + 1024
+
+
+def test_adamw_bad_arguments_are_rejected_before_any_launch():
+    assert A.apollo_adamw_state_bytes([]) == 0
+    assert A.apollo_adamw_state_bytes([(0, 0)]) == 0
+    assert A.apollo_adamw_state_bytes([(8, 7)]) == 0
+    assert "dtype" in A.apollo_adamw_last_error()
+    assert A.apollo_adamw_state_bytes([((1 << 40) + 1, 0)]) == 0
+    shapes = [(1000, 0)]
+    sb, wb = A.apollo_adamw_state_bytes(shapes), A.apollo_adamw_workspace_bytes(shapes)
+    for bad in (dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1.0), dict(weight_decay=float("inf")),
+                dict(bias_correction=2)):
+        assert A.apollo_adamw_init(_acfg(**bad), shapes, 256, sb, 512, wb)[0] == A.APOLLO_EINVAL
+    assert A.apollo_adamw_init(_acfg(), shapes, 256, sb - 1, 512, wb)[0] == A.APOLLO_ESTATE
+    assert A.apollo_adamw_init(_acfg(), shapes, 256, sb, 512, wb - 1)[0] == A.APOLLO_ESTATE
+    assert A.apollo_adamw_init(_acfg(), shapes, 260, sb, 512, wb)[0] == A.APOLLO_ESTATE
+    assert A.apollo_adamw_init(_acfg(), shapes, None, sb, 512, wb)[0] == A.APOLLO_EINVAL
+    assert A.apollo_adamw_init(None, shapes, 256, sb, 512, wb)[0] == A.APOLLO_EINVAL
+    assert A.apollo_adamw_step(None, [(16, 32)], 1, 0.1) == A.APOLLO_EINVAL
+    A.apollo_adamw_destroy(None)
