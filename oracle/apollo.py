@@ -22,6 +22,12 @@ Readings taken where the paper is silent or inconsistent:
   * A channel whose projected gradient is exactly zero gets s_j = 0 (0/0 otherwise).
   * M^R, V^R are kept when P is re-sampled.
   * Steps are 1-based: P is re-sampled when (t-1) mod T == 0, epoch = (t-1) div T.
+  * Storage types.  The paper trains "in BF16 data format" and sizes its state at 2 bytes per
+    element (Table 3), but gives no rounding rule.  Taken here: arithmetic in (at least) binary32;
+    a quantity kept in bfloat16 (W with weight_dtype="bf16"; M^R, V^R with state_dtype="bf16") is
+    rounded to nearest, ties to even, when it is stored, and everything computed after that uses
+    the stored value: R~ is formed from the rounded moments, so the state alone determines the
+    rest of the step and a resumed run repeats it.
 """
 from dataclasses import dataclass
 
@@ -47,6 +53,18 @@ class Config:
     refresh_interval: int = 200    # T
     bias_correction: bool = True
     side: str = "auto"             # "auto" | "left" (project rows) | "right" (project columns)
+    weight_dtype: str = "f32"      # "f32" | "bf16": storage type of W
+    state_dtype: str = "f32"       # "f32" | "bf16": storage type of M^R, V^R
+
+
+def stored(x, dtype):
+    """x as it reads back after being stored in `dtype`: unchanged for "f32" (the oracle keeps
+    fp64 there), the nearest bfloat16 (ties to even) of its binary32 value for "bf16"."""
+    if dtype == "f32":
+        return x
+    if dtype != "bf16":
+        raise ValueError("unknown storage type %r" % (dtype,))
+    return gauss.round_to_bf16(np.asarray(x, dtype=np.float64).astype(np.float32)).astype(np.float64)
 
 
 class TensorState:
@@ -75,11 +93,17 @@ def init_state(cfg, rows, cols):
     return TensorState(cfg.rank, n)
 
 
-def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None):
+def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt_moments=None):
     """One optimizer step on one tensor.  W, G: float64 arrays (rows x cols); W is updated in
     place and also returned.  t is the 1-based step.  P, if given, replaces the generated
     r x m projection INCLUDING its 1/sqrt(r) (used by tests to inject a hand-set matrix).
-    Returns a dict with the intermediate quantities (R, R~, s, colsq, norm, c).
+    adopt_moments, if given, is a function (M_exact, V_exact) -> (M, V) called right after the
+    moment update; what it returns becomes the stored state and feeds the rest of the step.
+    Parity tests of the bfloat16 state use it to check the other side's rounding of each moment
+    and then to continue from that side's decisions (a rounding taken one way on a value that
+    sits near a tie is as correct as the other; everything downstream must follow one of them).
+    Returns a dict with the intermediate quantities (R, R~, s, colsq, norm, c, and the values
+    before storage rounding: M_exact, V_exact, W_exact).
     """
     rows, cols = G.shape
     left = is_left(rows, cols, cfg.side)
@@ -99,8 +123,12 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None):
         R = np.asarray(P, dtype=np.float64) @ Gm
 
     # Step 2: low-rank moments and the Adam-normalised low-rank gradient.
-    state.M = cfg.beta1 * state.M + (1.0 - cfg.beta1) * R
-    state.V = cfg.beta2 * state.V + (1.0 - cfg.beta2) * R * R
+    M_exact = cfg.beta1 * state.M + (1.0 - cfg.beta1) * R
+    V_exact = cfg.beta2 * state.V + (1.0 - cfg.beta2) * R * R
+    if adopt_moments is None:
+        state.M, state.V = stored(M_exact, cfg.state_dtype), stored(V_exact, cfg.state_dtype)
+    else:
+        state.M, state.V = adopt_moments(M_exact, V_exact)
     if cfg.bias_correction:
         bc1 = 1.0 - cfg.beta1 ** t
         bc2 = 1.0 - cfg.beta2 ** t
@@ -132,8 +160,10 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None):
     U = cfg.scale * c * (Gm * s[None, :])         # the scaled gradient, m x n
     if not left:
         U = U.T
-    W -= lr * U + lr * cfg.weight_decay * W
-    return {"R": R, "Rt": Rt, "s": s, "colsq": colsq, "norm": norm, "c": c, "left": left}
+    W_exact = W - (lr * U + lr * cfg.weight_decay * W)
+    W[...] = stored(W_exact, cfg.weight_dtype)
+    return {"R": R, "Rt": Rt, "s": s, "colsq": colsq, "norm": norm, "c": c, "left": left,
+            "M_exact": M_exact, "V_exact": V_exact, "W_exact": W_exact}
 
 
 def state_elements(cfg, shapes):

@@ -399,3 +399,109 @@ def test_state_size_matches_table_1_and_the_7b_figure():
     assert mini == sum(2 * max(s) + 2 for s in shapes)
     assert float(g["mini_scale_squared"]) == 128 and int(g["refresh_interval"]) == apollo.Config(rank=1).refresh_interval
     assert apollo.Config(rank=1).nl_gamma == float(g["nl_gamma"])
+
+
+# ----------------------------------------------------------------------------- bfloat16 storage
+def _is_bf16(x):
+    b = np.asarray(x, dtype=np.float32).view(np.uint32)
+    return np.all(np.asarray(x, dtype=np.float32).astype(np.float64) == x) and not np.any(b & 0xFFFF)
+
+
+def test_stored_rounds_to_nearest_even_bfloat16():
+    # 1 + 2^-8 is halfway between 1 and 1 + 2^-7: ties go to the even mantissa (1); 1 + 3 * 2^-8
+    # is halfway between 1 + 2^-7 (odd) and 1 + 2^-6 (even)
+    x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -(1.0 + 2.0 ** -8),
+                  3.140625, 1e-30, 0.0])
+    got = apollo.stored(x, "bf16")
+    assert list(got[:5]) == [1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -1.0, 3.140625]
+    assert got[6] == 0.0 and abs(got[5] - 1e-30) <= 1e-30 * 2.0 ** -8
+    assert _is_bf16(got)
+    assert apollo.stored(x, "f32") is x
+    with pytest.raises(ValueError):
+        apollo.stored(x, "fp8")
+
+
+def test_bf16_storage_equals_f32_when_every_result_is_representable():
+    """Powers of two everywhere: betas 0.5 / 0.75, P and G small integers, lr a power of two --
+    every moment and every weight is a bfloat16 number, so the two storage types must agree bit
+    for bit over several steps (the rounding is the only difference between them)."""
+    P = np.array([[1.0, 0.0, 1.0]])
+    G = np.array([[2.0, 4.0, 0.0, 1.0], [1.0, 1.0, 1.0, 1.0], [2.0, 0.0, 4.0, 1.0]])
+    out = {}
+    for dt in ("f32", "bf16"):
+        cfg = _cfg(rank=1, beta1=0.5, beta2=0.75, eps=0.0, nl_gamma=0.0, weight_dtype=dt, state_dtype=dt)
+        st = apollo.init_state(cfg, 3, 4)
+        W = np.zeros((3, 4))
+        # one step only for W: s is not a power of two in general, W after the step is rounded
+        info = apollo.step(cfg, st, W, G, 1, 0.0, P=P)
+        out[dt] = (st.M.copy(), st.V.copy(), info["s"].copy())
+        info2 = apollo.step(cfg, st, W, 2 * G, 2, 0.0, P=P)
+        out[dt] += (st.M.copy(), st.V.copy())
+    for a, b in zip(out["f32"], out["bf16"]):
+        assert np.array_equal(a, b)
+    assert _is_bf16(out["bf16"][0]) and _is_bf16(out["bf16"][3])
+
+
+def test_bf16_moments_are_rounded_when_stored_and_the_factor_uses_the_stored_values():
+    P = np.array([[1.0]])
+    # R = G; beta1 = 0.5: M = R / 2 = 1 + 2^-8 -> tie -> stored 1; V = R^2 / 4 (beta2 = 0.75)
+    R = 2.0 + 2.0 ** -7
+    G = np.array([[R, 3.0]])
+    cfg = _cfg(rank=1, beta1=0.5, beta2=0.75, eps=0.0, nl_gamma=0.0, bias_correction=False,
+               state_dtype="bf16")
+    st = apollo.init_state(cfg, 1, 2)
+    info = apollo.step(cfg, st, np.zeros((1, 2)), G, 1, 0.0, P=P)
+    assert info["M_exact"][0, 0] == 1.0 + 2.0 ** -8 and st.M[0, 0] == 1.0
+    v_exact = R * R / 4
+    assert info["V_exact"][0, 0] == v_exact
+    v_st = float(apollo.stored(np.array([v_exact]), "bf16")[0])
+    assert st.V[0, 0] == v_st and v_st != v_exact
+    # s_0 = |M / sqrt(V)| / |R| from the STORED moments
+    assert info["s"][0] == pytest.approx((1.0 / math.sqrt(v_st)) / R, rel=1e-15)
+    assert info["s"][0] != pytest.approx(((1.0 + 2.0 ** -8) / math.sqrt(v_exact)) / R, rel=1e-6)
+    # f32 storage keeps the exact values
+    cfg32 = _cfg(rank=1, beta1=0.5, beta2=0.75, eps=0.0, nl_gamma=0.0, bias_correction=False)
+    st32 = apollo.init_state(cfg32, 1, 2)
+    apollo.step(cfg32, st32, np.zeros((1, 2)), G, 1, 0.0, P=P)
+    assert st32.M[0, 0] == 1.0 + 2.0 ** -8
+
+
+def test_adopt_moments_replaces_the_stored_state_and_feeds_the_rest_of_the_step():
+    P = np.array([[1.0]])
+    G = np.array([[2.0, 1.0]])
+    cfg = _cfg(rank=1, beta1=0.5, beta2=0.75, eps=0.0, nl_gamma=0.0, bias_correction=False)
+    st = apollo.init_state(cfg, 1, 2)
+    seen = {}
+
+    def adopt(M_exact, V_exact):
+        seen["M"], seen["V"] = M_exact.copy(), V_exact.copy()
+        return 2.0 * M_exact, V_exact
+
+    info = apollo.step(cfg, st, np.zeros((1, 2)), G, 1, 0.0, P=P, adopt_moments=adopt)
+    assert np.array_equal(seen["M"], [[1.0, 0.5]]) and np.array_equal(seen["V"], [[1.0, 0.25]])
+    assert np.array_equal(st.M, [[2.0, 1.0]])
+    # R~ = M / sqrt(V) = 2 (both channels), s = 2 / |R|
+    assert np.allclose(info["s"], [1.0, 2.0])
+
+
+def test_bf16_weights_round_after_the_update_and_small_updates_vanish():
+    P = np.array([[1.0]])
+    G = np.array([[1.0, 1.0]])
+    cfg = _cfg(rank=1, beta1=0.0, beta2=0.0, eps=0.0, nl_gamma=0.0, weight_dtype="bf16")
+    # first step: R~ = sign(R) = 1, s = 1: update lr * G
+    W = np.array([[1.0, 1.0]])
+    st = apollo.init_state(cfg, 1, 2)
+    info = apollo.step(cfg, st, W, G, 1, 2.0 ** -7, P=P)
+    assert np.array_equal(info["W_exact"], [[1.0 - 2.0 ** -7] * 2]) and np.array_equal(W, info["W_exact"])
+    # an update below half an ulp of the stored weight (2^-9 at 1.0, going down: ulp 2^-8) is lost
+    W = np.array([[1.0, 1.0]])
+    st = apollo.init_state(cfg, 1, 2)
+    info = apollo.step(cfg, st, W, G, 1, 2.0 ** -11, P=P)
+    assert info["W_exact"][0, 0] == 1.0 - 2.0 ** -11 and np.array_equal(W, [[1.0, 1.0]])
+    # decay and update are rounded once, together
+    cfg2 = _cfg(rank=1, beta1=0.0, beta2=0.0, eps=0.0, nl_gamma=0.0, weight_dtype="bf16", weight_decay=0.5)
+    W = np.array([[1.0, 1.0]])
+    st = apollo.init_state(cfg2, 1, 2)
+    info = apollo.step(cfg2, st, W, G, 1, 2.0 ** -9, P=P)
+    assert info["W_exact"][0, 0] == 1.0 - 2.0 ** -9 - 2.0 ** -10      # 1 - 3 * 2^-10
+    assert W[0, 0] == 1.0 - 2.0 ** -8                                 # nearest bf16 below 1 (spacing 2^-8): 3/4 of the way
