@@ -54,20 +54,24 @@ def make_cfg(A, wl, seed=20241205):
     mode = A.APOLLO_TENSOR if wl.mode == "tensor" else A.APOLLO_CHANNEL
     return A.ApolloConfig(rank=wl.rank, mode=mode, seed=seed, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
                           scale=wl.scale, weight_decay=wl.weight_decay, nl_gamma=wl.nl_gamma,
-                          refresh_interval=wl.refresh_interval, bias_correction=1, side=A.APOLLO_SIDE_AUTO, reserved=0)
+                          refresh_interval=wl.refresh_interval, bias_correction=1, side=A.APOLLO_SIDE_AUTO,
+                          weight_dtype=A.APOLLO_BF16 if str(wl.weight_dtype) == "torch.bfloat16" else A.APOLLO_F32,
+                          state_dtype=A.APOLLO_BF16 if str(wl.state_dtype) == "torch.bfloat16" else A.APOLLO_F32, reserved=0)
 
 
 def algorithmic_work(wl):
     """Per step and per phase: bytes the method itself has to move (and matrix-core flops)."""
     import torch
     gb = 2 if wl.grad_dtype == torch.bfloat16 else 4
+    wb = 2 if wl.weight_dtype == torch.bfloat16 else 4     # W is read and written
+    sb = 2 if wl.state_dtype == torch.bfloat16 else 4      # M and V are read and written
     params = wl.n_params
     chan = sum(max(s) for s in wl.shapes)                 # sum of channel counts n
     return {
         "projection": {"bytes": gb * params, "flops": 2.0 * wl.rank * params},
-        "adam_norms": {"bytes": 16.0 * wl.rank * chan, "flops": 0.0},
-        "update": {"bytes": (gb + 8.0) * params, "flops": 0.0},
-        "total_bytes": (2 * gb + 8.0) * params + 16.0 * wl.rank * chan,
+        "adam_norms": {"bytes": 4.0 * sb * wl.rank * chan, "flops": 0.0},
+        "update": {"bytes": (gb + 2.0 * wb) * params, "flops": 0.0},
+        "total_bytes": (2 * gb + 2.0 * wb) * params + 4.0 * sb * wl.rank * chan,
     }
 
 
@@ -86,7 +90,7 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev):
     rc, ms, n = A.apollo_profile_read(st.handle)
     assert rc == 0 and n == steps, (rc, n)
     A.apollo_profile_enable(st.handle, False)
-    finite = all(bool(torch.isfinite(w).all()) for w in weights[:7])
+    finite = all(bool(torch.isfinite(w.float()).all()) for w in weights[:7])
     state_bytes, ws_bytes = st.state.numel(), st.workspace.numel()
     st.close()
     del st
@@ -212,7 +216,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama7b_mini")
-    ap.add_argument("--also", default="llama7b_r256", help="second variant on the same shapes ('' = none)")
+    ap.add_argument("--also", default="llama7b_r256,llama7b_mini_bf16,llama7b_r256_bf16",
+                    help="further variants on the same shapes, comma separated ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-adamw-rest", action="store_true",
                     help="skip the element-wise AdamW launch on the non-projected parameters")
@@ -253,15 +258,21 @@ def main():
     grads = WL.make_grads(wl, 1, dev)
     torch.cuda.synchronize()
     main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev)
-    also = None
-    if args.also:
-        wl2 = WL.workload(args.also)
+    also = []
+    cur_wdt = wl.weight_dtype
+    for name in [a for a in args.also.split(",") if a]:
+        wl2 = WL.workload(name)
         assert wl2.shapes == wl.shapes and wl2.grad_dtype == wl.grad_dtype
+        if wl2.weight_dtype != cur_wdt:          # other weight type: the same values, stored in it
+            del weights
+            torch.cuda.empty_cache()
+            weights = WL.make_weights(wl2, dev)
+            cur_wdt = wl2.weight_dtype
         r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev)
-        also = {"workload": describe(wl2), "value": r2["value"], "unit": "params/s", "ms_per_step": r2["ms_per_step"],
-                "phase_ms": r2["phase_ms"], "roofline": r2["roofline"],
-                "whole_step_hbm_frac": r2["whole_step_hbm_frac"], "projection_roofline": r2["projection_roofline"],
-                "finite": r2["finite"]}
+        also.append({"workload": describe(wl2), "value": r2["value"], "unit": "params/s", "ms_per_step": r2["ms_per_step"],
+                     "phase_ms": r2["phase_ms"], "roofline": r2["roofline"],
+                     "whole_step_hbm_frac": r2["whole_step_hbm_frac"],
+                     "projection_roofline": r2["projection_roofline"], "finite": r2["finite"]})
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(A, WL, torch, wl, weights, grads)
@@ -286,9 +297,11 @@ def main():
 
 
 def describe(wl):
-    return ("%s: %d matrices (%s), %s gradients ~ %s(%g), fp32 W/M/V, %s rank %d, alpha %.4g, T %d"
+    short = lambda dt: "bf16" if str(dt) == "torch.bfloat16" else "fp32"
+    return ("%s: %d matrices (%s), %s gradients ~ %s(%g), %s W, %s M/V, %s rank %d, alpha %.4g, T %d"
             % (wl.name, len(wl.shapes), ", ".join("%dx%d" % s for s in sorted(set(wl.shapes))),
-               str(wl.grad_dtype).replace("torch.", ""), wl.grad_kind, wl.grad_scale,
+               str(wl.grad_dtype).replace("torch.", ""), wl.grad_kind, wl.grad_scale, short(wl.weight_dtype),
+               short(wl.state_dtype),
                "APOLLO-Mini tensor-wise" if wl.mode == "tensor" else "APOLLO channel-wise", wl.rank, wl.scale,
                wl.refresh_interval))
 

@@ -55,7 +55,8 @@ enum {
                                2^31 or more elements in one tensor                             */
 };
 
-/* gradient element type (W, M^R, V^R and all factors are fp32) */
+/* element types: of the gradient (per tensor), of W and of M^R, V^R (per configuration);
+   all factors and the stored norm are fp32 */
 enum { APOLLO_F32 = 0, APOLLO_BF16 = 1 };
 /* granularity of the scaling factor: APOLLO (Eq. 4) or APOLLO-Mini (Section 4.2) */
 enum { APOLLO_CHANNEL = 0, APOLLO_TENSOR = 1 };
@@ -64,7 +65,7 @@ enum { APOLLO_CHANNEL = 0, APOLLO_TENSOR = 1 };
 enum { APOLLO_SIDE_AUTO = 0, APOLLO_SIDE_LEFT = 1, APOLLO_SIDE_RIGHT = 2 };
 /* selectors of apollo_debug_get */
 enum {
-  APOLLO_DBG_M = 0,     /* M^R, r x n fp32, channel index contiguous                          */
+  APOLLO_DBG_M = 0,     /* M^R, r x n, channel index contiguous; always delivered as fp32      */
   APOLLO_DBG_V = 1,     /* V^R, r x n fp32                                                    */
   APOLLO_DBG_S = 2,     /* scaling factor of the last step: n fp32 (channel) or 1 fp32 (tensor) */
   APOLLO_DBG_NORM = 3,  /* stored norm ||alpha G diag(s)||_F after limiting, 1 fp32            */
@@ -91,18 +92,28 @@ typedef struct {
   int32_t refresh_interval; /* T >= 1: a new P is drawn when (step-1) % T == 0                 */
   int32_t bias_correction;  /* 1 = Adam's bias correction (default), 0 = literal Section 4.1   */
   int32_t side;             /* APOLLO_SIDE_*                                                   */
+  int32_t weight_dtype;     /* APOLLO_F32 (0, default) or APOLLO_BF16: element type of every W  */
+  int32_t state_dtype;      /* APOLLO_F32 (0, default) or APOLLO_BF16: element type of M^R, V^R */
   int32_t reserved;         /* set to 0                                                        */
 } apollo_config_t;
 
+/* Storage in bfloat16 (the paper trains "in BF16 data format" and sizes the state at 2 bytes per
+ * element, Table 3, without giving a rounding rule): arithmetic is fp32; a quantity kept in
+ * bfloat16 is rounded to nearest, ties to even, when it is stored, and whatever is computed after
+ * that uses the stored value (R~ is formed from the rounded moments), so the state alone
+ * determines the rest of the step.  An update smaller than half a unit in the last place of a
+ * bfloat16 weight is lost; that is a property of the format, not of this library. */
+
 typedef struct {
-  void* w;        /* DEVICE, fp32, rows x cols, 16-byte aligned, updated in place              */
+  void* w;        /* DEVICE, weight_dtype (fp32 by default), rows x cols, 16-byte aligned,
+                     updated in place                                                          */
   const void* g;  /* DEVICE, grad_dtype, rows x cols, 16-byte aligned, read only               */
 } apollo_tensor_t;
 
 /* Bytes of optimizer state for the tensor list (Table 1: 2nr + 2 scalars per tensor, here
  * 2nr moments + 1 norm, the seed being in the config), 0 on invalid arguments.
  * Layout, stable and meant for checkpointing: per tensor, in list order, each block starting
- * on a 256-byte boundary: M^R[r][n] fp32, V^R[r][n] fp32, prev_norm fp32. */
+ * on a 256-byte boundary: M^R[r][n], V^R[r][n] (state_dtype: fp32 or bf16), prev_norm fp32. */
 size_t apollo_state_bytes(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n_tensors);
 
 /* Byte offsets of one tensor's M^R, V^R and prev_norm inside the state buffer.  Any of the

@@ -27,7 +27,8 @@ class ApolloConfig(C.Structure):
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("scale", C.c_float), ("weight_decay", C.c_float), ("nl_gamma", C.c_float),
                 ("refresh_interval", C.c_int32), ("bias_correction", C.c_int32),
-                ("side", C.c_int32), ("reserved", C.c_int32)]
+                ("side", C.c_int32), ("weight_dtype", C.c_int32), ("state_dtype", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class ApolloTensor(C.Structure):
@@ -320,8 +321,9 @@ class ApolloStepper:
         self.weights = list(weights)
         self.grads = list(grads)
         self.shapes = []
+        wdt = torch.bfloat16 if cfg.weight_dtype == APOLLO_BF16 else torch.float32
         for w, g in zip(self.weights, self.grads):
-            assert w.dtype == torch.float32 and w.dim() == 2 and w.is_contiguous() and g.is_contiguous()
+            assert w.dtype == wdt and w.dim() == 2 and w.is_contiguous() and g.is_contiguous()
             assert g.shape == w.shape and g.dtype in (torch.float32, torch.bfloat16)
             self.shapes.append((w.shape[0], w.shape[1], APOLLO_BF16 if g.dtype == torch.bfloat16 else APOLLO_F32))
         sb = apollo_state_bytes(cfg, self.shapes)

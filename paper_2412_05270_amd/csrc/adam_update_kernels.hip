@@ -13,7 +13,42 @@ namespace apollo {
 // a fixed order, then the channels of the block are reduced to four block partials.  No
 // atomics: results are run-to-run identical.  M^R, V^R and R are streamed (non-temporal).
 // ---------------------------------------------------------------------------------------------
-template <int VEC>
+// VEC consecutive elements of a moment array at element index idx, as floats; the array is fp32
+// or bfloat16 (SB16).  Streamed (non-temporal).  idx is a multiple of VEC and the arrays are
+// aligned so that the VEC elements form one naturally aligned access.
+template <int VEC, bool SB16>
+__device__ __forceinline__ float __attribute__((ext_vector_type(VEC))) load_state(const APOLLO_GLOBAL void* base, size_t idx) {
+  typedef float vec_t __attribute__((ext_vector_type(VEC)));
+  if constexpr (!SB16) {
+    return __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(reinterpret_cast<const APOLLO_GLOBAL float*>(base) + idx));
+  } else if constexpr (VEC == 4) {
+    const u32x2_t h = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x2_t*>(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(base) + idx));
+    vec_t v = {__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xFFFF0000u), __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xFFFF0000u)};
+    return v;
+  } else {
+    static_assert(VEC == 1 || VEC == 4, "VEC");
+    vec_t v = {bf16_bits_to_f32(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(base)[idx])};
+    return v;
+  }
+}
+
+// The values are already bfloat16 numbers when SB16 (rounded by the caller): the store truncates.
+template <int VEC, bool SB16>
+__device__ __forceinline__ void store_state(APOLLO_GLOBAL void* base, size_t idx, float __attribute__((ext_vector_type(VEC))) v) {
+  typedef float vec_t __attribute__((ext_vector_type(VEC)));
+  if constexpr (!SB16) {
+    __builtin_nontemporal_store(v, reinterpret_cast<APOLLO_GLOBAL vec_t*>(reinterpret_cast<APOLLO_GLOBAL float*>(base) + idx));
+  } else if constexpr (VEC == 4) {
+    u32x2_t h;
+    h.x = (__float_as_uint(v[0]) >> 16) | (__float_as_uint(v[1]) & 0xFFFF0000u);
+    h.y = (__float_as_uint(v[2]) >> 16) | (__float_as_uint(v[3]) & 0xFFFF0000u);
+    __builtin_nontemporal_store(h, reinterpret_cast<APOLLO_GLOBAL u32x2_t*>(reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base) + idx));
+  } else {
+    reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base)[idx] = (uint16_t)(__float_as_uint(v[0]) >> 16);
+  }
+}
+
+template <int VEC, bool SB16>
 __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
   typedef float vec_t __attribute__((ext_vector_type(VEC)));
   __shared__ float red_a[3][64 * VEC], red_b[3][64 * VEC];
@@ -36,10 +71,10 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
       vec_t Rv[2], mo[2], vo[2];
       Rv[0] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx0));
       Rv[1] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx1));
-      mo[0] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.M + idx0));
-      mo[1] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.M + idx1));
-      vo[0] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.V + idx0));
-      vo[1] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.V + idx1));
+      mo[0] = load_state<VEC, SB16>(d.M, idx0);
+      mo[1] = load_state<VEC, SB16>(d.M, idx1);
+      vo[0] = load_state<VEC, SB16>(d.V, idx0);
+      vo[1] = load_state<VEC, SB16>(d.V, idx1);
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         if (h == 1 && !two) break;
@@ -53,8 +88,12 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           const float Re = Rv[h][e];
-          const float me = __builtin_fmaf(sp.beta1, mo[h][e], sp.omb1 * Re);
-          const float ve = __builtin_fmaf(sp.beta2, vo[h][e], sp.omb2 * (Re * Re));
+          float me = __builtin_fmaf(sp.beta1, mo[h][e], sp.omb1 * Re);
+          float ve = __builtin_fmaf(sp.beta2, vo[h][e], sp.omb2 * (Re * Re));
+          if (SB16) {   // bfloat16 state: round now, and form R~ from what is stored
+            me = bf16_bits_to_f32(f32_to_bf16_bits(me));
+            ve = bf16_bits_to_f32(f32_to_bf16_bits(ve));
+          }
           // hardware square root and reciprocal (1 ulp each) instead of the correctly rounded
           // sequences: 3 instead of ~50 instructions per element of a kernel that otherwise only
           // streams; the error (~3e-7 relative) is far below the fp32 rounding of the sums it enters
@@ -64,8 +103,8 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
           mn[e] = me;
           vn[e] = ve;
         }
-        __builtin_nontemporal_store(mn, reinterpret_cast<APOLLO_GLOBAL vec_t*>(d.M + idx));
-        __builtin_nontemporal_store(vn, reinterpret_cast<APOLLO_GLOBAL vec_t*>(d.V + idx));
+        store_state<VEC, SB16>(d.M, idx, mn);
+        store_state<VEC, SB16>(d.V, idx, vn);
       }
     }
   }
@@ -113,13 +152,16 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
   }
 }
 
-hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, const StepParams& sp, hipStream_t st) {
+hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
+                             hipStream_t st) {
   if ((n & 3) == 0) {
     dim3 grid((unsigned)((n / 4 + 63) / 64), (unsigned)count, 1);
-    hipLaunchKernelGGL(adam_norms_kernel<4>, grid, dim3(256), 0, st, d_descs, sp);
+    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true>), grid, dim3(256), 0, st, d_descs, sp);
+    else hipLaunchKernelGGL((adam_norms_kernel<4, false>), grid, dim3(256), 0, st, d_descs, sp);
   } else {
     dim3 grid((unsigned)((n + 63) / 64), (unsigned)count, 1);
-    hipLaunchKernelGGL(adam_norms_kernel<1>, grid, dim3(256), 0, st, d_descs, sp);
+    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<1, true>), grid, dim3(256), 0, st, d_descs, sp);
+    else hipLaunchKernelGGL((adam_norms_kernel<1, false>), grid, dim3(256), 0, st, d_descs, sp);
   }
   return hipGetLastError();
 }
@@ -207,88 +249,158 @@ __device__ __forceinline__ uint32_t fastdiv(uint32_t v, const FastDiv& f) {
   return (t + ((v - t) >> 1)) >> f.shift;
 }
 
-// ALIGNED: cols % 4 == 0, so a quad never straddles a row and the tensor has no ragged tail.
-template <bool BF16, int CHAN, bool ALIGNED>
+// EPT consecutive elements (4 or 8) of a bf16 or fp32 array at element index e0 (a multiple of EPT;
+// the group is naturally aligned), as floats, in 16-byte (8-byte for four bf16) accesses.
+template <int EPT, bool IS_BF16, bool NT>
+__device__ __forceinline__ void load_elems(const APOLLO_GLOBAL void* base, size_t e0, float (&out)[EPT]) {
+  if constexpr (IS_BF16) {
+    uint32_t h[EPT / 2];
+    if constexpr (EPT == 8) {
+      const APOLLO_GLOBAL u32x4_t* p = reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(base) + e0);
+      const u32x4_t v = NT ? __builtin_nontemporal_load(p) : *p;
+      h[0] = v.x; h[1] = v.y; h[2] = v.z; h[3] = v.w;
+    } else {
+      const APOLLO_GLOBAL u32x2_t* p = reinterpret_cast<const APOLLO_GLOBAL u32x2_t*>(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(base) + e0);
+      const u32x2_t v = NT ? __builtin_nontemporal_load(p) : *p;
+      h[0] = v.x; h[1] = v.y;
+    }
+#pragma unroll
+    for (int i = 0; i < EPT / 2; ++i) {
+      out[2 * i] = __uint_as_float(h[i] << 16);
+      out[2 * i + 1] = __uint_as_float(h[i] & 0xFFFF0000u);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < EPT / 4; ++i) {
+      const APOLLO_GLOBAL f32x4_t* p = reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(reinterpret_cast<const APOLLO_GLOBAL float*>(base) + e0) + i;
+      const f32x4_t v = NT ? __builtin_nontemporal_load(p) : *p;
+      out[4 * i] = v.x; out[4 * i + 1] = v.y; out[4 * i + 2] = v.z; out[4 * i + 3] = v.w;
+    }
+  }
+}
+
+// The counterpart store (non-temporal); bf16: one rounding to nearest even of each fp32 value.
+template <int EPT, bool IS_BF16>
+__device__ __forceinline__ void store_elems(APOLLO_GLOBAL void* base, size_t e0, const float (&v)[EPT]) {
+  if constexpr (IS_BF16) {
+    uint32_t h[EPT / 2];
+#pragma unroll
+    for (int i = 0; i < EPT / 2; ++i) h[i] = f32_to_bf16_bits(v[2 * i]) | (f32_to_bf16_bits(v[2 * i + 1]) << 16);
+    if constexpr (EPT == 8)
+      __builtin_nontemporal_store(mk_u4(h[0], h[1], h[2], h[3]),
+                                  reinterpret_cast<APOLLO_GLOBAL u32x4_t*>(reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base) + e0));
+    else {
+      u32x2_t w2 = {h[0], h[1]};
+      __builtin_nontemporal_store(w2, reinterpret_cast<APOLLO_GLOBAL u32x2_t*>(reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base) + e0));
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < EPT / 4; ++i)
+      __builtin_nontemporal_store(mk_f4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]),
+                                  reinterpret_cast<APOLLO_GLOBAL f32x4_t*>(reinterpret_cast<APOLLO_GLOBAL float*>(base) + e0) + i);
+  }
+}
+
+// One thread = EPT consecutive elements (4; 8 when both W and G are bfloat16, so that every access
+// is still 16 bytes per lane).  ALIGNED: cols % EPT == 0, so a group never straddles a row and the
+// tensor has no ragged tail.
+template <bool BF16, int CHAN, bool ALIGNED, bool WB16, int EPT>
 __global__ __launch_bounds__(256) void update_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
                                                      FastDiv div_cols) {
   const TensorView d(descs[blockIdx.y]);
   const uint32_t cols = (uint32_t)d.cols;
   const size_t total = (size_t)d.rows * (size_t)d.cols;
-  const size_t q = (size_t)blockIdx.x * 256u + threadIdx.x;      // quad index
-  const size_t e0 = q * 4u;
+  const size_t e0 = ((size_t)blockIdx.x * 256u + threadIdx.x) * (size_t)EPT;
   if (e0 >= total) return;
   const float coef = d.scal[0];
   const float decay = sp.lr_decay;
-  float k[4] = {coef, coef, coef, coef};
+  float k[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) k[e] = coef;
   if (CHAN != kChanNone) {
     uint32_t row = fastdiv((uint32_t)e0, div_cols);
     uint32_t col = (uint32_t)e0 - row * cols;
     if (ALIGNED) {
       if (CHAN == kChanCol) {
-        const f32x4_t sv = *reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(d.s + col);
-        k[0] *= sv.x; k[1] *= sv.y; k[2] *= sv.z; k[3] *= sv.w;
+        float sv[EPT];
+        load_elems<EPT, false, false>(d.s, col, sv);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) k[e] *= sv[e];
       } else {
         const float sr = d.s[row];
-        k[0] *= sr; k[1] *= sr; k[2] *= sr; k[3] *= sr;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) k[e] *= sr;
       }
     } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
+      for (int e = 0; e < EPT; ++e) {
         if (e0 + e < total) k[e] *= d.s[CHAN == kChanCol ? col : row];
         if (++col == cols) { col = 0; ++row; }
       }
     }
   }
-  if (ALIGNED || e0 + 4 <= total) {
-    float g[4];
-    if (BF16) {
-      const u32x2_t gv = reinterpret_cast<const APOLLO_GLOBAL u32x2_t*>(d.g)[q];
-      g[0] = __uint_as_float(gv.x << 16); g[1] = __uint_as_float(gv.x & 0xFFFF0000u);
-      g[2] = __uint_as_float(gv.y << 16); g[3] = __uint_as_float(gv.y & 0xFFFF0000u);
-    } else {
-      const f32x4_t gv = reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(d.g)[q];
-      g[0] = gv.x; g[1] = gv.y; g[2] = gv.z; g[3] = gv.w;
-    }
-    f32x4_t w = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(d.w) + q);
-    w.x = w.x - __builtin_fmaf(k[0], g[0], decay * w.x);
-    w.y = w.y - __builtin_fmaf(k[1], g[1], decay * w.y);
-    w.z = w.z - __builtin_fmaf(k[2], g[2], decay * w.z);
-    w.w = w.w - __builtin_fmaf(k[3], g[3], decay * w.w);
-    __builtin_nontemporal_store(w, reinterpret_cast<APOLLO_GLOBAL f32x4_t*>(d.w) + q);
+  if (ALIGNED || e0 + EPT <= total) {
+    float g[EPT], w[EPT];
+    load_elems<EPT, BF16, false>(d.g, e0, g);
+    load_elems<EPT, WB16, true>(d.w, e0, w);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) w[e] = w[e] - __builtin_fmaf(k[e], g[e], decay * w[e]);
+    store_elems<EPT, WB16>(d.w, e0, w);
   } else {
-    for (int e = 0; e < 4 && e0 + e < total; ++e) {     // ragged tail of an unaligned tensor
+    for (int e = 0; e < EPT && e0 + e < total; ++e) {     // ragged tail of an unaligned tensor
       const float g = BF16 ? bf16_bits_to_f32(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(d.g)[e0 + e])
                            : reinterpret_cast<const APOLLO_GLOBAL float*>(d.g)[e0 + e];
-      const float w = d.w[e0 + e];
-      d.w[e0 + e] = w - __builtin_fmaf(k[e], g, decay * w);
+      if (WB16) {
+        APOLLO_GLOBAL uint16_t* wp = reinterpret_cast<APOLLO_GLOBAL uint16_t*>(d.w) + e0 + e;
+        const float w = bf16_bits_to_f32(*wp);
+        *wp = (uint16_t)f32_to_bf16_bits(w - __builtin_fmaf(k[e], g, decay * w));
+      } else {
+        APOLLO_GLOBAL float* wp = reinterpret_cast<APOLLO_GLOBAL float*>(d.w) + e0 + e;
+        const float w = *wp;
+        *wp = w - __builtin_fmaf(k[e], g, decay * w);
+      }
     }
   }
 }
 
-template <bool BF16, int CHAN>
+template <bool BF16, int CHAN, bool WB16>
 static hipError_t launch_update_t(const TensorDesc* d_descs, int count, int rows, int cols, const StepParams& sp,
                                   hipStream_t st) {
-  const size_t quads = ((size_t)rows * cols + 3) / 4;
-  dim3 grid((unsigned)((quads + 255) / 256), (unsigned)count, 1);
   const FastDiv fd = make_fastdiv((uint32_t)cols);
+  const size_t total = (size_t)rows * cols;
+  if constexpr (BF16 && WB16) {
+    if ((cols & 7) == 0) {
+      dim3 grid((unsigned)((total / 8 + 255) / 256), (unsigned)count, 1);
+      hipLaunchKernelGGL((update_kernel<BF16, CHAN, true, WB16, 8>), grid, dim3(256), 0, st, d_descs, sp, fd);
+      return hipGetLastError();
+    }
+  }
+  const size_t quads = (total + 3) / 4;
+  dim3 grid((unsigned)((quads + 255) / 256), (unsigned)count, 1);
   if ((cols & 3) == 0)
-    hipLaunchKernelGGL((update_kernel<BF16, CHAN, true>), grid, dim3(256), 0, st, d_descs, sp, fd);
+    hipLaunchKernelGGL((update_kernel<BF16, CHAN, true, WB16, 4>), grid, dim3(256), 0, st, d_descs, sp, fd);
   else
-    hipLaunchKernelGGL((update_kernel<BF16, CHAN, false>), grid, dim3(256), 0, st, d_descs, sp, fd);
+    hipLaunchKernelGGL((update_kernel<BF16, CHAN, false, WB16, 4>), grid, dim3(256), 0, st, d_descs, sp, fd);
   return hipGetLastError();
 }
 
+template <bool BF16, bool WB16>
+static hipError_t launch_update_c(const TensorDesc* d_descs, int count, int rows, int cols, int chan,
+                                  const StepParams& sp, hipStream_t st) {
+  if (chan == kChanCol) return launch_update_t<BF16, kChanCol, WB16>(d_descs, count, rows, cols, sp, st);
+  if (chan == kChanRow) return launch_update_t<BF16, kChanRow, WB16>(d_descs, count, rows, cols, sp, st);
+  return launch_update_t<BF16, kChanNone, WB16>(d_descs, count, rows, cols, sp, st);
+}
+
 hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
-                         const StepParams& sp, hipStream_t st) {
+                         bool w_bf16, const StepParams& sp, hipStream_t st) {
   const int chan = sp.tensor_mode ? kChanNone : (left ? kChanCol : kChanRow);
   if (bf16) {
-    if (chan == kChanCol) return launch_update_t<true, kChanCol>(d_descs, count, rows, cols, sp, st);
-    if (chan == kChanRow) return launch_update_t<true, kChanRow>(d_descs, count, rows, cols, sp, st);
-    return launch_update_t<true, kChanNone>(d_descs, count, rows, cols, sp, st);
+    return w_bf16 ? launch_update_c<true, true>(d_descs, count, rows, cols, chan, sp, st)
+                  : launch_update_c<true, false>(d_descs, count, rows, cols, chan, sp, st);
   }
-  if (chan == kChanCol) return launch_update_t<false, kChanCol>(d_descs, count, rows, cols, sp, st);
-  if (chan == kChanRow) return launch_update_t<false, kChanRow>(d_descs, count, rows, cols, sp, st);
-  return launch_update_t<false, kChanNone>(d_descs, count, rows, cols, sp, st);
+  return w_bf16 ? launch_update_c<false, true>(d_descs, count, rows, cols, chan, sp, st)
+                : launch_update_c<false, false>(d_descs, count, rows, cols, chan, sp, st);
 }
 
 }  // namespace apollo

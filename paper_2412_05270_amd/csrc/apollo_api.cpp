@@ -73,6 +73,10 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     return fail(err, APOLLO_EINVAL, "betas must lie in [0, 1)");
   if (!(cfg->eps >= 0.f) || !(cfg->nl_gamma >= 0.f) || !std::isfinite(cfg->scale) || !std::isfinite(cfg->weight_decay))
     return fail(err, APOLLO_EINVAL, "eps / nl_gamma negative or scale / weight_decay not finite");
+  if ((cfg->weight_dtype != APOLLO_F32 && cfg->weight_dtype != APOLLO_BF16) ||
+      (cfg->state_dtype != APOLLO_F32 && cfg->state_dtype != APOLLO_BF16))
+    return fail(err, APOLLO_EUNSUPPORTED, "weight_dtype / state_dtype must be fp32 or bf16");
+  const size_t state_elem = cfg->state_dtype == APOLLO_BF16 ? 2 : sizeof(float);
 
   plan.t.resize(n);
   size_t st = 0;
@@ -111,7 +115,7 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
       t.n_slabs = sl;
     }
     t.k2_blocks = (t.n & 3) == 0 ? (t.n / 4 + 63) / 64 : (t.n + 63) / 64;   // blocks of adam_norms_kernel
-    const size_t rn = (size_t)cfg->rank * (size_t)t.n * sizeof(float);
+    const size_t rn = (size_t)cfg->rank * (size_t)t.n * state_elem;
     st = align_up(st);
     t.st_m = st;
     t.st_v = st + rn;
@@ -299,8 +303,8 @@ apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg, c
     const TensorPlan& t = h->plan.t[k];
     TensorDesc& d = h->desc[t.desc_index];
     std::memset(&d, 0, sizeof d);
-    d.M = reinterpret_cast<float*>(h->state + t.st_m);
-    d.V = reinterpret_cast<float*>(h->state + t.st_v);
+    d.M = h->state + t.st_m;
+    d.V = h->state + t.st_v;
     d.prev_norm = reinterpret_cast<float*>(h->state + t.st_norm);
     d.P = t.path == Path::kRank1 ? nullptr : static_cast<void*>(h->ws + t.ws_p);
     d.gpad = t.pad_g ? static_cast<void*>(h->ws + t.ws_gpad) : nullptr;
@@ -348,7 +352,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   if (changed) {
     for (int32_t k = 0; k < n; ++k) {
       TensorDesc& d = h->desc[h->plan.t[k].desc_index];
-      d.w = static_cast<float*>(tensors[k].w);
+      d.w = tensors[k].w;
       d.g = tensors[k].g;
       h->last[k] = tensors[k];
     }
@@ -399,7 +403,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   // (c) low-rank Adam moments, channel factors, block partial sums
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
-    e = launch_adam_norms(dd + g.first, g.count, g.n, sp, st);
+    e = launch_adam_norms(dd + g.first, g.count, g.n, h->cfg.state_dtype == APOLLO_BF16, sp, st);
     what = "moment update";
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[3], st);
@@ -412,7 +416,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   // (e) W update
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
-    e = launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, sp, st);
+    e = launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, h->cfg.weight_dtype == APOLLO_BF16, sp, st);
     what = "weight update";
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[5], st);
@@ -470,9 +474,10 @@ apollo_status_t apollo_debug_get(apollo_handle_t* h, int32_t tensor, int32_t wha
   const size_t rn = (size_t)h->cfg.rank * t.n * sizeof(float);
   const void* src = nullptr;
   size_t need = 0;
+  bool widen = false;     // the source is bfloat16 and is delivered as fp32
   switch (what) {
-    case APOLLO_DBG_M: src = h->state + t.st_m; need = rn; break;
-    case APOLLO_DBG_V: src = h->state + t.st_v; need = rn; break;
+    case APOLLO_DBG_M: src = h->state + t.st_m; need = rn; widen = h->cfg.state_dtype == APOLLO_BF16; break;
+    case APOLLO_DBG_V: src = h->state + t.st_v; need = rn; widen = h->cfg.state_dtype == APOLLO_BF16; break;
     case APOLLO_DBG_S:
       if (h->cfg.mode == APOLLO_TENSOR) { src = h->ws + t.ws_scal + 3 * sizeof(float); need = sizeof(float); }
       else { src = h->ws + t.ws_s; need = (size_t)t.n * sizeof(float); }
@@ -484,8 +489,10 @@ apollo_status_t apollo_debug_get(apollo_handle_t* h, int32_t tensor, int32_t wha
     default: return fail(h->err, APOLLO_EINVAL, "unknown selector %lld", what);
   }
   if (bytes != need) return fail(h->err, APOLLO_EINVAL, "selector %lld holds %lld bytes, %lld given", what, (long long)need, (long long)bytes);
-  const hipError_t e = hipMemcpyAsync(out, src, need, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(hip_stream));
-  if (e != hipSuccess) return hip_fail(h->err, e, "hipMemcpyAsync(debug)");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = widen ? launch_bf16_to_f32(static_cast<float*>(out), src, need / sizeof(float), st)
+                             : hipMemcpyAsync(out, src, need, hipMemcpyDeviceToDevice, st);
+  if (e != hipSuccess) return hip_fail(h->err, e, "copy (debug)");
   return APOLLO_OK;
 }
 

@@ -12,10 +12,10 @@ namespace apollo {
 // between steps.  m = projected (reduced) dimension, n = channel dimension (Algorithm 1 has
 // W in R^{m x n}, m <= n; `left` says whether m runs along the stored rows).
 struct TensorDesc {
-  float* w;            // rows x cols fp32, updated in place
+  void* w;             // rows x cols, fp32 or bf16, updated in place
   const void* g;       // rows x cols, bf16 or fp32
-  float* M;            // state: M^R, r x n
-  float* V;            // state: V^R, r x n
+  void* M;             // state: M^R, r x n, fp32 or bf16
+  void* V;             // state: V^R, r x n
   float* prev_norm;    // state: stored norm of the scaled gradient (limiter), 1 float
   void* P;             // scratch: unit-variance projection z, fragment-major (see p_index)
   void* gpad;          // scratch: copy of g with rows padded to ldg elements (16-byte aligned rows), or null
@@ -70,10 +70,10 @@ __device__ __forceinline__ APOLLO_GLOBAL T* gptr(T* p) {
 
 // A TensorDesc with its pointers typed as global memory; kernels build one from the table entry.
 struct TensorView {
-  APOLLO_GLOBAL float* w;
+  APOLLO_GLOBAL void* w;
   APOLLO_GLOBAL const void* g;
-  APOLLO_GLOBAL float* M;
-  APOLLO_GLOBAL float* V;
+  APOLLO_GLOBAL void* M;
+  APOLLO_GLOBAL void* V;
   APOLLO_GLOBAL float* prev_norm;
   APOLLO_GLOBAL void* P;
   APOLLO_GLOBAL void* gpad;
@@ -134,11 +134,12 @@ hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, i
 bool project_mfma_needs_padding(int rows, int cols, bool left);
 hipError_t launch_pad_gradient(const TensorDesc* d_descs, int count, int rows, int cols, int ldg, hipStream_t st);
 bool project_mfma_supported(int rows, int cols, bool left, bool bf16, int r);
-hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, const StepParams& sp,
+hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
                              hipStream_t st);
 hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepParams& sp, hipStream_t st);
 hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
-                         const StepParams& sp, hipStream_t st);
+                         bool w_bf16, const StepParams& sp, hipStream_t st);
+hipError_t launch_bf16_to_f32(float* dst, const void* src, size_t count, hipStream_t st);
 hipError_t launch_philox_words(const uint32_t* ctr, uint32_t k0, uint32_t k1, uint32_t* out,
                                int64_t count, hipStream_t st);
 hipError_t launch_gauss_parts(uint32_t first, int64_t count, float* radius, float* cosv, float* sinv,

@@ -170,6 +170,20 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
   return hipGetLastError();
 }
 
+// bf16 -> fp32, element by element (debug view of a bfloat16 state).
+__global__ __launch_bounds__(256) void bf16_to_f32_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * 256u + threadIdx.x; i < count; i += (size_t)gridDim.x * 256u)
+    dst[i] = bf16_bits_to_f32(src[i]);
+}
+
+hipError_t launch_bf16_to_f32(float* dst, const void* src, size_t count, hipStream_t st) {
+  if (count == 0) return hipSuccess;
+  size_t blocks = (count + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, dst, static_cast<const uint16_t*>(src), count);
+  return hipGetLastError();
+}
+
 // Plain copy of n16 16-byte words, one per thread (reference kernel of known traffic for
 // calibrating hardware byte counters).
 __global__ __launch_bounds__(256) void copy_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst,

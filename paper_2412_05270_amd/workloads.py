@@ -38,6 +38,8 @@ class Workload:
     eps: float = 1e-8
     nl_gamma: float = 1.01
     weight_decay: float = 0.0
+    weight_dtype: torch.dtype = torch.float32   # storage type of W
+    state_dtype: torch.dtype = torch.float32    # storage type of the low-rank moments
     extra: dict = field(default_factory=dict)
 
     @property
@@ -65,6 +67,13 @@ def workload(name):
     if name == "llama7b_r256":
         return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=256,
                         steps=20)
+    if name == "llama7b_mini_bf16":      # the paper's all-bfloat16 setting: W and the moments in bf16
+        return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=1,
+                        mode="tensor", scale=MINI_SCALE, steps=20, weight_dtype=torch.bfloat16,
+                        state_dtype=torch.bfloat16)
+    if name == "llama7b_r256_bf16":
+        return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=256,
+                        steps=20, weight_dtype=torch.bfloat16, state_dtype=torch.bfloat16)
     if name == "llama13b_mini":
         return Workload(name, 5, llama_shapes(5120, 13824, 40), torch.bfloat16, "colscale", 1.0, rank=1,
                         mode="tensor", scale=MINI_SCALE, steps=5)
@@ -81,9 +90,11 @@ def _generator(device, seed):
 
 
 def make_weights(wl, device):
-    """fp32 weights ~ N(0, w_std^2), one tensor per shape, seeded by the configuration."""
+    """Weights ~ N(0, w_std^2) (drawn in fp32, stored in the workload's weight type), one tensor per
+    shape, seeded by the configuration."""
     gen = _generator(device, 1000 * wl.config_id)
-    return [torch.randn(s, generator=gen, device=device, dtype=torch.float32) * wl.w_std for s in wl.shapes]
+    return [(torch.randn(s, generator=gen, device=device, dtype=torch.float32) * wl.w_std).to(wl.weight_dtype)
+            for s in wl.shapes]
 
 
 def _one_grad(shape, wl, gen, device, structure_along_rows):

@@ -39,11 +39,14 @@ def make_configs(wl, seed=0x5EED5EED1234, side="auto", bias_correction=True):
     cfg = A.ApolloConfig(rank=wl.rank, mode=mode, seed=seed, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
                          scale=wl.scale, weight_decay=wl.weight_decay, nl_gamma=wl.nl_gamma,
                          refresh_interval=wl.refresh_interval, bias_correction=1 if bias_correction else 0,
-                         side=side_code, reserved=0)
+                         side=side_code, weight_dtype=A.APOLLO_BF16 if wl.weight_dtype == torch.bfloat16 else A.APOLLO_F32,
+                         state_dtype=A.APOLLO_BF16 if wl.state_dtype == torch.bfloat16 else A.APOLLO_F32, reserved=0)
     ocfg = O.Config(rank=wl.rank, mode=O.TENSOR if wl.mode == "tensor" else O.CHANNEL, seed=seed,
                     beta1=f32(wl.beta1), beta2=f32(wl.beta2), eps=f32(wl.eps), scale=f32(wl.scale),
                     weight_decay=f32(wl.weight_decay), nl_gamma=f32(wl.nl_gamma),
-                    refresh_interval=wl.refresh_interval, bias_correction=bias_correction, side=side)
+                    refresh_interval=wl.refresh_interval, bias_correction=bias_correction, side=side,
+                    weight_dtype="bf16" if wl.weight_dtype == torch.bfloat16 else "f32",
+                    state_dtype="bf16" if wl.state_dtype == torch.bfloat16 else "f32")
     return cfg, ocfg
 
 
@@ -63,6 +66,29 @@ def assert_close(name, got, ref, tol, extra_abs=0.0):
         k = int(np.argmax(err - bound))
         raise AssertionError("%s: %d of %d elements off; worst at flat %d: got %.9g ref %.9g (rms %.3g, tol %g)"
                              % (name, int(bad.sum()), ref.size, k, got.ravel()[k], ref.ravel()[k], rms, tol))
+
+
+def assert_rounds_within(name, got, exact, tol, extra_abs=0.0):
+    """For a quantity stored in bfloat16: `got` must consist of bfloat16 numbers, each of which is
+    the rounding of SOME value within the tolerance of the oracle's unrounded value `exact`.
+    Rounding is monotonic, so that is: stored(exact - d) <= got <= stored(exact + d), with
+    d = tol (|exact| + rms exact) + extra_abs.  (A value near a tie may round either way when
+    the two sides differ by an admissible error; both roundings are correct results.)"""
+    got = np.asarray(got, dtype=np.float64)
+    exact = np.asarray(exact, dtype=np.float64)
+    assert got.shape == exact.shape, (name, got.shape, exact.shape)
+    assert np.all(np.isfinite(got)), name + ": non-finite values"
+    assert np.array_equal(O.stored(got, "bf16"), got), name + ": not bfloat16 numbers"
+    rms = math.sqrt(float(np.mean(exact * exact))) if exact.size else 0.0
+    d = tol * (np.abs(exact) + rms) + extra_abs
+    lo, hi = O.stored(exact - d, "bf16"), O.stored(exact + d, "bf16")
+    bad = (got < lo) | (got > hi)
+    if np.any(bad):
+        k = int(np.argmax(bad))
+        raise AssertionError("%s: %d of %d elements outside the roundings of the admissible interval; first at flat %d: "
+                             "got %.9g, exact %.9g, interval rounds to [%.9g, %.9g]"
+                             % (name, int(bad.sum()), exact.size, k, got.ravel()[k], exact.ravel()[k],
+                                lo.ravel()[k], hi.ravel()[k]))
 
 
 def condition_factors(info, state, ocfg, t, tol):
@@ -122,6 +148,7 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
     bf16 = wl.grad_dtype == torch.bfloat16
     tol = TOL_BF16 if bf16 else TOL_F32
     cfg, ocfg = make_configs(wl, seed, side, bias_correction)
+    state_bf16, w_bf16 = wl.state_dtype == torch.bfloat16, wl.weight_dtype == torch.bfloat16
     weights = WL.make_weights(wl, device)
     grads = [torch.empty(s, dtype=wl.grad_dtype, device=device) for s in wl.shapes]
     stepper = A.ApolloStepper(cfg, weights, grads, device=device)
@@ -141,7 +168,20 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
             # term reads W, and the two trajectories differ by the admissible error of earlier steps
             W_or[i] = before[i].copy()
             W_prev = before[i]
-            info = O.step(ocfg, states[i], W_or[i], G, t, lr32, tensor_id=i, grad_is_bf16=bf16)
+            tag = "%s tensor %d step %d " % (wl.name, i, t)
+            adopt = None
+            if state_bf16:
+                # bfloat16 moments: the library's roundings are checked against the oracle's unrounded
+                # values and then adopted, so that everything downstream follows the same decisions
+                M_gpu = to_host_f64(stepper.debug(i, A.APOLLO_DBG_M))
+                V_gpu = to_host_f64(stepper.debug(i, A.APOLLO_DBG_V))
+
+                def adopt(M_exact, V_exact, M_gpu=M_gpu, V_gpu=V_gpu, tag=tag, full=full):
+                    if full:
+                        assert_rounds_within(tag + "M", M_gpu, M_exact, tol)
+                        assert_rounds_within(tag + "V", V_gpu, V_exact, tol)
+                    return M_gpu, V_gpu
+            info = O.step(ocfg, states[i], W_or[i], G, t, lr32, tensor_id=i, grad_is_bf16=bf16, adopt_moments=adopt)
             hits += info["c"] < 1.0
             f_chan, f_norm = condition_factors(info, states[i], ocfg, t, tol)
             f_c = f_norm + f_norm_prev[i]
@@ -154,11 +194,11 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
             dw_bound = tol * f_dw * (np.abs(dw_ref) + rms_dw)
             if not full:
                 continue
-            tag = "%s tensor %d step %d " % (wl.name, i, t)
             assert_close(tag + "R", to_host_f64(stepper.debug(i, A.APOLLO_DBG_R)), info["R"], tol)
             assert_close(tag + "colsq", to_host_f64(stepper.debug(i, A.APOLLO_DBG_COLSQ)), info["colsq"], tol)
-            assert_close(tag + "M", to_host_f64(stepper.debug(i, A.APOLLO_DBG_M)), states[i].M, tol)
-            assert_close(tag + "V", to_host_f64(stepper.debug(i, A.APOLLO_DBG_V)), states[i].V, tol)
+            if not state_bf16:
+                assert_close(tag + "M", to_host_f64(stepper.debug(i, A.APOLLO_DBG_M)), states[i].M, tol)
+                assert_close(tag + "V", to_host_f64(stepper.debug(i, A.APOLLO_DBG_V)), states[i].V, tol)
             s_gpu = to_host_f64(stepper.debug(i, A.APOLLO_DBG_S))
             s_ref = info["s"] if wl.mode == "channel" else info["s"][:1]
             f_s = f_chan if wl.mode == "channel" else f_chan[:1]
@@ -170,9 +210,14 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
             after = to_host_f64(weights[i])
             if float(c_gpu[0]) < 1.0 and not info["c"] < 1.0:         # only the GPU side limited (c ~ 1)
                 dw_bound = dw_bound + tol * f_c * (np.abs(dw_ref) + rms_dw)
-            assert_close(tag + "dW", after - before[i], dw_ref, 0.0,
-                         extra_abs=dw_bound + np.abs(after) * 2.0 ** -24)
-            assert_close(tag + "W", after, W_or[i], tol, extra_abs=dw_bound)
+            if w_bf16:
+                # bfloat16 weights: the stored weight must be a rounding of a value within the
+                # admissible error of the oracle's unrounded new weight
+                assert_rounds_within(tag + "W", after, info["W_exact"], 0.0, extra_abs=dw_bound + np.abs(after) * 2.0 ** -24)
+            else:
+                assert_close(tag + "dW", after - before[i], dw_ref, 0.0,
+                             extra_abs=dw_bound + np.abs(after) * 2.0 ** -24)
+                assert_close(tag + "W", after, W_or[i], tol, extra_abs=dw_bound)
         if progress:
             print("%s: step %d/%d compared" % (wl.name, t, steps), flush=True)
     stepper.close()

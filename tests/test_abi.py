@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _cfg(**kw):
     base = dict(rank=4, mode=A.APOLLO_CHANNEL, seed=1, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0,
                 weight_decay=0.0, nl_gamma=1.01, refresh_interval=200, bias_correction=1,
-                side=A.APOLLO_SIDE_AUTO, reserved=0)
+                side=A.APOLLO_SIDE_AUTO, weight_dtype=A.APOLLO_F32, state_dtype=A.APOLLO_F32, reserved=0)
     base.update(kw)
     return A.ApolloConfig(**base)
 
@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(A.ApolloShape) == 24
-    assert C.sizeof(A.ApolloConfig) == 56
+    assert C.sizeof(A.ApolloConfig) == 64
     assert C.sizeof(A.ApolloTensor) == 16
     assert C.sizeof(A.ApolloFlatShape) == 16
     assert C.sizeof(A.ApolloAdamwConfig) == 24
@@ -93,6 +93,20 @@ def test_init_rejects_small_or_misaligned_buffers_without_touching_them():
     assert A.apollo_init(cfg, shapes, 264, sb, 512, wb)[0] == A.APOLLO_ESTATE
     assert A.apollo_init(cfg, shapes, None, sb, 512, wb)[0] == A.APOLLO_EINVAL
     assert A.apollo_init(None, shapes, 256, sb, 512, wb)[0] == A.APOLLO_EINVAL
+
+
+def test_storage_types_are_validated_and_size_the_state():
+    shapes = [(8, 20, A.APOLLO_F32)]
+    per32 = ((2 * 4 * 20 * 4 + 4) + 255) // 256 * 256
+    per16 = ((2 * 4 * 20 * 2 + 4) + 255) // 256 * 256
+    assert A.apollo_state_bytes(_cfg(rank=4), shapes) == per32
+    assert A.apollo_state_bytes(_cfg(rank=4, state_dtype=A.APOLLO_BF16), shapes) == per16
+    assert A.apollo_state_bytes(_cfg(rank=4, weight_dtype=A.APOLLO_BF16), shapes) == per32
+    cfg = _cfg(rank=4, state_dtype=A.APOLLO_BF16)
+    assert A.apollo_state_offsets(cfg, shapes, 0) == (0, 0, 4 * 20 * 2, 2 * 4 * 20 * 2)
+    assert A.apollo_state_bytes(_cfg(state_dtype=2), shapes) == 0
+    assert A.apollo_state_bytes(_cfg(weight_dtype=-1), shapes) == 0
+    assert "dtype" in A.apollo_last_error()
 
 
 def test_null_handle_calls_fail_cleanly():
