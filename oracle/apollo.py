@@ -55,6 +55,9 @@ class Config:
     side: str = "auto"             # "auto" | "left" (project rows) | "right" (project columns)
     weight_dtype: str = "f32"      # "f32" | "bf16": storage type of W
     state_dtype: str = "f32"       # "f32" | "bf16": storage type of M^R, V^R
+    projection: str = "random"     # "random" (Algorithm 1) | "identity": the structured channel-wise
+                                   # rule of Section 3.2 itself, full-rank moments of G (P = I, rank
+                                   # ignored: r = m), the reference the low-rank factors approximate
 
 
 def stored(x, dtype):
@@ -89,8 +92,9 @@ def is_left(rows, cols, side="auto"):
 
 
 def init_state(cfg, rows, cols):
-    n = cols if is_left(rows, cols, cfg.side) else rows
-    return TensorState(cfg.rank, n)
+    left = is_left(rows, cols, cfg.side)
+    n, m = (cols, rows) if left else (rows, cols)
+    return TensorState(m if cfg.projection == "identity" else cfg.rank, n)
 
 
 def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt_moments=None):
@@ -111,8 +115,14 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt
     m, n = Gm.shape
     r = cfg.rank
 
-    # Step 1: gradient into the low-rank space.
-    if P is None:
+    # Step 1: gradient into the low-rank space (or, Section 3.2, no projection at all).
+    if cfg.projection == "identity":
+        if P is not None:
+            raise ValueError("a hand-set P and projection='identity' exclude each other")
+        R = Gm.copy()
+    elif cfg.projection != "random":
+        raise ValueError("unknown projection %r" % (cfg.projection,))
+    elif P is None:
         epoch = (t - 1) // cfg.refresh_interval
         key = (cfg.seed, tensor_id, epoch, r, m, bool(grad_is_bf16))
         if state.z_key != key:                    # "if t mod T = 0: P_t <- N_seed(0, 1/r)"
@@ -171,6 +181,7 @@ def state_elements(cfg, shapes):
     2n + 2 for Mini at r = 1, n the larger dimension; the "+2" are the seed and the norm)."""
     total = 0
     for rows, cols in shapes:
-        n = cols if is_left(rows, cols, cfg.side) else rows
-        total += 2 * n * cfg.rank + 2
+        left = is_left(rows, cols, cfg.side)
+        n, m = (cols, rows) if left else (rows, cols)
+        total += 2 * n * (m if cfg.projection == "identity" else cfg.rank) + 2
     return total

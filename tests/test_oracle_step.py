@@ -505,3 +505,77 @@ def test_bf16_weights_round_after_the_update_and_small_updates_vanish():
     info = apollo.step(cfg2, st, W, G, 1, 2.0 ** -9, P=P)
     assert info["W_exact"][0, 0] == 1.0 - 2.0 ** -9 - 2.0 ** -10      # 1 - 3 * 2^-10
     assert W[0, 0] == 1.0 - 2.0 ** -8                                 # nearest bf16 below 1 (spacing 2^-8): 3/4 of the way
+
+
+# ----------------------------------------------------------------------------- no projection (Section 3.2)
+def test_identity_projection_is_the_structured_rule_of_section_3_2_by_brute_force():
+    """Full-rank moments of G, G~ = M^ / (sqrt(V^) + eps), s_j = ||G~[:, j]|| / ||G[:, j]|| (Eq. 2),
+    update G diag(s): scalar loops on a small tensor, both orientations."""
+    rng = np.random.default_rng(8)
+    for rows, cols in ((3, 5), (5, 3)):
+        cfg = _cfg(projection="identity", rank=99, nl_gamma=0.0, eps=1e-6)
+        left = rows <= cols
+        m, n = (rows, cols) if left else (cols, rows)
+        st = apollo.init_state(cfg, rows, cols)
+        assert st.M.shape == (m, n)
+        W = rng.normal(size=(rows, cols))
+        Wb = [list(r) for r in W]
+        M = [[0.0] * cols for _ in range(rows)]
+        V = [[0.0] * cols for _ in range(rows)]
+        for t in (1, 2, 3):
+            G = rng.normal(size=(rows, cols))
+            apollo.step(cfg, st, W, G, t, 0.1)
+            Gt = [[0.0] * cols for _ in range(rows)]
+            for i in range(rows):
+                for j in range(cols):
+                    M[i][j] = 0.9 * M[i][j] + 0.1 * G[i, j]
+                    V[i][j] = 0.999 * V[i][j] + 0.001 * G[i, j] ** 2
+                    Gt[i][j] = (M[i][j] / (1 - 0.9 ** t)) / (math.sqrt(V[i][j] / (1 - 0.999 ** t)) + 1e-6)
+            for ch in range(n):
+                idx = [(i, ch) for i in range(rows)] if left else [(ch, i) for i in range(cols)]
+                num = math.sqrt(sum(Gt[i][j] ** 2 for i, j in idx))
+                den = math.sqrt(sum(G[i, j] ** 2 for i, j in idx))
+                for i, j in idx:
+                    Wb[i][j] -= 0.1 * (num / den) * G[i, j]
+        np.testing.assert_allclose(W, np.array(Wb), rtol=1e-12)
+
+
+def test_identity_projection_on_a_single_row_is_textbook_adam():
+    """m = 1: every channel holds one element, s_j = |G~_j| / |G_j|, so G diag(s) = sign(G) |G~|:
+    element-wise AdamW as long as each element's gradient keeps its sign (the first moment then has
+    the sign of the gradient); checked against the separate AdamW oracle (pinned against torch)."""
+    from oracle import adamw
+    rng = np.random.default_rng(9)
+    cfg = _cfg(projection="identity", nl_gamma=0.0, weight_decay=0.05)
+    acfg = adamw.Config(beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.05)
+    W = rng.normal(size=(1, 17))
+    Wa = W.copy().reshape(-1)
+    st, sa = apollo.init_state(cfg, 1, 17), adamw.init_state(17)
+    sign = np.sign(rng.normal(size=(1, 17)))
+    for t in range(1, 6):
+        G = sign * np.abs(rng.normal(size=(1, 17)))
+        apollo.step(cfg, st, W, G, t, 0.01)
+        adamw.step(acfg, sa, Wa, G.reshape(-1), t, 0.01)
+    np.testing.assert_allclose(W.reshape(-1), Wa, rtol=1e-12)
+    # with a sign flip the structured rule follows the gradient's sign, Adam the moment's
+    G = -sign * 1e-3
+    W2, Wa2 = W.copy(), Wa.copy()
+    apollo.step(cfg, st, W2, G, 6, 0.01)
+    adamw.step(acfg, sa, Wa2, G.reshape(-1), 6, 0.01)
+    assert np.all(np.sign(W2 - W * (1 - 0.01 * 0.05)) == -np.sign(G))
+    assert np.all(np.sign(Wa2 - Wa * (1 - 0.01 * 0.05)) == np.sign(G).reshape(-1))
+
+
+def test_identity_projection_equals_a_hand_set_identity_matrix_and_counts_full_rank_state():
+    rng = np.random.default_rng(10)
+    G = rng.normal(size=(4, 6))
+    a, b = _cfg(projection="identity"), _cfg(rank=4)
+    Wa, Wb = np.ones((4, 6)), np.ones((4, 6))
+    sa, sb = apollo.init_state(a, 4, 6), apollo.init_state(b, 4, 6)
+    for t in (1, 2):
+        ia = apollo.step(a, sa, Wa, G * t, t, 0.1)
+        ib = apollo.step(b, sb, Wb, G * t, t, 0.1, P=np.eye(4))
+    assert np.array_equal(Wa, Wb) and np.array_equal(ia["s"], ib["s"])
+    assert apollo.state_elements(a, [(4, 6), (6, 4)]) == 2 * (2 * 4 * 6 + 2)
+    with pytest.raises(ValueError):
+        apollo.step(a, sa, Wa, G, 3, 0.1, P=np.eye(4))
