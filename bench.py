@@ -56,7 +56,8 @@ def make_cfg(A, wl, seed=20241205):
                           scale=wl.scale, weight_decay=wl.weight_decay, nl_gamma=wl.nl_gamma,
                           refresh_interval=wl.refresh_interval, bias_correction=1, side=A.APOLLO_SIDE_AUTO,
                           weight_dtype=A.APOLLO_BF16 if str(wl.weight_dtype) == "torch.bfloat16" else A.APOLLO_F32,
-                          state_dtype=A.APOLLO_BF16 if str(wl.state_dtype) == "torch.bfloat16" else A.APOLLO_F32, reserved=0)
+                          state_dtype=A.APOLLO_BF16 if str(wl.state_dtype) == "torch.bfloat16" else A.APOLLO_F32,
+                          projection=A.APOLLO_PROJ_IDENTITY if wl.projection == "identity" else A.APOLLO_PROJ_RANDOM)
 
 
 def algorithmic_work(wl):
@@ -67,6 +68,13 @@ def algorithmic_work(wl):
     sb = 2 if wl.state_dtype == torch.bfloat16 else 4      # M and V are read and written
     params = wl.n_params
     chan = sum(max(s) for s in wl.shapes)                 # sum of channel counts n
+    if wl.projection == "identity":   # no projection: the moment pass reads G and the full-size M, V
+        return {
+            "projection": {"bytes": 0.0, "flops": 0.0},
+            "adam_norms": {"bytes": (gb + 4.0 * sb) * params, "flops": 0.0},
+            "update": {"bytes": (gb + 2.0 * wb) * params, "flops": 0.0},
+            "total_bytes": (2 * gb + 2.0 * wb + 4.0 * sb) * params,
+        }
     return {
         "projection": {"bytes": gb * params, "flops": 2.0 * wl.rank * params},
         "adam_norms": {"bytes": 4.0 * sb * wl.rank * chan, "flops": 0.0},
@@ -302,7 +310,8 @@ def describe(wl):
             % (wl.name, len(wl.shapes), ", ".join("%dx%d" % s for s in sorted(set(wl.shapes))),
                str(wl.grad_dtype).replace("torch.", ""), wl.grad_kind, wl.grad_scale, short(wl.weight_dtype),
                short(wl.state_dtype),
-               "APOLLO-Mini tensor-wise" if wl.mode == "tensor" else "APOLLO channel-wise", wl.rank, wl.scale,
+               ("full-rank moments, " if wl.projection == "identity" else "")
+               + ("APOLLO-Mini tensor-wise" if wl.mode == "tensor" else "APOLLO channel-wise"), wl.rank, wl.scale,
                wl.refresh_interval))
 
 

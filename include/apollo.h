@@ -63,6 +63,9 @@ enum { APOLLO_CHANNEL = 0, APOLLO_TENSOR = 1 };
 /* which dimension is projected away: AUTO = the smaller one (Algorithm 1's m <= n);
    LEFT = rows (R = P G, channels are columns); RIGHT = columns (R = G P^T, channels are rows) */
 enum { APOLLO_SIDE_AUTO = 0, APOLLO_SIDE_LEFT = 1, APOLLO_SIDE_RIGHT = 2 };
+/* where the moments live: in the random low-rank space of Algorithm 1, or (Section 3.2) in the
+   full space */
+enum { APOLLO_PROJ_RANDOM = 0, APOLLO_PROJ_IDENTITY = 1 };
 /* selectors of apollo_debug_get */
 enum {
   APOLLO_DBG_M = 0,     /* M^R, r x n, channel index contiguous; always delivered as fp32      */
@@ -94,8 +97,16 @@ typedef struct {
   int32_t side;             /* APOLLO_SIDE_*                                                   */
   int32_t weight_dtype;     /* APOLLO_F32 (0, default) or APOLLO_BF16: element type of every W  */
   int32_t state_dtype;      /* APOLLO_F32 (0, default) or APOLLO_BF16: element type of M^R, V^R */
-  int32_t reserved;         /* set to 0                                                        */
+  int32_t projection;       /* APOLLO_PROJ_RANDOM (0, default) or APOLLO_PROJ_IDENTITY          */
 } apollo_config_t;
+
+/* APOLLO_PROJ_IDENTITY: no projection at all -- the structured channel-wise rule of Section 3.2
+ * (Eq. 2) itself, with full-rank Adam moments of G: G~ = M^ / (sqrt(V^) + eps), s_j = ||G~[:,j]|| /
+ * ||G[:,j]|| (or one factor per tensor with APOLLO_TENSOR), limiter and update as in Algorithm 1.
+ * It is the reference the low-rank factors approximate (Theorem 4.1's ratio sqrt(r/n) is measured
+ * against it).  `rank` is ignored (r = m, P = I, no 1/sqrt(r)); the moments have the tensor's own
+ * rows x cols row-major layout, which is also what apollo_debug_get delivers for M and V;
+ * APOLLO_DBG_R is not available.  State: 2 rows cols elements + 1 norm per tensor. */
 
 /* Storage in bfloat16 (the paper trains "in BF16 data format" and sizes the state at 2 bytes per
  * element, Table 3, without giving a rounding rule): arithmetic is fp32; a quantity kept in

@@ -14,6 +14,7 @@ APOLLO_OK, APOLLO_EINVAL, APOLLO_ENOMEM, APOLLO_ESTATE, APOLLO_EHIP, APOLLO_EUNS
 APOLLO_F32, APOLLO_BF16 = 0, 1
 APOLLO_CHANNEL, APOLLO_TENSOR = 0, 1
 APOLLO_SIDE_AUTO, APOLLO_SIDE_LEFT, APOLLO_SIDE_RIGHT = 0, 1, 2
+APOLLO_PROJ_RANDOM, APOLLO_PROJ_IDENTITY = 0, 1
 (APOLLO_DBG_M, APOLLO_DBG_V, APOLLO_DBG_S, APOLLO_DBG_NORM, APOLLO_DBG_C, APOLLO_DBG_R,
  APOLLO_DBG_COLSQ) = range(7)
 
@@ -28,7 +29,7 @@ class ApolloConfig(C.Structure):
                 ("scale", C.c_float), ("weight_decay", C.c_float), ("nl_gamma", C.c_float),
                 ("refresh_interval", C.c_int32), ("bias_correction", C.c_int32),
                 ("side", C.c_int32), ("weight_dtype", C.c_int32), ("state_dtype", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("projection", C.c_int32)]
 
 
 class ApolloTensor(C.Structure):
@@ -359,7 +360,10 @@ class ApolloStepper:
         torch = self.torch
         n, _ = self.channels(tensor)
         r = self.cfg.rank
-        if what in (APOLLO_DBG_M, APOLLO_DBG_V, APOLLO_DBG_R):
+        if what in (APOLLO_DBG_M, APOLLO_DBG_V) and self.cfg.projection == APOLLO_PROJ_IDENTITY:
+            # without a projection the moments have the tensor's own layout
+            out = torch.empty(self.shapes[tensor][:2], dtype=torch.float32, device=self.state.device)
+        elif what in (APOLLO_DBG_M, APOLLO_DBG_V, APOLLO_DBG_R):
             out = torch.empty((r, n), dtype=torch.float32, device=self.state.device)
         elif what == APOLLO_DBG_COLSQ or (what == APOLLO_DBG_S and self.cfg.mode == APOLLO_CHANNEL):
             out = torch.empty(n, dtype=torch.float32, device=self.state.device)

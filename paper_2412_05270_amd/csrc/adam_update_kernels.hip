@@ -48,13 +48,17 @@ __device__ __forceinline__ void store_state(APOLLO_GLOBAL void* base, size_t idx
   }
 }
 
-template <int VEC, bool SB16>
+// RSRC: where R comes from.  0: the projection's scratch R (fp32).  1 / 2: no projection (Section 3.2,
+// full-rank moments): "R" is the gradient itself, fp32 / bf16, r = m rows, and the squared channel
+// norm of G is b_j; only for tensors whose rows are projected (channels = stored columns), so that
+// the gradient has R's own layout.
+template <int VEC, bool SB16, int RSRC>
 __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
   typedef float vec_t __attribute__((ext_vector_type(VEC)));
   __shared__ float red_a[3][64 * VEC], red_b[3][64 * VEC];
   __shared__ float blk[4][64];
   const TensorView d(descs[blockIdx.y]);
-  const int r = sp.r, n = d.n, n_slabs = d.n_slabs;
+  const int r = RSRC == 0 ? sp.r : d.m, n = d.n, n_slabs = RSRC == 0 ? d.n_slabs : 1;
   const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int j0 = (blockIdx.x * 64 + c) * VEC;
   const size_t slab_stride = (size_t)r * (size_t)n;
@@ -69,8 +73,13 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
       const size_t idx0 = (size_t)kk * n + j0;
       const size_t idx1 = two ? idx0 + (size_t)4 * n : idx0;
       vec_t Rv[2], mo[2], vo[2];
-      Rv[0] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx0));
-      Rv[1] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx1));
+      if constexpr (RSRC == 0) {
+        Rv[0] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx0));
+        Rv[1] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx1));
+      } else {
+        Rv[0] = load_state<VEC, RSRC == 2>(d.g, idx0);
+        Rv[1] = load_state<VEC, RSRC == 2>(d.g, idx1);
+      }
       mo[0] = load_state<VEC, SB16>(d.M, idx0);
       mo[1] = load_state<VEC, SB16>(d.M, idx1);
       vo[0] = load_state<VEC, SB16>(d.V, idx0);
@@ -123,7 +132,8 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
       const int j = j0 + e;
       const float ae = ((a[e] + red_a[0][c * VEC + e]) + red_a[1][c * VEC + e]) + red_a[2][c * VEC + e];
       const float be = ((b[e] + red_b[0][c * VEC + e]) + red_b[1][c * VEC + e]) + red_b[2][c * VEC + e];
-      float csq = d.colsq[j];
+      float csq = RSRC == 0 ? d.colsq[j] : be;
+      if (RSRC != 0) d.colsq[j] = be;
       if (n_slabs > 1) {
         for (int sl = 1; sl < n_slabs; ++sl) csq += d.colsq[(size_t)sl * n + j];
         d.colsq[j] = csq;
@@ -152,16 +162,126 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
   }
 }
 
-hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
-                             hipStream_t st) {
+template <int RSRC>
+static hipError_t launch_adam_norms_t(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
+                                      hipStream_t st) {
   if ((n & 3) == 0) {
     dim3 grid((unsigned)((n / 4 + 63) / 64), (unsigned)count, 1);
-    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true>), grid, dim3(256), 0, st, d_descs, sp);
-    else hipLaunchKernelGGL((adam_norms_kernel<4, false>), grid, dim3(256), 0, st, d_descs, sp);
+    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
+    else hipLaunchKernelGGL((adam_norms_kernel<4, false, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
   } else {
     dim3 grid((unsigned)((n + 63) / 64), (unsigned)count, 1);
-    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<1, true>), grid, dim3(256), 0, st, d_descs, sp);
-    else hipLaunchKernelGGL((adam_norms_kernel<1, false>), grid, dim3(256), 0, st, d_descs, sp);
+    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<1, true, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
+    else hipLaunchKernelGGL((adam_norms_kernel<1, false, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
+                             hipStream_t st) {
+  return launch_adam_norms_t<0>(d_descs, count, n, state_bf16, sp, st);
+}
+
+// ---------------------------------------------------------------------------------------------
+// No projection (Section 3.2, Eq. 2), channels = stored rows (a tensor with rows > cols): the
+// moments have the gradient's own layout, one wave per channel walks its row of G, M and V with
+// 16-byte accesses and reduces a_j = sum G~^2, b_j = sum G^2 over the lanes (butterfly, fixed
+// order).  One block = four channels; it leaves the same four partial sums as adam_norms_kernel.
+// ---------------------------------------------------------------------------------------------
+template <bool GB16, bool SB16>
+__global__ __launch_bounds__(256) void adam_identity_rows_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
+  __shared__ float blk[4][4];
+  const TensorView d(descs[blockIdx.y]);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int m = d.m, n = d.n;
+  const int j = blockIdx.x * 4 + w;
+  float a = 0.f, b = 0.f;
+  auto element = [&](float g, float mo, float vo, float& mn, float& vn) {
+    float me = __builtin_fmaf(sp.beta1, mo, sp.omb1 * g);
+    float ve = __builtin_fmaf(sp.beta2, vo, sp.omb2 * (g * g));
+    if (SB16) {
+      me = bf16_bits_to_f32(f32_to_bf16_bits(me));
+      ve = bf16_bits_to_f32(f32_to_bf16_bits(ve));
+    }
+    const float rt = (me * sp.inv_bc1) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(ve * sp.inv_bc2) + sp.eps);
+    a = __builtin_fmaf(rt, rt, a);
+    b = __builtin_fmaf(g, g, b);
+    mn = me;
+    vn = ve;
+  };
+  if (j < n) {
+    const size_t base = (size_t)j * m;
+    if ((m & 3) == 0) {
+      typedef float vec_t __attribute__((ext_vector_type(4)));
+      for (int i = lane * 4; i < m; i += 256) {
+        const vec_t g = load_state<4, GB16>(d.g, base + i);
+        const vec_t mo = load_state<4, SB16>(d.M, base + i);
+        const vec_t vo = load_state<4, SB16>(d.V, base + i);
+        vec_t mn, vn;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float me, ve;
+          element(g[e], mo[e], vo[e], me, ve);
+          mn[e] = me;
+          vn[e] = ve;
+        }
+        store_state<4, SB16>(d.M, base + i, mn);
+        store_state<4, SB16>(d.V, base + i, vn);
+      }
+    } else {
+      typedef float vec_t __attribute__((ext_vector_type(1)));
+      for (int i = lane; i < m; i += 64) {
+        const vec_t g = load_state<1, GB16>(d.g, base + i);
+        const vec_t mo = load_state<1, SB16>(d.M, base + i);
+        const vec_t vo = load_state<1, SB16>(d.V, base + i);
+        vec_t mn, vn;
+        float me, ve;
+        element(g[0], mo[0], vo[0], me, ve);
+        mn[0] = me;
+        vn[0] = ve;
+        store_state<1, SB16>(d.M, base + i, mn);
+        store_state<1, SB16>(d.V, base + i, vn);
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    a += __shfl_xor(a, off, 64);
+    b += __shfl_xor(b, off, 64);
+  }
+  if (lane == 0) {
+    float sj = 0.f;
+    if (j < n) {
+      sj = (b > 0.f) ? __builtin_sqrtf(a) / __builtin_sqrtf(b) : 0.f;
+      d.s[j] = sj;
+      d.colsq[j] = b;
+    } else {
+      a = b = 0.f;
+    }
+    blk[0][w] = a;
+    blk[1][w] = b;
+    blk[2][w] = b;
+    blk[3][w] = sj * sj * b;
+  }
+  __syncthreads();
+  if (threadIdx.x < 4) {
+    const int q = threadIdx.x;
+    d.partials[(size_t)blockIdx.x * 4 + q] = ((blk[q][0] + blk[q][1]) + blk[q][2]) + blk[q][3];
+  }
+}
+
+hipError_t launch_adam_identity(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool g_bf16,
+                                bool state_bf16, const StepParams& sp, hipStream_t st) {
+  if (left)
+    return g_bf16 ? launch_adam_norms_t<2>(d_descs, count, cols, state_bf16, sp, st)
+                  : launch_adam_norms_t<1>(d_descs, count, cols, state_bf16, sp, st);
+  dim3 grid((unsigned)((rows + 3) / 4), (unsigned)count, 1);
+  if (g_bf16) {
+    if (state_bf16) hipLaunchKernelGGL((adam_identity_rows_kernel<true, true>), grid, dim3(256), 0, st, d_descs, sp);
+    else hipLaunchKernelGGL((adam_identity_rows_kernel<true, false>), grid, dim3(256), 0, st, d_descs, sp);
+  } else {
+    if (state_bf16) hipLaunchKernelGGL((adam_identity_rows_kernel<false, true>), grid, dim3(256), 0, st, d_descs, sp);
+    else hipLaunchKernelGGL((adam_identity_rows_kernel<false, false>), grid, dim3(256), 0, st, d_descs, sp);
   }
   return hipGetLastError();
 }

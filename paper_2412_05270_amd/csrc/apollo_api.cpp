@@ -23,10 +23,11 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 thread_local std::string g_last_error;
 
-enum class Path { kRank1, kMfma, kGeneric };
+enum class Path { kRank1, kMfma, kGeneric, kIdentity };   // kIdentity: no projection (Section 3.2)
 
 struct TensorPlan {
   int32_t rows, cols, m, n, m8;
+  int32_t r;                                                    // rows of the moments: the rank, or m without projection
   bool left, bf16;
   Path path;
   int32_t n_slabs, k2_blocks;
@@ -65,7 +66,10 @@ int fail(std::string& dst, int code, const char* fmt, long long a = 0, long long
 int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n, Plan& plan, std::string& err) {
   if (!cfg || !shapes) return fail(err, APOLLO_EINVAL, "null config or shape list");
   if (n < 1 || n > kMaxTensors) return fail(err, APOLLO_EINVAL, "n_tensors %lld outside 1..65535", n);
-  if (cfg->rank < 1) return fail(err, APOLLO_EINVAL, "rank %lld < 1", cfg->rank);
+  if (cfg->projection != APOLLO_PROJ_RANDOM && cfg->projection != APOLLO_PROJ_IDENTITY)
+    return fail(err, APOLLO_EINVAL, "unknown projection %lld", cfg->projection);
+  const bool identity = cfg->projection == APOLLO_PROJ_IDENTITY;
+  if (!identity && cfg->rank < 1) return fail(err, APOLLO_EINVAL, "rank %lld < 1", cfg->rank);
   if (cfg->mode != APOLLO_CHANNEL && cfg->mode != APOLLO_TENSOR) return fail(err, APOLLO_EINVAL, "unknown mode %lld", cfg->mode);
   if (cfg->side < APOLLO_SIDE_AUTO || cfg->side > APOLLO_SIDE_RIGHT) return fail(err, APOLLO_EINVAL, "unknown side %lld", cfg->side);
   if (cfg->refresh_interval < 1) return fail(err, APOLLO_EINVAL, "refresh_interval %lld < 1", cfg->refresh_interval);
@@ -97,9 +101,12 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     t.m = t.left ? t.rows : t.cols;
     t.n = t.left ? t.cols : t.rows;
     t.m8 = (t.m + 7) & ~7;
-    if (cfg->rank > t.m)
+    if (!identity && cfg->rank > t.m)
       return fail(err, APOLLO_EINVAL, "tensor %lld: rank %lld exceeds the projected dimension %lld", k, cfg->rank, t.m);
-    if (cfg->rank == 1 && project_rank1_supported(t.rows, t.cols, t.left, t.bf16))
+    t.r = identity ? t.m : cfg->rank;
+    if (identity)
+      t.path = Path::kIdentity;
+    else if (cfg->rank == 1 && project_rank1_supported(t.rows, t.cols, t.left, t.bf16))
       t.path = Path::kRank1;
     else if (project_mfma_supported(t.rows, t.cols, t.left, t.bf16, cfg->rank))
       t.path = Path::kMfma;
@@ -115,7 +122,8 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
       t.n_slabs = sl;
     }
     t.k2_blocks = (t.n & 3) == 0 ? (t.n / 4 + 63) / 64 : (t.n + 63) / 64;   // blocks of adam_norms_kernel
-    const size_t rn = (size_t)cfg->rank * (size_t)t.n * state_elem;
+    if (identity && !t.left) t.k2_blocks = (t.n + 3) / 4;                 // of adam_identity_rows_kernel
+    const size_t rn = (size_t)t.r * (size_t)t.n * state_elem;
     st = align_up(st);
     t.st_m = st;
     t.st_v = st + rn;
@@ -157,11 +165,11 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
   for (int32_t k = 0; k < n; ++k) {
     TensorPlan& t = plan.t[k];
     t.ws_p = ws;
-    if (t.path != Path::kRank1) ws = align_up(ws + (size_t)cfg->rank * t.m8 * (t.bf16 ? 2 : 4));
+    if (t.path != Path::kRank1 && t.path != Path::kIdentity) ws = align_up(ws + (size_t)cfg->rank * t.m8 * (t.bf16 ? 2 : 4));
     t.ws_gpad = ws;
     if (t.pad_g) ws = align_up(ws + (size_t)t.rows * t.ldg * 2);
     t.ws_r = ws;
-    ws = align_up(ws + (size_t)t.n_slabs * cfg->rank * t.n * sizeof(float));
+    if (t.path != Path::kIdentity) ws = align_up(ws + (size_t)t.n_slabs * cfg->rank * t.n * sizeof(float));
     t.ws_colsq = ws;
     ws = align_up(ws + (size_t)t.n_slabs * t.n * sizeof(float));
     t.ws_s = ws;
@@ -208,7 +216,7 @@ StepParams make_step_params(const apollo_config_t& c, int64_t step, float lr) {
   sp.epoch = (uint32_t)(((uint64_t)(step - 1) / (uint64_t)c.refresh_interval) & 0xffffffffu);
   sp.r = c.rank;
   sp.tensor_mode = c.mode == APOLLO_TENSOR;
-  sp.rsqrt_r = (float)(1.0 / std::sqrt((double)c.rank));
+  sp.rsqrt_r = c.rank > 0 ? (float)(1.0 / std::sqrt((double)c.rank)) : 1.0f;
   sp.beta1 = c.beta1;
   sp.beta2 = c.beta2;
   sp.omb1 = 1.0f - c.beta1;
@@ -306,7 +314,7 @@ apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg, c
     d.M = h->state + t.st_m;
     d.V = h->state + t.st_v;
     d.prev_norm = reinterpret_cast<float*>(h->state + t.st_norm);
-    d.P = t.path == Path::kRank1 ? nullptr : static_cast<void*>(h->ws + t.ws_p);
+    d.P = (t.path == Path::kRank1 || t.path == Path::kIdentity) ? nullptr : static_cast<void*>(h->ws + t.ws_p);
     d.gpad = t.pad_g ? static_cast<void*>(h->ws + t.ws_gpad) : nullptr;
     d.ldg = t.ldg;
     d.R = reinterpret_cast<float*>(h->ws + t.ws_r);
@@ -379,7 +387,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   // (a) the transient copy of P for the groups that read it from scratch
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
-    if (g.path == Path::kRank1) continue;
+    if (g.path == Path::kRank1 || g.path == Path::kIdentity) continue;
     e = launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, st);
     what = "projection fill";
     if (e == hipSuccess && g.pad_g) {
@@ -392,6 +400,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
     what = "projection";
+    if (g.path == Path::kIdentity) continue;
     if (g.path == Path::kRank1)
       e = launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sp, st);
     else if (g.path == Path::kMfma)
@@ -403,7 +412,10 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   // (c) low-rank Adam moments, channel factors, block partial sums
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
-    e = launch_adam_norms(dd + g.first, g.count, g.n, h->cfg.state_dtype == APOLLO_BF16, sp, st);
+    if (g.path == Path::kIdentity)
+      e = launch_adam_identity(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, h->cfg.state_dtype == APOLLO_BF16, sp, st);
+    else
+      e = launch_adam_norms(dd + g.first, g.count, g.n, h->cfg.state_dtype == APOLLO_BF16, sp, st);
     what = "moment update";
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[3], st);
@@ -458,6 +470,7 @@ apollo_status_t apollo_debug_fill_projection(apollo_handle_t* h, int32_t tensor,
   if (!out) return fail(h->err, APOLLO_EINVAL, "null output");
   if (step < 1) return fail(h->err, APOLLO_EINVAL, "step %lld < 1", step);
   if (dtype != APOLLO_F32 && dtype != APOLLO_BF16) return fail(h->err, APOLLO_EUNSUPPORTED, "dtype %lld", dtype);
+  if (h->cfg.projection == APOLLO_PROJ_IDENTITY) return fail(h->err, APOLLO_EINVAL, "this configuration has no projection matrix");
   const StepParams sp = make_step_params(h->cfg, step, 0.f);
   const hipError_t e = launch_fill_projection_rowmajor(out, dtype == APOLLO_BF16, h->cfg.rank, h->plan.t[tensor].m,
                                                        (uint32_t)tensor, sp, static_cast<hipStream_t>(hip_stream));
@@ -471,7 +484,7 @@ apollo_status_t apollo_debug_get(apollo_handle_t* h, int32_t tensor, int32_t wha
   if (tensor < 0 || tensor >= (int32_t)h->plan.t.size()) return fail(h->err, APOLLO_EINVAL, "tensor index %lld out of range", tensor);
   if (!out) return fail(h->err, APOLLO_EINVAL, "null output");
   const TensorPlan& t = h->plan.t[tensor];
-  const size_t rn = (size_t)h->cfg.rank * t.n * sizeof(float);
+  const size_t rn = (size_t)t.r * t.n * sizeof(float);
   const void* src = nullptr;
   size_t need = 0;
   bool widen = false;     // the source is bfloat16 and is delivered as fp32
@@ -484,7 +497,9 @@ apollo_status_t apollo_debug_get(apollo_handle_t* h, int32_t tensor, int32_t wha
       break;
     case APOLLO_DBG_NORM: src = h->state + t.st_norm; need = sizeof(float); break;
     case APOLLO_DBG_C: src = h->ws + t.ws_scal + sizeof(float); need = sizeof(float); break;
-    case APOLLO_DBG_R: src = h->ws + t.ws_r; need = rn; break;
+    case APOLLO_DBG_R:
+      if (t.path == Path::kIdentity) return fail(h->err, APOLLO_EINVAL, "no projected gradient without a projection");
+      src = h->ws + t.ws_r; need = rn; break;
     case APOLLO_DBG_COLSQ: src = h->ws + t.ws_colsq; need = (size_t)t.n * sizeof(float); break;
     default: return fail(h->err, APOLLO_EINVAL, "unknown selector %lld", what);
   }

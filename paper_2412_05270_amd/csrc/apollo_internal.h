@@ -139,6 +139,8 @@ hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool s
 hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepParams& sp, hipStream_t st);
 hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
                          bool w_bf16, const StepParams& sp, hipStream_t st);
+hipError_t launch_adam_identity(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool g_bf16,
+                                bool state_bf16, const StepParams& sp, hipStream_t st);
 hipError_t launch_bf16_to_f32(float* dst, const void* src, size_t count, hipStream_t st);
 hipError_t launch_philox_words(const uint32_t* ctr, uint32_t k0, uint32_t k1, uint32_t* out,
                                int64_t count, hipStream_t st);

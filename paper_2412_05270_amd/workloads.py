@@ -40,6 +40,7 @@ class Workload:
     weight_decay: float = 0.0
     weight_dtype: torch.dtype = torch.float32   # storage type of W
     state_dtype: torch.dtype = torch.float32    # storage type of the low-rank moments
+    projection: str = "random"                  # "random" | "identity" (no projection: full-rank moments)
     extra: dict = field(default_factory=dict)
 
     @property
@@ -74,6 +75,9 @@ def workload(name):
     if name == "llama7b_r256_bf16":
         return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=256,
                         steps=20, weight_dtype=torch.bfloat16, state_dtype=torch.bfloat16)
+    if name == "llama7b_identity":       # Section 3.2's channel-wise rule with full-rank moments (no projection)
+        return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=1,
+                        steps=10, projection="identity")
     if name == "llama13b_mini":
         return Workload(name, 5, llama_shapes(5120, 13824, 40), torch.bfloat16, "colscale", 1.0, rank=1,
                         mode="tensor", scale=MINI_SCALE, steps=5)

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _cfg(**kw):
     base = dict(rank=4, mode=A.APOLLO_CHANNEL, seed=1, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0,
                 weight_decay=0.0, nl_gamma=1.01, refresh_interval=200, bias_correction=1,
-                side=A.APOLLO_SIDE_AUTO, weight_dtype=A.APOLLO_F32, state_dtype=A.APOLLO_F32, reserved=0)
+                side=A.APOLLO_SIDE_AUTO, weight_dtype=A.APOLLO_F32, state_dtype=A.APOLLO_F32, projection=A.APOLLO_PROJ_RANDOM)
     base.update(kw)
     return A.ApolloConfig(**base)
 
@@ -107,6 +107,15 @@ def test_storage_types_are_validated_and_size_the_state():
     assert A.apollo_state_bytes(_cfg(state_dtype=2), shapes) == 0
     assert A.apollo_state_bytes(_cfg(weight_dtype=-1), shapes) == 0
     assert "dtype" in A.apollo_last_error()
+
+
+def test_identity_projection_sizes_full_rank_state_and_ignores_the_rank():
+    shapes = [(8, 20, A.APOLLO_F32), (20, 8, A.APOLLO_BF16)]
+    per = ((2 * 8 * 20 * 4 + 4) + 255) // 256 * 256
+    for rank in (0, 4, 1000):
+        assert A.apollo_state_bytes(_cfg(rank=rank, projection=A.APOLLO_PROJ_IDENTITY), shapes) == 2 * per
+    assert A.apollo_state_bytes(_cfg(projection=2), shapes) == 0
+    assert A.apollo_state_bytes(_cfg(rank=0), shapes) == 0
 
 
 def test_null_handle_calls_fail_cleanly():

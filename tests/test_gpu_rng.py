@@ -69,7 +69,7 @@ def test_projection_matrix_bit_exact(rows, cols, rank, bf16, step):
     T = 5
     seed = 0x0123456789ABCDEF
     cfg = A.ApolloConfig(rank=rank, mode=A.APOLLO_CHANNEL, seed=seed, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0,
-                         weight_decay=0.0, nl_gamma=1.01, refresh_interval=T, bias_correction=1, side=0, reserved=0)
+                         weight_decay=0.0, nl_gamma=1.01, refresh_interval=T, bias_correction=1, side=0, projection=0)
     dt = torch.bfloat16 if bf16 else torch.float32
     ws = [torch.zeros(rows, cols, device=DEV), torch.zeros(rows, cols, device=DEV)]
     gs = [torch.zeros(rows, cols, device=DEV, dtype=dt) for _ in ws]

@@ -95,9 +95,9 @@ def test_limiter_is_exercised_and_matches():
     """A gradient, its negative, then its negative again: the moment nearly cancels and builds up
     again, so the scaled-gradient norm grows by far more than gamma at step 3."""
     shapes = [(64, 128), (128, 64)]
-    for mode, rank in (("channel", 8), ("tensor", 1)):
+    for mode, rank, proj in (("channel", 8, "random"), ("tensor", 1, "random"), ("channel", 1, "identity")):
         wl = WL.Workload("limiter", 9, shapes, torch.bfloat16, "normal", 1e-2, rank=rank, mode=mode,
-                         refresh_interval=100, steps=4, lr=1e-2)
+                         refresh_interval=100, steps=4, lr=1e-2, projection=proj)
         cfg, ocfg = make_configs(wl)
         from oracle import apollo as O
         weights = WL.make_weights(wl, DEV)
