@@ -33,7 +33,7 @@ from dataclasses import dataclass
 
 import numpy as np
 
-from . import gauss
+from . import gauss, q8
 
 CHANNEL = "channel"   # APOLLO: one factor per channel
 TENSOR = "tensor"     # APOLLO-Mini: one factor per tensor
@@ -53,7 +53,8 @@ class Config:
     refresh_interval: int = 200    # T
     bias_correction: bool = True
     side: str = "auto"             # "auto" | "left" (project rows) | "right" (project columns)
-    weight_dtype: str = "f32"      # "f32" | "bf16": storage type of W
+    weight_dtype: str = "f32"      # "f32" | "bf16" | "q8" (group-wise 8-bit codes, oracle.q8): storage of W
+    weight_rounding: str = "nearest"   # "nearest" | "stochastic": rounding of the 8-bit codes
     state_dtype: str = "f32"       # "f32" | "bf16": storage type of M^R, V^R
     projection: str = "random"     # "random" (Algorithm 1) | "identity": the structured channel-wise
                                    # rule of Section 3.2 itself, full-rank moments of G (P = I, rank
@@ -99,7 +100,8 @@ def init_state(cfg, rows, cols):
 
 def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt_moments=None):
     """One optimizer step on one tensor.  W, G: float64 arrays (rows x cols); W is updated in
-    place and also returned.  t is the 1-based step.  P, if given, replaces the generated
+    place and also returned (with weight_dtype="q8", W is a q8.Q8Weights whose codes, scales and
+    zeros are replaced).  t is the 1-based step.  P, if given, replaces the generated
     r x m projection INCLUDING its 1/sqrt(r) (used by tests to inject a hand-set matrix).
     adopt_moments, if given, is a function (M_exact, V_exact) -> (M, V) called right after the
     moment update; what it returns becomes the stored state and feeds the rest of the step.
@@ -110,6 +112,9 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt
     before storage rounding: M_exact, V_exact, W_exact).
     """
     rows, cols = G.shape
+    Wq = None
+    if cfg.weight_dtype == "q8":
+        Wq, W = W, W.dequantise()
     left = is_left(rows, cols, cfg.side)
     Gm = G if left else G.T                       # m x n with the projected dimension first
     m, n = Gm.shape
@@ -171,9 +176,16 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt
     if not left:
         U = U.T
     W_exact = W - (lr * U + lr * cfg.weight_decay * W)
-    W[...] = stored(W_exact, cfg.weight_dtype)
-    return {"R": R, "Rt": Rt, "s": s, "colsq": colsq, "norm": norm, "c": c, "left": left,
-            "M_exact": M_exact, "V_exact": V_exact, "W_exact": W_exact}
+    out = {"R": R, "Rt": Rt, "s": s, "colsq": colsq, "norm": norm, "c": c, "left": left,
+           "M_exact": M_exact, "V_exact": V_exact, "W_exact": W_exact}
+    if Wq is not None:
+        u = q8.rounding_offsets(W_exact.shape, cfg.weight_rounding, cfg.seed, tensor_id, t)
+        new, x = q8.quantise(W_exact, u)
+        Wq.codes, Wq.scale, Wq.zero = new.codes, new.scale, new.zero
+        out["q8_x"], out["q8_u"] = x, u
+    else:
+        W[...] = stored(W_exact, cfg.weight_dtype)
+    return out
 
 
 def state_elements(cfg, shapes):
