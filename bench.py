@@ -1,6 +1,6 @@
 """Benchmark of the APOLLO / APOLLO-Mini optimizer step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b_mini] [--also llama7b_r256]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b_mini] [--also a,b,...]
 
 A "step" is one pass of the whole hot path (projection scratch fill, projection, low-rank Adam +
 factors, limiter, weight update) over every matrix of a synthetic LLaMA-shaped parameter set
@@ -9,7 +9,9 @@ value = parameters updated per second over exactly K timed steps; "roofline" des
 kernel phase that takes the most time (algorithmic bytes or flops per step divided by that
 phase's HIP-event time, against the MI355X peak); "cpu_baseline" is the fp64 oracle timed on
 the host cores on a bounded sample of the same workload; "also" carries the same measurement
-for the second variant the benchmark definition asks for on the same shapes.
+for further variants on the same shapes (rank 256, which the benchmark definition asks for as well;
+bfloat16 and 8-bit storage); "adamw_rest" the element-wise AdamW launch on the model's non-projected
+parameters.
 """
 import argparse
 import json
@@ -55,7 +57,8 @@ def make_cfg(A, wl, seed=20241205):
     return A.ApolloConfig(rank=wl.rank, mode=mode, seed=seed, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
                           scale=wl.scale, weight_decay=wl.weight_decay, nl_gamma=wl.nl_gamma,
                           refresh_interval=wl.refresh_interval, bias_correction=1, side=A.APOLLO_SIDE_AUTO,
-                          weight_dtype=A.APOLLO_BF16 if str(wl.weight_dtype) == "torch.bfloat16" else A.APOLLO_F32,
+                          weight_dtype={"torch.bfloat16": A.APOLLO_BF16, "torch.uint8": A.APOLLO_Q8}.get(str(wl.weight_dtype), A.APOLLO_F32),
+                          weight_rounding=A.APOLLO_ROUND_STOCHASTIC if wl.weight_rounding == "stochastic" else A.APOLLO_ROUND_NEAREST,
                           state_dtype=A.APOLLO_BF16 if str(wl.state_dtype) == "torch.bfloat16" else A.APOLLO_F32,
                           projection=A.APOLLO_PROJ_IDENTITY if wl.projection == "identity" else A.APOLLO_PROJ_RANDOM)
 
@@ -65,6 +68,8 @@ def algorithmic_work(wl):
     import torch
     gb = 2 if wl.grad_dtype == torch.bfloat16 else 4
     wb = 2 if wl.weight_dtype == torch.bfloat16 else 4     # W is read and written
+    if wl.weight_dtype == torch.uint8:
+        wb = 1.0 + 8.0 / 128.0                             # 8-bit codes + (scale, zero) per 128 elements
     sb = 2 if wl.state_dtype == torch.bfloat16 else 4      # M and V are read and written
     params = wl.n_params
     chan = sum(max(s) for s in wl.shapes)                 # sum of channel counts n
@@ -85,7 +90,10 @@ def algorithmic_work(wl):
 
 def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev):
     cfg = make_cfg(A, wl)
-    st = A.ApolloStepper(cfg, weights, grads, device=dev)
+    metas = None
+    if wl.weight_dtype == torch.uint8:
+        weights, metas = weights
+    st = A.ApolloStepper(cfg, weights, grads, device=dev, metas=metas)
     for t in range(1, warmup + 1):
         st.step(t, wl.lr)
     torch.cuda.synchronize()
@@ -98,7 +106,7 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev):
     rc, ms, n = A.apollo_profile_read(st.handle)
     assert rc == 0 and n == steps, (rc, n)
     A.apollo_profile_enable(st.handle, False)
-    finite = all(bool(torch.isfinite(w.float()).all()) for w in weights[:7])
+    finite = all(bool(torch.isfinite(w.float()).all()) for w in (metas if metas is not None else weights)[:7])
     state_bytes, ws_bytes = st.state.numel(), st.workspace.numel()
     st.close()
     del st
@@ -118,9 +126,11 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev):
         roof = {"bound": "hbm", "achieved": w["bytes"] / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": hbm_frac, "traffic": None}
     roof["kernel"] = KERNEL_OF_PHASE[dom]
+    if dom == "update" and wl.weight_dtype == torch.uint8:
+        roof["kernel"] = "update_q8_kernel"
     if dom == "projection" and wl.rank == 1:
         roof["kernel"] = "project_rank1_left_kernel + project_rank1_right_kernel"
-    roof["traffic"] = measured_traffic(wl.name, KERNEL_OF_PHASE[dom])
+    roof["traffic"] = measured_traffic(wl.name, roof["kernel"] if dom == "update" else KERNEL_OF_PHASE[dom])
     roof["traffic_note"] = "HBM bytes read + written per step (all launches of the kernel), rocprofv3 counters, profiles/"
     roof["algorithmic"] = w["bytes"]
     roof["phase"] = dom
@@ -224,7 +234,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama7b_mini")
-    ap.add_argument("--also", default="llama7b_r256,llama7b_mini_bf16,llama7b_r256_bf16",
+    ap.add_argument("--also", default="llama7b_r256,llama7b_mini_bf16,llama7b_r256_bf16,llama7b_mini_q8",
                     help="further variants on the same shapes, comma separated ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-adamw-rest", action="store_true",
@@ -262,7 +272,7 @@ def main():
         print(json.dumps({"adamw_rest": measure_adamw_rest(A, torch, args.steps, args.warmup, dev)}))
         return
     wl = WL.workload(args.workload)
-    weights = WL.make_weights(wl, dev)
+    weights = WL.make_q8_weights(wl, dev) if wl.weight_dtype == torch.uint8 else WL.make_weights(wl, dev)
     grads = WL.make_grads(wl, 1, dev)
     torch.cuda.synchronize()
     main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev)
@@ -274,7 +284,7 @@ def main():
         if wl2.weight_dtype != cur_wdt:          # other weight type: the same values, stored in it
             del weights
             torch.cuda.empty_cache()
-            weights = WL.make_weights(wl2, dev)
+            weights = WL.make_q8_weights(wl2, dev) if wl2.weight_dtype == torch.uint8 else WL.make_weights(wl2, dev)
             cur_wdt = wl2.weight_dtype
         r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev)
         also.append({"workload": describe(wl2), "value": r2["value"], "unit": "params/s", "ms_per_step": r2["ms_per_step"],
@@ -305,7 +315,7 @@ def main():
 
 
 def describe(wl):
-    short = lambda dt: "bf16" if str(dt) == "torch.bfloat16" else "fp32"
+    short = lambda dt: {"torch.bfloat16": "bf16", "torch.uint8": "8-bit (group 128, %s rounding)" % wl.weight_rounding}.get(str(dt), "fp32")
     return ("%s: %d matrices (%s), %s gradients ~ %s(%g), %s W, %s M/V, %s rank %d, alpha %.4g, T %d"
             % (wl.name, len(wl.shapes), ", ".join("%dx%d" % s for s in sorted(set(wl.shapes))),
                str(wl.grad_dtype).replace("torch.", ""), wl.grad_kind, wl.grad_scale, short(wl.weight_dtype),

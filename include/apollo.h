@@ -57,7 +57,9 @@ enum {
 
 /* element types: of the gradient (per tensor), of W and of M^R, V^R (per configuration);
    all factors and the stored norm are fp32 */
-enum { APOLLO_F32 = 0, APOLLO_BF16 = 1 };
+enum { APOLLO_F32 = 0, APOLLO_BF16 = 1, APOLLO_Q8 = 2 /* weights only: see apollo_config_t */ };
+/* rounding of the 8-bit weight codes */
+enum { APOLLO_ROUND_NEAREST = 0, APOLLO_ROUND_STOCHASTIC = 1 };
 /* granularity of the scaling factor: APOLLO (Eq. 4) or APOLLO-Mini (Section 4.2) */
 enum { APOLLO_CHANNEL = 0, APOLLO_TENSOR = 1 };
 /* which dimension is projected away: AUTO = the smaller one (Algorithm 1's m <= n);
@@ -95,10 +97,24 @@ typedef struct {
   int32_t refresh_interval; /* T >= 1: a new P is drawn when (step-1) % T == 0                 */
   int32_t bias_correction;  /* 1 = Adam's bias correction (default), 0 = literal Section 4.1   */
   int32_t side;             /* APOLLO_SIDE_*                                                   */
-  int32_t weight_dtype;     /* APOLLO_F32 (0, default) or APOLLO_BF16: element type of every W  */
+  int32_t weight_dtype;     /* APOLLO_F32 (0, default), APOLLO_BF16 or APOLLO_Q8: storage of every W */
   int32_t state_dtype;      /* APOLLO_F32 (0, default) or APOLLO_BF16: element type of M^R, V^R */
   int32_t projection;       /* APOLLO_PROJ_RANDOM (0, default) or APOLLO_PROJ_IDENTITY          */
+  int32_t weight_rounding;  /* APOLLO_ROUND_* of the codes when weight_dtype is APOLLO_Q8       */
+  int32_t reserved;         /* set to 0                                                        */
 } apollo_config_t;
+
+/* APOLLO_Q8: group-wise 8-bit weights (Section 5.4 / Table 6 combine APOLLO with "int-8 weight
+ * quantization", "group size of 128", and say no more; the reading taken is the usual asymmetric
+ * min/max group quantiser with optional stochastic rounding).  W is held as unsigned 8-bit codes
+ * q (rows x cols, row-major, cols a multiple of 128) and, per group of 128 consecutive elements,
+ * an fp32 pair (scale, zero) in apollo_tensor_t.w_meta:  w = zero + scale * q.  A step de-quantises,
+ * applies the update of Algorithm 1 (step 4) in fp32 and quantises every group again from its own
+ * new range: zero' = min w', scale' = (max w' - min w') / 255, q' = min(255, floor((w' - zero') /
+ * scale' + u)), u = 1/2 (nearest) or, stochastic, a 16-bit uniform from Philox4x32-10 under `seed`
+ * with counter (o mod 2^32, step mod 2^32, 2^31 + tensor index, o div 2^32), o = e div 8 for
+ * flattened element index e; output word k gives element 8 o + 2 k its low and element
+ * 8 o + 2 k + 1 its high 16 bits, u = bits / 65536. */
 
 /* APOLLO_PROJ_IDENTITY: no projection at all -- the structured channel-wise rule of Section 3.2
  * (Eq. 2) itself, with full-rank Adam moments of G: G~ = M^ / (sqrt(V^) + eps), s_j = ||G~[:,j]|| /
@@ -119,6 +135,8 @@ typedef struct {
   void* w;        /* DEVICE, weight_dtype (fp32 by default), rows x cols, 16-byte aligned,
                      updated in place                                                          */
   const void* g;  /* DEVICE, grad_dtype, rows x cols, 16-byte aligned, read only               */
+  void* w_meta;   /* DEVICE, only with APOLLO_Q8 weights (else ignored, may be NULL): rows * cols /
+                     128 pairs (scale, zero) fp32, 8-byte aligned, updated in place              */
 } apollo_tensor_t;
 
 /* Bytes of optimizer state for the tensor list (Table 1: 2nr + 2 scalars per tensor, here

@@ -98,7 +98,8 @@ def init_state(cfg, rows, cols):
     return TensorState(m if cfg.projection == "identity" else cfg.rank, n)
 
 
-def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt_moments=None):
+def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt_moments=None,
+         adopt_factors=None):
     """One optimizer step on one tensor.  W, G: float64 arrays (rows x cols); W is updated in
     place and also returned (with weight_dtype="q8", W is a q8.Q8Weights whose codes, scales and
     zeros are replaced).  t is the 1-based step.  P, if given, replaces the generated
@@ -108,6 +109,10 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt
     Parity tests of the bfloat16 state use it to check the other side's rounding of each moment
     and then to continue from that side's decisions (a rounding taken one way on a value that
     sits near a tie is as correct as the other; everything downstream must follow one of them).
+    adopt_factors, if given, is a function (s, c) -> (s, c) called after the limiter; what it
+    returns scales the update.  Parity tests of the 8-bit weights use it the same way: the other
+    side's factors are first compared with the oracle's, then adopted, so that the integer codes of
+    the new weights are compared on identical real-valued inputs (up to binary32 rounding).
     Returns a dict with the intermediate quantities (R, R~, s, colsq, norm, c, and the values
     before storage rounding: M_exact, V_exact, W_exact).
     """
@@ -170,13 +175,16 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt
         c = cfg.nl_gamma * state.prev_norm / norm
         norm = cfg.nl_gamma * state.prev_norm
     state.prev_norm = norm
+    s_own, c_own = s, c
+    if adopt_factors is not None:
+        s, c = adopt_factors(s, c)
 
     # Step 4: update in the original space.
     U = cfg.scale * c * (Gm * s[None, :])         # the scaled gradient, m x n
     if not left:
         U = U.T
     W_exact = W - (lr * U + lr * cfg.weight_decay * W)
-    out = {"R": R, "Rt": Rt, "s": s, "colsq": colsq, "norm": norm, "c": c, "left": left,
+    out = {"R": R, "Rt": Rt, "s": s_own, "colsq": colsq, "norm": norm, "c": c_own, "left": left,
            "M_exact": M_exact, "V_exact": V_exact, "W_exact": W_exact}
     if Wq is not None:
         u = q8.rounding_offsets(W_exact.shape, cfg.weight_rounding, cfg.seed, tensor_id, t)

@@ -11,7 +11,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libapollo_mi355x.so"
 
 APOLLO_OK, APOLLO_EINVAL, APOLLO_ENOMEM, APOLLO_ESTATE, APOLLO_EHIP, APOLLO_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
-APOLLO_F32, APOLLO_BF16 = 0, 1
+APOLLO_F32, APOLLO_BF16, APOLLO_Q8 = 0, 1, 2
+APOLLO_ROUND_NEAREST, APOLLO_ROUND_STOCHASTIC = 0, 1
 APOLLO_CHANNEL, APOLLO_TENSOR = 0, 1
 APOLLO_SIDE_AUTO, APOLLO_SIDE_LEFT, APOLLO_SIDE_RIGHT = 0, 1, 2
 APOLLO_PROJ_RANDOM, APOLLO_PROJ_IDENTITY = 0, 1
@@ -29,11 +30,11 @@ class ApolloConfig(C.Structure):
                 ("scale", C.c_float), ("weight_decay", C.c_float), ("nl_gamma", C.c_float),
                 ("refresh_interval", C.c_int32), ("bias_correction", C.c_int32),
                 ("side", C.c_int32), ("weight_dtype", C.c_int32), ("state_dtype", C.c_int32),
-                ("projection", C.c_int32)]
+                ("projection", C.c_int32), ("weight_rounding", C.c_int32), ("reserved", C.c_int32)]
 
 
 class ApolloTensor(C.Structure):
-    _fields_ = [("w", C.c_void_p), ("g", C.c_void_p)]
+    _fields_ = [("w", C.c_void_p), ("g", C.c_void_p), ("w_meta", C.c_void_p)]
 
 
 class ApolloFlatShape(C.Structure):
@@ -161,8 +162,8 @@ def apollo_step(handle, tensors, step, lr, stream=None, n_tensors=None):
     """tensors: a ctypes array of ApolloTensor (or a list of (w_ptr, g_ptr))."""
     if tensors is not None and not isinstance(tensors, C.Array):
         arr = (ApolloTensor * len(tensors))()
-        for i, (w, g) in enumerate(tensors):
-            arr[i] = ApolloTensor(w, g)
+        for i, t in enumerate(tensors):
+            arr[i] = ApolloTensor(*t)        # (w, g) or (w, g, w_meta)
         tensors = arr
     n = n_tensors if n_tensors is not None else (len(tensors) if tensors is not None else 0)
     return load_library().apollo_step(handle, tensors, n, step, lr, stream)
@@ -315,14 +316,20 @@ class ApolloStepper:
     Only allocation and pointer bookkeeping live here; every call goes to the C ABI.
     """
 
-    def __init__(self, cfg, weights, grads, device="cuda:0", zero_state=True):
+    def __init__(self, cfg, weights, grads, device="cuda:0", zero_state=True, metas=None):
+        """metas: with 8-bit weights (weights then are uint8 code tensors), one fp32 tensor of
+        (scale, zero) pairs per tensor, shape (rows * cols / 128, 2)."""
         import torch
         self.torch = torch
         self.cfg = cfg
         self.weights = list(weights)
         self.grads = list(grads)
+        self.metas = list(metas) if metas is not None else [None] * len(self.weights)
         self.shapes = []
-        wdt = torch.bfloat16 if cfg.weight_dtype == APOLLO_BF16 else torch.float32
+        wdt = {APOLLO_BF16: torch.bfloat16, APOLLO_Q8: torch.uint8}.get(cfg.weight_dtype, torch.float32)
+        for w, mt in zip(self.weights, self.metas):
+            assert (mt is None) == (cfg.weight_dtype != APOLLO_Q8)
+            assert mt is None or (mt.dtype == torch.float32 and mt.is_contiguous() and mt.numel() == w.numel() // 64)
         for w, g in zip(self.weights, self.grads):
             assert w.dtype == wdt and w.dim() == 2 and w.is_contiguous() and g.is_contiguous()
             assert g.shape == w.shape and g.dtype in (torch.float32, torch.bfloat16)
@@ -339,12 +346,13 @@ class ApolloStepper:
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_last_error())
         self._tensors = (ApolloTensor * len(self.weights))()
-        self.set_tensors(self.weights, self.grads)
+        self.set_tensors(self.weights, self.grads, self.metas)
 
-    def set_tensors(self, weights, grads):
+    def set_tensors(self, weights, grads, metas=None):
         self.weights, self.grads = list(weights), list(grads)
-        for i, (w, g) in enumerate(zip(self.weights, self.grads)):
-            self._tensors[i] = ApolloTensor(w.data_ptr(), g.data_ptr())
+        self.metas = list(metas) if metas is not None else [None] * len(self.weights)
+        for i, (w, g, mt) in enumerate(zip(self.weights, self.grads, self.metas)):
+            self._tensors[i] = ApolloTensor(w.data_ptr(), g.data_ptr(), mt.data_ptr() if mt is not None else None)
 
     def step(self, step, lr):
         rc = apollo_step(self.handle, self._tensors, step, lr, self.stream.cuda_stream)

@@ -523,4 +523,112 @@ hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int col
                 : launch_update_c<false, false>(d_descs, count, rows, cols, chan, sp, st);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Update of group-wise 8-bit weights (the format and the rounding stream are stated in
+// include/apollo.h): de-quantise, W <- W - coef * s_ch * G - lr*lambda * W in fp32, quantise every
+// group of 128 elements again from its new range.  One thread = 8 consecutive elements (8 bytes
+// of codes, 16 bytes of a bf16 gradient), so a group is 16 consecutive lanes: its minimum and
+// maximum come from four butterfly steps within those lanes, and one Philox call per thread
+// yields the eight 16-bit rounding offsets.  cols is a multiple of 128: a group never straddles a
+// row, and a 16-lane group is either whole or absent at the end of the tensor.
+// ---------------------------------------------------------------------------------------------
+template <bool BF16, int CHAN>
+__global__ __launch_bounds__(256) void update_q8_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
+                                                        FastDiv div_cols) {
+  const TensorView d(descs[blockIdx.y]);
+  const uint32_t cols = (uint32_t)d.cols;
+  const size_t total = (size_t)d.rows * (size_t)d.cols;
+  const size_t oct = (size_t)blockIdx.x * 256u + threadIdx.x;
+  const size_t e0 = oct * 8u;
+  if (e0 >= total) return;
+  const float coef = d.scal[0];
+  const float decay = sp.lr_decay;
+  float k[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) k[e] = coef;
+  if (CHAN != kChanNone) {
+    const uint32_t row = fastdiv((uint32_t)e0, div_cols);
+    const uint32_t col = (uint32_t)e0 - row * cols;
+    if (CHAN == kChanCol) {
+      float sv[8];
+      load_elems<8, false, false>(d.s, col, sv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) k[e] *= sv[e];
+    } else {
+      const float sr = d.s[row];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) k[e] *= sr;
+    }
+  }
+  float g[8];
+  load_elems<8, BF16, false>(d.g, e0, g);
+  const u32x2_t codes = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x2_t*>(d.w) + oct);
+  const size_t group = e0 >> 7;
+  const float scale = d.w_meta[2 * group], zero = d.w_meta[2 * group + 1];
+  float w[8];
+  float lo = 3.4e38f, hi = -3.4e38f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t q = ((e < 4 ? codes.x : codes.y) >> (8 * (e & 3))) & 0xFFu;
+    const float wo = __builtin_fmaf(scale, (float)q, zero);
+    w[e] = wo - __builtin_fmaf(k[e], g[e], decay * wo);
+    lo = fminf(lo, w[e]);
+    hi = fmaxf(hi, w[e]);
+  }
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) {
+    lo = fminf(lo, __shfl_xor(lo, off, 64));
+    hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+  }
+  const float range = hi - lo;
+  const float inv = range > 0.f ? 255.f / range : 0.f;
+  float u[8];
+  if (sp.q8_stochastic) {
+    uint32_t c[4] = {(uint32_t)oct, sp.step_lo, 0x80000000u | (uint32_t)d.tensor_id, (uint32_t)(oct >> 32)};
+    philox4x32_10(c, sp.ks);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u[2 * kk] = (float)(c[kk] & 0xFFFFu) * (1.f / 65536.f);
+      u[2 * kk + 1] = (float)(c[kk] >> 16) * (1.f / 65536.f);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) u[e] = 0.5f;
+  }
+  uint32_t out[2] = {0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float x = (w[e] - lo) * inv;
+    uint32_t q = (uint32_t)__builtin_floorf(x + u[e]);
+    q = q > 255u ? 255u : q;
+    out[e >> 2] |= q << (8 * (e & 3));
+  }
+  u32x2_t packed = {out[0], out[1]};
+  __builtin_nontemporal_store(packed, reinterpret_cast<APOLLO_GLOBAL u32x2_t*>(d.w) + oct);
+  if ((threadIdx.x & 15) == 0) {
+    d.w_meta[2 * group] = range * (1.f / 255.f);
+    d.w_meta[2 * group + 1] = lo;
+  }
+}
+
+template <bool BF16>
+static hipError_t launch_update_q8_t(const TensorDesc* d_descs, int count, int rows, int cols, int chan,
+                                     const StepParams& sp, hipStream_t st) {
+  const FastDiv fd = make_fastdiv((uint32_t)cols);
+  const size_t octs = (size_t)rows * cols / 8;
+  dim3 grid((unsigned)((octs + 255) / 256), (unsigned)count, 1);
+  if (chan == kChanCol) hipLaunchKernelGGL((update_q8_kernel<BF16, kChanCol>), grid, dim3(256), 0, st, d_descs, sp, fd);
+  else if (chan == kChanRow) hipLaunchKernelGGL((update_q8_kernel<BF16, kChanRow>), grid, dim3(256), 0, st, d_descs, sp, fd);
+  else hipLaunchKernelGGL((update_q8_kernel<BF16, kChanNone>), grid, dim3(256), 0, st, d_descs, sp, fd);
+  return hipGetLastError();
+}
+
+// cols must be a multiple of 128 (checked when the handle is created).
+hipError_t launch_update_q8(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
+                            const StepParams& sp, hipStream_t st) {
+  const int chan = sp.tensor_mode ? kChanNone : (left ? kChanCol : kChanRow);
+  return bf16 ? launch_update_q8_t<true>(d_descs, count, rows, cols, chan, sp, st)
+              : launch_update_q8_t<false>(d_descs, count, rows, cols, chan, sp, st);
+}
+
 }  // namespace apollo

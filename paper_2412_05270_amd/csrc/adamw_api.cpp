@@ -163,7 +163,7 @@ apollo_status_t apollo_adamw_init(apollo_adamw_handle_t** out, const apollo_adam
   h->state = static_cast<char*>(state);
   h->ws = static_cast<char*>(workspace);
   h->desc.resize(n_tensors);
-  h->last.assign(n_tensors, apollo_tensor_t{nullptr, nullptr});
+  h->last.assign(n_tensors, apollo_tensor_t{nullptr, nullptr, nullptr});
   std::vector<uint32_t> table(h->plan.n_blocks);
   for (int32_t k = 0; k < n_tensors; ++k) {
     const FlatPlan::T& t = h->plan.t[k];

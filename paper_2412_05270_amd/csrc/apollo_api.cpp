@@ -77,9 +77,11 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     return fail(err, APOLLO_EINVAL, "betas must lie in [0, 1)");
   if (!(cfg->eps >= 0.f) || !(cfg->nl_gamma >= 0.f) || !std::isfinite(cfg->scale) || !std::isfinite(cfg->weight_decay))
     return fail(err, APOLLO_EINVAL, "eps / nl_gamma negative or scale / weight_decay not finite");
-  if ((cfg->weight_dtype != APOLLO_F32 && cfg->weight_dtype != APOLLO_BF16) ||
+  if ((cfg->weight_dtype != APOLLO_F32 && cfg->weight_dtype != APOLLO_BF16 && cfg->weight_dtype != APOLLO_Q8) ||
       (cfg->state_dtype != APOLLO_F32 && cfg->state_dtype != APOLLO_BF16))
-    return fail(err, APOLLO_EUNSUPPORTED, "weight_dtype / state_dtype must be fp32 or bf16");
+    return fail(err, APOLLO_EUNSUPPORTED, "weight_dtype must be fp32, bf16 or q8 and state_dtype fp32 or bf16");
+  if (cfg->weight_rounding != APOLLO_ROUND_NEAREST && cfg->weight_rounding != APOLLO_ROUND_STOCHASTIC)
+    return fail(err, APOLLO_EINVAL, "unknown weight_rounding %lld", cfg->weight_rounding);
   const size_t state_elem = cfg->state_dtype == APOLLO_BF16 ? 2 : sizeof(float);
 
   plan.t.resize(n);
@@ -94,6 +96,8 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
       return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: dimension above %lld", k, kMaxDim);
     if (s.rows * s.cols >= (1ll << 31))
       return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: more than 2^31 - 1 elements", k);
+    if (cfg->weight_dtype == APOLLO_Q8 && (s.cols % 128) != 0)
+      return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: 8-bit weights need a row length that is a multiple of 128", k);
     t.rows = (int32_t)s.rows;
     t.cols = (int32_t)s.cols;
     t.bf16 = s.grad_dtype == APOLLO_BF16;
@@ -232,6 +236,8 @@ StepParams make_step_params(const apollo_config_t& c, int64_t step, float lr) {
   sp.gamma = c.nl_gamma;
   sp.lr = lr;
   sp.lr_decay = lr * c.weight_decay;
+  sp.step_lo = (uint32_t)((uint64_t)step & 0xffffffffu);
+  sp.q8_stochastic = c.weight_rounding == APOLLO_ROUND_STOCHASTIC;
   return sp;
 }
 
@@ -306,7 +312,7 @@ apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg, c
   h->state = static_cast<char*>(state);
   h->ws = static_cast<char*>(workspace);
   h->desc.resize(n_tensors);
-  h->last.assign(n_tensors, apollo_tensor_t{nullptr, nullptr});
+  h->last.assign(n_tensors, apollo_tensor_t{nullptr, nullptr, nullptr});
   for (int32_t k = 0; k < n_tensors; ++k) {
     const TensorPlan& t = h->plan.t[k];
     TensorDesc& d = h->desc[t.desc_index];
@@ -354,13 +360,16 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
     if (!tensors[k].w || !tensors[k].g) return fail(h->err, APOLLO_EINVAL, "tensor %lld: null w or g", k);
     if (((uintptr_t)tensors[k].w | (uintptr_t)tensors[k].g) & 15u)
       return fail(h->err, APOLLO_EINVAL, "tensor %lld: w / g not 16-byte aligned", k);
-    if (tensors[k].w != h->last[k].w || tensors[k].g != h->last[k].g) changed = true;
+    if (h->cfg.weight_dtype == APOLLO_Q8 && (!tensors[k].w_meta || ((uintptr_t)tensors[k].w_meta & 7u)))
+      return fail(h->err, APOLLO_EINVAL, "tensor %lld: w_meta null or not 8-byte aligned", k);
+    if (tensors[k].w != h->last[k].w || tensors[k].g != h->last[k].g || tensors[k].w_meta != h->last[k].w_meta) changed = true;
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (changed) {
     for (int32_t k = 0; k < n; ++k) {
       TensorDesc& d = h->desc[h->plan.t[k].desc_index];
       d.w = tensors[k].w;
+      d.w_meta = static_cast<float*>(tensors[k].w_meta);
       d.g = tensors[k].g;
       h->last[k] = tensors[k];
     }
@@ -428,7 +437,10 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   // (e) W update
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
-    e = launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, h->cfg.weight_dtype == APOLLO_BF16, sp, st);
+    if (h->cfg.weight_dtype == APOLLO_Q8)
+      e = launch_update_q8(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, sp, st);
+    else
+      e = launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, h->cfg.weight_dtype == APOLLO_BF16, sp, st);
     what = "weight update";
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[5], st);

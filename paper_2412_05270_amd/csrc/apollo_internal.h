@@ -12,7 +12,8 @@ namespace apollo {
 // between steps.  m = projected (reduced) dimension, n = channel dimension (Algorithm 1 has
 // W in R^{m x n}, m <= n; `left` says whether m runs along the stored rows).
 struct TensorDesc {
-  void* w;             // rows x cols, fp32 or bf16, updated in place
+  void* w;             // rows x cols, fp32, bf16 or 8-bit codes, updated in place
+  float* w_meta;       // 8-bit weights: (scale, zero) per group of 128 elements, else unused
   const void* g;       // rows x cols, bf16 or fp32
   void* M;             // state: M^R, r x n, fp32 or bf16
   void* V;             // state: V^R, r x n
@@ -45,6 +46,8 @@ struct StepParams {
   float inv_bc1, inv_bc2;  // 1/(1-beta^t) or 1
   float alpha, gamma;
   float lr, lr_decay;  // lr, lr * lambda
+  uint32_t step_lo;    // step mod 2^32 (counter word of the weight-rounding stream)
+  int32_t q8_stochastic;
 };
 
 // Pointers read from a TensorDesc are generic to the compiler; every buffer they name is device
@@ -71,6 +74,7 @@ __device__ __forceinline__ APOLLO_GLOBAL T* gptr(T* p) {
 // A TensorDesc with its pointers typed as global memory; kernels build one from the table entry.
 struct TensorView {
   APOLLO_GLOBAL void* w;
+  APOLLO_GLOBAL float* w_meta;
   APOLLO_GLOBAL const void* g;
   APOLLO_GLOBAL void* M;
   APOLLO_GLOBAL void* V;
@@ -84,7 +88,7 @@ struct TensorView {
   APOLLO_GLOBAL float* scal;
   int32_t rows, cols, m, n, m8, left, tensor_id, n_slabs, k2_blocks, ldg;
   __device__ __forceinline__ explicit TensorView(const TensorDesc& d)
-      : w(gptr(d.w)), g(gptr(d.g)), M(gptr(d.M)), V(gptr(d.V)), prev_norm(gptr(d.prev_norm)), P(gptr(d.P)), gpad(gptr(d.gpad)),
+      : w(gptr(d.w)), w_meta(gptr(d.w_meta)), g(gptr(d.g)), M(gptr(d.M)), V(gptr(d.V)), prev_norm(gptr(d.prev_norm)), P(gptr(d.P)), gpad(gptr(d.gpad)),
         R(gptr(d.R)), colsq(gptr(d.colsq)), s(gptr(d.s)), partials(gptr(d.partials)), scal(gptr(d.scal)),
         rows(d.rows), cols(d.cols), m(d.m), n(d.n), m8(d.m8), left(d.left), tensor_id(d.tensor_id),
         n_slabs(d.n_slabs), k2_blocks(d.k2_blocks), ldg(d.ldg) {}
@@ -141,6 +145,8 @@ hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int col
                          bool w_bf16, const StepParams& sp, hipStream_t st);
 hipError_t launch_adam_identity(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool g_bf16,
                                 bool state_bf16, const StepParams& sp, hipStream_t st);
+hipError_t launch_update_q8(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
+                            const StepParams& sp, hipStream_t st);
 hipError_t launch_bf16_to_f32(float* dst, const void* src, size_t count, hipStream_t st);
 hipError_t launch_philox_words(const uint32_t* ctr, uint32_t k0, uint32_t k1, uint32_t* out,
                                int64_t count, hipStream_t st);

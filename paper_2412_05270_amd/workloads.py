@@ -38,7 +38,8 @@ class Workload:
     eps: float = 1e-8
     nl_gamma: float = 1.01
     weight_decay: float = 0.0
-    weight_dtype: torch.dtype = torch.float32   # storage type of W
+    weight_dtype: torch.dtype = torch.float32   # storage type of W (torch.uint8: group-wise 8-bit codes)
+    weight_rounding: str = "nearest"            # "nearest" | "stochastic": rounding of 8-bit codes
     state_dtype: torch.dtype = torch.float32    # storage type of the low-rank moments
     projection: str = "random"                  # "random" | "identity" (no projection: full-rank moments)
     extra: dict = field(default_factory=dict)
@@ -75,6 +76,10 @@ def workload(name):
     if name == "llama7b_r256_bf16":
         return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=256,
                         steps=20, weight_dtype=torch.bfloat16, state_dtype=torch.bfloat16)
+    if name == "llama7b_mini_q8":        # Q-APOLLO-Mini: group-wise 8-bit weights, stochastic rounding
+        return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=1,
+                        mode="tensor", scale=MINI_SCALE, steps=20, weight_dtype=torch.uint8,
+                        weight_rounding="stochastic")
     if name == "llama7b_identity":       # Section 3.2's channel-wise rule with full-rank moments (no projection)
         return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=1,
                         steps=10, projection="identity")
@@ -99,6 +104,22 @@ def make_weights(wl, device):
     gen = _generator(device, 1000 * wl.config_id)
     return [(torch.randn(s, generator=gen, device=device, dtype=torch.float32) * wl.w_std).to(wl.weight_dtype)
             for s in wl.shapes]
+
+
+def make_q8_weights(wl, device):
+    """Synthetic group-wise 8-bit weights: uniform random codes and, per group of 128 elements, a
+    (scale, zero) pair that spans about +-4 w_std -- the shape and value range of quantised N(0,
+    w_std^2) weights, without running a quantiser.  Returns (codes, metas): uint8 rows x cols and
+    fp32 (rows * cols / 128, 2) tensors."""
+    gen = _generator(device, 1000 * wl.config_id + 500)
+    codes, metas = [], []
+    for rows, cols in wl.shapes:
+        assert cols % 128 == 0
+        codes.append(torch.randint(0, 256, (rows, cols), generator=gen, device=device, dtype=torch.uint8))
+        groups = rows * cols // 128
+        span = wl.w_std * (7.0 + 2.0 * torch.rand(groups, generator=gen, device=device, dtype=torch.float32))
+        metas.append(torch.stack([span / 255.0, -0.5 * span], dim=1).contiguous())
+    return codes, metas
 
 
 def _one_grad(shape, wl, gen, device, structure_along_rows):

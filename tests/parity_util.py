@@ -39,14 +39,17 @@ def make_configs(wl, seed=0x5EED5EED1234, side="auto", bias_correction=True):
     cfg = A.ApolloConfig(rank=wl.rank, mode=mode, seed=seed, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
                          scale=wl.scale, weight_decay=wl.weight_decay, nl_gamma=wl.nl_gamma,
                          refresh_interval=wl.refresh_interval, bias_correction=1 if bias_correction else 0,
-                         side=side_code, weight_dtype=A.APOLLO_BF16 if wl.weight_dtype == torch.bfloat16 else A.APOLLO_F32,
+                         side=side_code,
+                         weight_dtype={torch.bfloat16: A.APOLLO_BF16, torch.uint8: A.APOLLO_Q8}.get(wl.weight_dtype, A.APOLLO_F32),
+                         weight_rounding=A.APOLLO_ROUND_STOCHASTIC if wl.weight_rounding == "stochastic" else A.APOLLO_ROUND_NEAREST,
                          state_dtype=A.APOLLO_BF16 if wl.state_dtype == torch.bfloat16 else A.APOLLO_F32,
                          projection=A.APOLLO_PROJ_IDENTITY if wl.projection == "identity" else A.APOLLO_PROJ_RANDOM)
     ocfg = O.Config(rank=wl.rank, mode=O.TENSOR if wl.mode == "tensor" else O.CHANNEL, seed=seed,
                     beta1=f32(wl.beta1), beta2=f32(wl.beta2), eps=f32(wl.eps), scale=f32(wl.scale),
                     weight_decay=f32(wl.weight_decay), nl_gamma=f32(wl.nl_gamma),
                     refresh_interval=wl.refresh_interval, bias_correction=bias_correction, side=side,
-                    weight_dtype="bf16" if wl.weight_dtype == torch.bfloat16 else "f32",
+                    weight_dtype={torch.bfloat16: "bf16", torch.uint8: "q8"}.get(wl.weight_dtype, "f32"),
+                    weight_rounding=wl.weight_rounding,
                     state_dtype="bf16" if wl.state_dtype == torch.bfloat16 else "f32", projection=wl.projection)
     return cfg, ocfg
 

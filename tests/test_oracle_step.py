@@ -579,3 +579,15 @@ def test_identity_projection_equals_a_hand_set_identity_matrix_and_counts_full_r
     assert apollo.state_elements(a, [(4, 6), (6, 4)]) == 2 * (2 * 4 * 6 + 2)
     with pytest.raises(ValueError):
         apollo.step(a, sa, Wa, G, 3, 0.1, P=np.eye(4))
+
+
+def test_adopt_factors_scales_the_update_but_not_the_reported_factors():
+    P = np.array([[1.0]])
+    G = np.array([[2.0, 1.0]])
+    cfg = _cfg(rank=1, beta1=0.0, beta2=0.0, eps=0.0, nl_gamma=0.0)
+    st = apollo.init_state(cfg, 1, 2)
+    W = np.zeros((1, 2))
+    info = apollo.step(cfg, st, W, G, 1, 0.5, P=P, adopt_factors=lambda s, c: (3.0 * s, 0.5 * c))
+    # own factors: s_j = 1 / |G_j|, c = 1; the update uses 3 s and c / 2: W = -lr * 1.5 * sign(G)
+    assert np.allclose(info["s"], [0.5, 1.0]) and info["c"] == 1.0
+    assert np.allclose(W, [[-0.75, -0.75]])
