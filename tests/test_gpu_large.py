@@ -18,6 +18,8 @@ pytestmark = pytest.mark.gpu
     ("llama7b_r256", 2),
     ("llama13b_mini", 2),
     ("llama13b_r256", 2),
+    ("llama7b_mini_bf16", 2),       # bfloat16 W and moments (valid-rounding checks)
+    ("llama7b_r256_bf16", 2),
 ])
 def test_full_size_sets(name, steps):
     wl = WL.workload(name)
@@ -32,4 +34,13 @@ def test_llama13b_zero_channels_on_the_tall_tensors():
     wl.name = "llama13b_r256_channel_structure"
     wl.shapes = wl.shapes[:7]                      # one layer is enough for the edge case
     run_parity(wl, list(range(7)), 2, progress=True)
+    torch.cuda.empty_cache()
+
+
+def test_full_size_q8_mini():
+    """LLaMA-7B shapes with group-wise 8-bit weights and stochastic rounding, every tensor stepped
+    on the GPU, three tensors of the first and of the last layer followed by the oracle."""
+    from test_gpu_q8 import _run
+    wl = WL.workload("llama7b_mini_q8")
+    _run(wl, 2, 1e-5, check_ids=_first_and_last_layer(wl), progress=True)
     torch.cuda.empty_cache()

@@ -22,31 +22,39 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _run(wl, steps, lr):
+def _run(wl, steps, lr, check_ids=None, progress=False):
     bf16 = wl.grad_dtype == torch.bfloat16
     tol = TOL_BF16 if bf16 else TOL_F32
     cfg, ocfg = make_configs(wl)
-    # initial weights: N(0, w_std^2) quantised on the host (nearest)
-    w0 = [to_host_f64(w) for w in WL.make_weights(WL.Workload(wl.name, wl.config_id, wl.shapes, wl.grad_dtype,
-                                                               wl.grad_kind, wl.grad_scale), DEV)]
-    codes, metas = [], []
-    for w in w0:
-        q, _ = Q.quantise(w, np.full(w.shape, 0.5))
-        codes.append(torch.from_numpy(q.codes).to(DEV))
-        metas.append(torch.from_numpy(np.stack([q.scale, q.zero], axis=-1).reshape(-1, 2).astype(np.float32)).to(DEV))
+    if check_ids is None:
+        # initial weights: N(0, w_std^2) quantised on the host (nearest)
+        check_ids = list(range(len(wl.shapes)))
+        w0 = [to_host_f64(w) for w in WL.make_weights(WL.Workload(wl.name, wl.config_id, wl.shapes, wl.grad_dtype,
+                                                                   wl.grad_kind, wl.grad_scale), DEV)]
+        codes, metas = [], []
+        for w in w0:
+            q, _ = Q.quantise(w, np.full(w.shape, 0.5))
+            codes.append(torch.from_numpy(q.codes).to(DEV))
+            metas.append(torch.from_numpy(np.stack([q.scale, q.zero], axis=-1).reshape(-1, 2).astype(np.float32)).to(DEV))
+    else:
+        codes, metas = WL.make_q8_weights(wl, DEV)     # the benchmark's synthetic codes and ranges
     grads = [torch.empty(s, dtype=wl.grad_dtype, device=DEV) for s in wl.shapes]
     st = A.ApolloStepper(cfg, codes, grads, device=DEV, metas=metas)
-    states = [O.init_state(ocfg, *s) for s in wl.shapes]
+    states = {i: O.init_state(ocfg, *wl.shapes[i]) for i in check_ids}
     moved = 0
     for t in range(1, steps + 1):
         WL.make_grads(wl, t, DEV, out=grads)
-        before = []
-        for i, (rows, cols) in enumerate(wl.shapes):
+        before = {}
+        for i in check_ids:
+            rows, cols = wl.shapes[i]
             mt = metas[i].double().cpu().numpy().reshape(rows, cols // 128, 2)
-            before.append(Q.Q8Weights(codes[i].cpu().numpy().copy(), mt[:, :, 0].copy(), mt[:, :, 1].copy()))
+            before[i] = Q.Q8Weights(codes[i].cpu().numpy().copy(), mt[:, :, 0].copy(), mt[:, :, 1].copy())
         st.step(t, lr)
         torch.cuda.synchronize()
-        for i, (rows, cols) in enumerate(wl.shapes):
+        if progress:
+            print("%s: step %d/%d done, comparing" % (wl.name, t, steps), flush=True)
+        for i in check_ids:
+            rows, cols = wl.shapes[i]
             tag = "%s tensor %d step %d " % (wl.name, i, t)
             Wq = before[i]
             w_before = Wq.dequantise()
