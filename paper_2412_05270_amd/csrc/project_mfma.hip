@@ -62,7 +62,9 @@ struct Cfg {
 // invariants.
 __device__ __forceinline__ void dma16(const APOLLO_GLOBAL void* base_uniform, uint32_t lane_off, uint32_t lds_dst_uniform) {
   uint32_t saved_m0;   // M0 is restored: the compiler may hold a value of its own there
-  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+  // (one wait state between the write of M0 and the load that reads it: the compiler's hazard
+  // handling does not look inside inline assembly)
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
                : "=&s"(saved_m0)
                : "s"(lds_dst_uniform), "v"(lane_off), "s"(base_uniform)
                : "memory");
