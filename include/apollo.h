@@ -22,7 +22,8 @@
  *
  * Conventions
  *   - Every pointer argument is a HOST pointer unless its comment says DEVICE.
- *   - The library allocates no device memory and creates no streams.  The caller owns W, G,
+ *   - The library allocates no device memory; it creates at most one stream of its own per handle
+ *     (see APOLLO_SCHEDULE_OVERLAP).  The caller owns W, G,
  *     the state buffer and the workspace (all DEVICE memory) and keeps them alive while the
  *     handle uses them.  The library owns only the host-side handle.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default
@@ -60,6 +61,8 @@ enum {
 enum { APOLLO_F32 = 0, APOLLO_BF16 = 1, APOLLO_Q8 = 2 /* weights only: see apollo_config_t */ };
 /* rounding of the 8-bit weight codes */
 enum { APOLLO_ROUND_NEAREST = 0, APOLLO_ROUND_STOCHASTIC = 1 };
+/* launch schedule of a step */
+enum { APOLLO_SCHEDULE_SERIAL = 0, APOLLO_SCHEDULE_OVERLAP = 1 };
 /* granularity of the scaling factor: APOLLO (Eq. 4) or APOLLO-Mini (Section 4.2) */
 enum { APOLLO_CHANNEL = 0, APOLLO_TENSOR = 1 };
 /* which dimension is projected away: AUTO = the smaller one (Algorithm 1's m <= n);
@@ -101,8 +104,19 @@ typedef struct {
   int32_t state_dtype;      /* APOLLO_F32 (0, default) or APOLLO_BF16: element type of M^R, V^R */
   int32_t projection;       /* APOLLO_PROJ_RANDOM (0, default) or APOLLO_PROJ_IDENTITY          */
   int32_t weight_rounding;  /* APOLLO_ROUND_* of the codes when weight_dtype is APOLLO_Q8       */
-  int32_t reserved;         /* set to 0                                                        */
+  int32_t schedule;         /* APOLLO_SCHEDULE_SERIAL (0, default) or APOLLO_SCHEDULE_OVERLAP    */
 } apollo_config_t;
+
+/* APOLLO_SCHEDULE_OVERLAP: when some projection runs on the matrix cores (bf16 gradients, rank a
+ * multiple of 32) and the tensors form more than one shape group, apollo_step runs the groups as
+ * chains on two streams -- the caller's and one the library creates in apollo_init (default
+ * priority, destroyed by apollo_destroy) -- so that one group's projection overlaps another group's
+ * memory-bound kernels.  The second stream is forked from and joined back into `hip_stream` within
+ * the call: the caller sees ordinary in-order work on its stream.  Results are bit-identical to
+ * APOLLO_SCHEDULE_SERIAL (the groups touch disjoint data); the gain measured on MI355X is small
+ * (about 3 % of a rank-256 step: the projection and the streaming kernels contend for the same
+ * load path), which is why it is not the default.  Steps recorded by apollo_profile_enable use the
+ * serial schedule, which is the one that has phases to time. */
 
 /* APOLLO_Q8: group-wise 8-bit weights (Section 5.4 / Table 6 combine APOLLO with "int-8 weight
  * quantization", "group size of 128", and say no more; the reading taken is the usual asymmetric

@@ -13,6 +13,7 @@ _LIB_NAME = "libapollo_mi355x.so"
 APOLLO_OK, APOLLO_EINVAL, APOLLO_ENOMEM, APOLLO_ESTATE, APOLLO_EHIP, APOLLO_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 APOLLO_F32, APOLLO_BF16, APOLLO_Q8 = 0, 1, 2
 APOLLO_ROUND_NEAREST, APOLLO_ROUND_STOCHASTIC = 0, 1
+APOLLO_SCHEDULE_SERIAL, APOLLO_SCHEDULE_OVERLAP = 0, 1
 APOLLO_CHANNEL, APOLLO_TENSOR = 0, 1
 APOLLO_SIDE_AUTO, APOLLO_SIDE_LEFT, APOLLO_SIDE_RIGHT = 0, 1, 2
 APOLLO_PROJ_RANDOM, APOLLO_PROJ_IDENTITY = 0, 1
@@ -30,7 +31,7 @@ class ApolloConfig(C.Structure):
                 ("scale", C.c_float), ("weight_decay", C.c_float), ("nl_gamma", C.c_float),
                 ("refresh_interval", C.c_int32), ("bias_correction", C.c_int32),
                 ("side", C.c_int32), ("weight_dtype", C.c_int32), ("state_dtype", C.c_int32),
-                ("projection", C.c_int32), ("weight_rounding", C.c_int32), ("reserved", C.c_int32)]
+                ("projection", C.c_int32), ("weight_rounding", C.c_int32), ("schedule", C.c_int32)]
 
 
 class ApolloTensor(C.Structure):

@@ -82,6 +82,8 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     return fail(err, APOLLO_EUNSUPPORTED, "weight_dtype must be fp32, bf16 or q8 and state_dtype fp32 or bf16");
   if (cfg->weight_rounding != APOLLO_ROUND_NEAREST && cfg->weight_rounding != APOLLO_ROUND_STOCHASTIC)
     return fail(err, APOLLO_EINVAL, "unknown weight_rounding %lld", cfg->weight_rounding);
+  if (cfg->schedule != APOLLO_SCHEDULE_OVERLAP && cfg->schedule != APOLLO_SCHEDULE_SERIAL)
+    return fail(err, APOLLO_EINVAL, "unknown schedule %lld", cfg->schedule);
   const size_t state_elem = cfg->state_dtype == APOLLO_BF16 ? 2 : sizeof(float);
 
   plan.t.resize(n);
@@ -202,6 +204,10 @@ struct apollo_handle {
   int ring_next = 0;
   bool have_ptrs = false;
   bool profiling = false;
+  hipStream_t side = nullptr;             // second stream of the overlapped schedule (created at init)
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  std::vector<hipEvent_t> ev_proj;        // one per group: its projection has finished
+  bool overlap = false;                   // the overlapped schedule applies to this tensor list
   std::vector<hipEvent_t> prof_events;    // 6 per recorded step
   size_t prof_used = 0;                   // events recorded since the last read
   std::string err;
@@ -337,6 +343,22 @@ apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg, c
     e = hipHostMalloc(reinterpret_cast<void**>(&h->ring[i]), h->plan.desc_bytes, hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ring_ev[i], hipEventDisableTiming);
   }
+  // Overlapped schedule (see apollo_step): only where a projection runs on the matrix cores, i.e.
+  // leaves HBM bandwidth unused that another group's streaming kernels can take.
+  h->overlap = cfg->schedule == APOLLO_SCHEDULE_OVERLAP && h->plan.groups.size() > 1;
+  if (h->overlap) {
+    bool any_mfma = false;
+    for (const Group& g : h->plan.groups) any_mfma = any_mfma || g.path == Path::kMfma;
+    h->overlap = any_mfma;
+  }
+  if (e == hipSuccess && h->overlap) {
+    e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);       // default priority
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming);
+    h->ev_proj.assign(h->plan.groups.size(), nullptr);
+    for (size_t i = 0; i < h->ev_proj.size() && e == hipSuccess; ++i)
+      e = hipEventCreateWithFlags(&h->ev_proj[i], hipEventDisableTiming);
+  }
   if (e == hipSuccess && zero_state) e = launch_fill_zero(h->state, h->plan.state_bytes, st);
   if (e != hipSuccess) {
     hip_fail(g_last_error, e, "apollo_init");
@@ -393,39 +415,94 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
     h->prof_used += 6;
     e = hipEventRecord(pev[0], st);
   }
+  const bool state_bf16 = h->cfg.state_dtype == APOLLO_BF16;
+  auto fill = [&](const Group& g, hipStream_t s) -> hipError_t {
+    if (g.path == Path::kRank1 || g.path == Path::kIdentity) return hipSuccess;
+    what = "projection fill";
+    hipError_t r = launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, s);
+    if (r == hipSuccess && g.pad_g) {
+      what = "gradient padding";
+      r = launch_pad_gradient(dd + g.first, g.count, g.rows, g.cols, g.ldg, s);
+    }
+    return r;
+  };
+  auto project = [&](const Group& g, hipStream_t s) -> hipError_t {
+    what = "projection";
+    if (g.path == Path::kIdentity) return hipSuccess;
+    if (g.path == Path::kRank1)
+      return launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sp, s);
+    if (g.path == Path::kMfma)
+      return launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, g.pad_g, sp, s);
+    return launch_project_generic(dd + g.first, g.count, g.n, g.bf16, sp, s);
+  };
+  auto moments = [&](const Group& g, hipStream_t s) -> hipError_t {
+    what = "moment update";
+    if (g.path == Path::kIdentity)
+      return launch_adam_identity(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, state_bf16, sp, s);
+    return launch_adam_norms(dd + g.first, g.count, g.n, state_bf16, sp, s);
+  };
+  auto update = [&](const Group& g, hipStream_t s) -> hipError_t {
+    what = "weight update";
+    if (h->cfg.weight_dtype == APOLLO_Q8)
+      return launch_update_q8(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, sp, s);
+    return launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, h->cfg.weight_dtype == APOLLO_BF16, sp, s);
+  };
+
+  if (h->overlap && !pev) {
+    // Overlapped schedule.  Each shape group is a chain fill -> projection -> moments -> limiter ->
+    // update that touches only its own tensors and scratch; chains alternate between the caller's
+    // stream and the library's second stream, and a projection waits for the previous group's
+    // projection.  So the matrix-core projection of one group, which leaves more than half of the
+    // HBM bandwidth unused, runs while the streaming kernels (moments, update) of the group before
+    // it use that bandwidth.  The second stream starts after everything queued on the caller's
+    // stream so far and is joined back before the call returns: to the caller the step is ordinary
+    // work on its stream.
+    hipStream_t streams[2] = {st, h->side};
+    e = hipEventRecord(h->ev_fork, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(h->side, h->ev_fork, 0);
+    what = "stream fork";
+    for (size_t gi = 0; gi < h->plan.groups.size() && e == hipSuccess; ++gi) {
+      const Group& g = h->plan.groups[gi];
+      hipStream_t s = streams[gi & 1];
+      if (gi > 0) e = hipStreamWaitEvent(s, h->ev_proj[gi - 1], 0);
+      if (e == hipSuccess) e = fill(g, s);
+      if (e == hipSuccess) e = project(g, s);
+      if (e == hipSuccess) e = hipEventRecord(h->ev_proj[gi], s);
+      if (e == hipSuccess) e = moments(g, s);
+      if (e == hipSuccess) {
+        what = "limiter";
+        e = launch_finalize(dd + g.first, g.count, sp, s);
+      }
+      if (e == hipSuccess) e = update(g, s);
+    }
+    // join even after a failed launch, so that the second stream never runs ahead of the caller's
+    hipError_t ej = hipEventRecord(h->ev_join, h->side);
+    if (ej == hipSuccess) ej = hipStreamWaitEvent(st, h->ev_join, 0);
+    if (e == hipSuccess && ej != hipSuccess) {
+      e = ej;
+      what = "stream join";
+    }
+    if (e != hipSuccess) return hip_fail(h->err, e, what);
+    return APOLLO_OK;
+  }
+
+  // Serial schedule, phase by phase (also the one that is timed phase by phase when profiling).
   // (a) the transient copy of P for the groups that read it from scratch
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
-    if (g.path == Path::kRank1 || g.path == Path::kIdentity) continue;
-    e = launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, st);
-    what = "projection fill";
-    if (e == hipSuccess && g.pad_g) {
-      e = launch_pad_gradient(dd + g.first, g.count, g.rows, g.cols, g.ldg, st);
-      what = "gradient padding";
-    }
+    e = fill(g, st);
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[1], st);
   // (b) R = P G and the per-channel squared norms of G
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
-    what = "projection";
-    if (g.path == Path::kIdentity) continue;
-    if (g.path == Path::kRank1)
-      e = launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sp, st);
-    else if (g.path == Path::kMfma)
-      e = launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, g.pad_g, sp, st);
-    else
-      e = launch_project_generic(dd + g.first, g.count, g.n, g.bf16, sp, st);
+    e = project(g, st);
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[2], st);
   // (c) low-rank Adam moments, channel factors, block partial sums
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
-    if (g.path == Path::kIdentity)
-      e = launch_adam_identity(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, h->cfg.state_dtype == APOLLO_BF16, sp, st);
-    else
-      e = launch_adam_norms(dd + g.first, g.count, g.n, h->cfg.state_dtype == APOLLO_BF16, sp, st);
-    what = "moment update";
+    e = moments(g, st);
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[3], st);
   // (d) per-tensor factor, norm and limiter
@@ -437,11 +514,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   // (e) W update
   for (const Group& g : h->plan.groups) {
     if (e != hipSuccess) break;
-    if (h->cfg.weight_dtype == APOLLO_Q8)
-      e = launch_update_q8(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, sp, st);
-    else
-      e = launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, h->cfg.weight_dtype == APOLLO_BF16, sp, st);
-    what = "weight update";
+    e = update(g, st);
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[5], st);
   if (e != hipSuccess) return hip_fail(h->err, e, what);
@@ -560,6 +633,14 @@ void apollo_destroy(apollo_handle_t* h) {
     if (h->ring[i]) (void)hipHostFree(h->ring[i]);
   }
   for (hipEvent_t ev : h->prof_events) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : h->ev_proj)
+    if (ev) (void)hipEventDestroy(ev);
+  if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+  if (h->ev_join) (void)hipEventDestroy(h->ev_join);
+  if (h->side) {
+    (void)hipStreamSynchronize(h->side);      // its own stream only
+    (void)hipStreamDestroy(h->side);
+  }
   delete h;
 }
 

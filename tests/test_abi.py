@@ -15,7 +15,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _cfg(**kw):
     base = dict(rank=4, mode=A.APOLLO_CHANNEL, seed=1, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0,
                 weight_decay=0.0, nl_gamma=1.01, refresh_interval=200, bias_correction=1,
-                side=A.APOLLO_SIDE_AUTO, weight_dtype=A.APOLLO_F32, state_dtype=A.APOLLO_F32, projection=A.APOLLO_PROJ_RANDOM)
+                side=A.APOLLO_SIDE_AUTO, weight_dtype=A.APOLLO_F32, state_dtype=A.APOLLO_F32, projection=A.APOLLO_PROJ_RANDOM,
+                weight_rounding=A.APOLLO_ROUND_NEAREST, schedule=A.APOLLO_SCHEDULE_SERIAL)
     base.update(kw)
     return A.ApolloConfig(**base)
 
@@ -116,6 +117,12 @@ def test_identity_projection_sizes_full_rank_state_and_ignores_the_rank():
         assert A.apollo_state_bytes(_cfg(rank=rank, projection=A.APOLLO_PROJ_IDENTITY), shapes) == 2 * per
     assert A.apollo_state_bytes(_cfg(projection=2), shapes) == 0
     assert A.apollo_state_bytes(_cfg(rank=0), shapes) == 0
+
+
+def test_unknown_schedule_and_rounding_are_rejected():
+    assert A.apollo_state_bytes(_cfg(schedule=2), [(8, 8, 0)]) == 0
+    assert A.apollo_state_bytes(_cfg(weight_rounding=5), [(8, 8, 0)]) == 0
+    assert A.apollo_state_bytes(_cfg(schedule=A.APOLLO_SCHEDULE_OVERLAP), [(8, 8, 0)]) > 0
 
 
 def test_null_handle_calls_fail_cleanly():
