@@ -52,15 +52,20 @@ __device__ __forceinline__ void store_state(APOLLO_GLOBAL void* base, size_t idx
 // full-rank moments): "R" is the gradient itself, fp32 / bf16, r = m rows, and the squared channel
 // norm of G is b_j; only for tensors whose rows are projected (channels = stored columns), so that
 // the gradient has R's own layout.
+// Row groups of a block: its 256 threads are kRG groups of kLanes threads; the groups take the rows
+// kk = q, q + kRG, ... of the same kLanes * VEC channels.
+constexpr int kRG = 4;
+constexpr int kLanes = 256 / kRG;
+
 template <int VEC, bool SB16, int RSRC>
 __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
   typedef float vec_t __attribute__((ext_vector_type(VEC)));
-  __shared__ float red_a[3][64 * VEC], red_b[3][64 * VEC];
-  __shared__ float blk[4][64];
+  __shared__ float red_a[kRG > 1 ? kRG - 1 : 1][kLanes * VEC], red_b[kRG > 1 ? kRG - 1 : 1][kLanes * VEC];
+  __shared__ float blk[4][kLanes];
   const TensorView d(descs[blockIdx.y]);
   const int r = RSRC == 0 ? sp.r : d.m, n = d.n, n_slabs = RSRC == 0 ? d.n_slabs : 1;
-  const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int j0 = (blockIdx.x * 64 + c) * VEC;
+  const int c = threadIdx.x % kLanes, q = threadIdx.x / kLanes;
+  const int j0 = (blockIdx.x * kLanes + c) * VEC;
   const size_t slab_stride = (size_t)r * (size_t)n;
   float a[VEC], b[VEC];
 #pragma unroll
@@ -68,10 +73,10 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
   if (j0 < n) {
     // two rows per trip, all their loads issued before the arithmetic of either: six 16-byte
     // loads in flight per lane instead of three
-    for (int kk = q; kk < r; kk += 8) {
-      const bool two = kk + 4 < r;
+    for (int kk = q; kk < r; kk += 2 * kRG) {
+      const bool two = kk + kRG < r;
       const size_t idx0 = (size_t)kk * n + j0;
-      const size_t idx1 = two ? idx0 + (size_t)4 * n : idx0;
+      const size_t idx1 = two ? idx0 + (size_t)kRG * n : idx0;
       vec_t Rv[2], mo[2], vo[2];
       if constexpr (RSRC == 0) {
         Rv[0] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx0));
@@ -130,8 +135,12 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
       const int j = j0 + e;
-      const float ae = ((a[e] + red_a[0][c * VEC + e]) + red_a[1][c * VEC + e]) + red_a[2][c * VEC + e];
-      const float be = ((b[e] + red_b[0][c * VEC + e]) + red_b[1][c * VEC + e]) + red_b[2][c * VEC + e];
+      float ae = a[e], be = b[e];
+#pragma unroll
+      for (int g = 0; g < kRG - 1; ++g) {      // fixed order
+        ae += red_a[g][c * VEC + e];
+        be += red_b[g][c * VEC + e];
+      }
       float csq = RSRC == 0 ? d.colsq[j] : be;
       if (RSRC != 0) d.colsq[j] = be;
       if (n_slabs > 1) {
@@ -153,24 +162,30 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
     blk[3][c] = t3;
   }
   __syncthreads();
-  // four waves: wave w reduces quantity w over the 64 channel groups (fixed butterfly order)
+  // four waves: wave w reduces quantity w over the block's channel groups (fixed order: the lane's
+  // strided values first, then the butterfly)
   {
-    float v = blk[q][c];
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < kLanes / 64; ++i) v += blk[w][lane + 64 * i];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    if (c == 0) d.partials[(size_t)blockIdx.x * 4 + q] = v;
+    if (lane == 0) d.partials[(size_t)blockIdx.x * 4 + w] = v;
   }
 }
+
+// Blocks adam_norms_kernel needs for n channels (= entries of the per-block partial sums, times 4).
+int adam_norms_blocks(int n) { return (n & 3) == 0 ? (n / 4 + kLanes - 1) / kLanes : (n + kLanes - 1) / kLanes; }
 
 template <int RSRC>
 static hipError_t launch_adam_norms_t(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
                                       hipStream_t st) {
+  dim3 grid((unsigned)adam_norms_blocks(n), (unsigned)count, 1);
   if ((n & 3) == 0) {
-    dim3 grid((unsigned)((n / 4 + 63) / 64), (unsigned)count, 1);
     if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
     else hipLaunchKernelGGL((adam_norms_kernel<4, false, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
   } else {
-    dim3 grid((unsigned)((n + 63) / 64), (unsigned)count, 1);
     if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<1, true, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
     else hipLaunchKernelGGL((adam_norms_kernel<1, false, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
   }

@@ -127,7 +127,7 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
       if ((t.rows + sl - 1) / sl > 1020) sl = (t.rows + 1019) / 1020;
       t.n_slabs = sl;
     }
-    t.k2_blocks = (t.n & 3) == 0 ? (t.n / 4 + 63) / 64 : (t.n + 63) / 64;   // blocks of adam_norms_kernel
+    t.k2_blocks = adam_norms_blocks(t.n);
     if (identity && !t.left) t.k2_blocks = (t.n + 3) / 4;                 // of adam_identity_rows_kernel
     const size_t rn = (size_t)t.r * (size_t)t.n * state_elem;
     st = align_up(st);

@@ -143,6 +143,7 @@ hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool s
 hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepParams& sp, hipStream_t st);
 hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
                          bool w_bf16, const StepParams& sp, hipStream_t st);
+int adam_norms_blocks(int n);
 hipError_t launch_adam_identity(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool g_bf16,
                                 bool state_bf16, const StepParams& sp, hipStream_t st);
 hipError_t launch_update_q8(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
