@@ -2,8 +2,9 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b_mini] [--also a,b,...]
 
-A "step" is one pass of the whole hot path (projection scratch fill, projection, low-rank Adam +
-factors, limiter, weight update) over every matrix of a synthetic LLaMA-shaped parameter set
+A "step" is one pass of the whole hot path (projection, low-rank Adam + factors, limiter, weight
+update; plus, on the one step in T = 200 that re-samples P, the generation of its scratch copy, which
+here falls into the warm-up) over every matrix of a synthetic LLaMA-shaped parameter set
 whose weights, gradients and optimizer state are already resident in HBM.  Prints ONE JSON line:
 value = parameters updated per second over exactly K timed steps; "roofline" describes the
 kernel phase that takes the most time (algorithmic bytes or flops per step divided by that

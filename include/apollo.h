@@ -5,8 +5,8 @@
  * gradient G (same shape, bf16 or fp32), the step of Algorithm 1 of "APOLLO: SGD-like
  * Memory, AdamW-level Performance" (arXiv 2412.05270):
  *
- *   1. P  <- seeded Gaussian random projection, r x m, variance 1/r, re-generated from a
- *            counter-based generator every step and never kept as optimizer state
+ *   1. P  <- seeded Gaussian random projection, r x m, variance 1/r, generated from a
+ *            counter-based generator whenever it is needed and never kept as optimizer state
  *            (Algorithm 1 "P_t <- N_seed(0,1/r)"; Section 4.1 "Generating random projection
  *            matrix"); a new P is drawn every T steps.
  *   2. R  <- P G                                   (Algorithm 1, step 1; r x n)
@@ -165,10 +165,13 @@ apollo_status_t apollo_state_offsets(const apollo_config_t* cfg, const apollo_sh
                                      int32_t n_tensors, int32_t tensor, size_t* m_offset,
                                      size_t* v_offset, size_t* norm_offset);
 
-/* Bytes of per-step scratch (the transient P tiles, R, per-channel sums, factors, per-tensor
- * scalars, the device descriptor table and, for a bf16 tensor whose rows are projected and whose
- * row length is not a multiple of 8, a copy of its gradient with rows padded to 16 bytes); contents are meaningless between steps except for
- * apollo_debug_get.  0 on invalid arguments. */
+/* Bytes of scratch (the generated P, R, per-channel sums, factors, per-tensor scalars, the device
+ * descriptor table and, for a bf16 tensor whose rows are projected and whose row length is not a
+ * multiple of 8, a copy of its gradient with rows padded to 16 bytes).  The library keeps P there
+ * from one step to the next within a refresh interval (Algorithm 1 holds P_t until it is re-sampled)
+ * and re-generates it whenever the step's interval differs from the one it holds: P is never
+ * optimizer state, nothing in the workspace has to be saved.  The caller must not write to the
+ * workspace while the handle lives.  0 on invalid arguments. */
 size_t apollo_workspace_bytes(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t n_tensors);
 
 /* Creates a handle for a fixed tensor list.  `state` (DEVICE, >= apollo_state_bytes, 256-byte

@@ -203,6 +203,8 @@ struct apollo_handle {
   bool ring_used[kRingSlots] = {false, false, false, false};
   int ring_next = 0;
   bool have_ptrs = false;
+  int64_t p_epoch = -1;                   // refresh epoch whose P the workspace scratch holds (-1: none)
+  hipStream_t p_stream = nullptr;         // stream on which that P was written
   bool profiling = false;
   hipStream_t side = nullptr;             // second stream of the overlapped schedule (created at init)
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
@@ -416,10 +418,17 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
     e = hipEventRecord(pev[0], st);
   }
   const bool state_bf16 = h->cfg.state_dtype == APOLLO_BF16;
+  // Algorithm 1 keeps P_t until the next re-sampling.  So does the scratch copy: it is generated
+  // when the step's refresh epoch differs from the one the workspace holds (first step, every T
+  // steps, after a jump in the step number) or when the caller switched streams (the copy was
+  // written in the other stream's order); otherwise the step reads what is there.
+  const int64_t epoch = (step - 1) / (int64_t)h->cfg.refresh_interval;
+  const bool regenerate = epoch != h->p_epoch || st != h->p_stream;
+  h->p_epoch = -1;                      // until this step is enqueued completely
   auto fill = [&](const Group& g, hipStream_t s) -> hipError_t {
     if (g.path == Path::kRank1 || g.path == Path::kIdentity) return hipSuccess;
     what = "projection fill";
-    hipError_t r = launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, s);
+    hipError_t r = regenerate ? launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, s) : hipSuccess;
     if (r == hipSuccess && g.pad_g) {
       what = "gradient padding";
       r = launch_pad_gradient(dd + g.first, g.count, g.rows, g.cols, g.ldg, s);
@@ -483,6 +492,8 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
       what = "stream join";
     }
     if (e != hipSuccess) return hip_fail(h->err, e, what);
+    h->p_epoch = epoch;
+    h->p_stream = st;
     return APOLLO_OK;
   }
 
@@ -518,6 +529,8 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[5], st);
   if (e != hipSuccess) return hip_fail(h->err, e, what);
+  h->p_epoch = epoch;
+  h->p_stream = st;
   return APOLLO_OK;
 }
 

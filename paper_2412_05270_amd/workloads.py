@@ -80,6 +80,10 @@ def workload(name):
         return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=1,
                         mode="tensor", scale=MINI_SCALE, steps=20, weight_dtype=torch.uint8,
                         weight_rounding="stochastic")
+    if name == "llama7b_mini_q8_nearest":
+        return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=1,
+                        mode="tensor", scale=MINI_SCALE, steps=20, weight_dtype=torch.uint8,
+                        weight_rounding="nearest")
     if name == "llama7b_identity":       # Section 3.2's channel-wise rule with full-rank moments (no projection)
         return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=1,
                         steps=10, projection="identity")

@@ -197,3 +197,36 @@ def test_overlapped_and_serial_schedules_agree_bit_for_bit():
     for a, b in zip(*runs):
         for x, y in zip(a, b):
             assert torch.equal(x, y)
+
+
+def test_projection_scratch_follows_jumps_of_the_step_number():
+    """The generated P stays in the workspace within a refresh interval and is re-generated when
+    the step's interval differs from the one held: a handle that is stepped 1, 2, 7, 3, 8 (T = 3:
+    intervals 0, 0, 2, 0, 2) must produce, at every step, exactly the R of a fresh handle that is
+    given only that step."""
+    shapes = [(128, 512), (512, 128)]
+    wl = WL.Workload("jumps", 15, shapes, torch.bfloat16, "normal", 1e-2, rank=32, refresh_interval=3, steps=1, lr=1e-3)
+    cfg, _ = make_configs(wl)
+    weights = WL.make_weights(wl, DEV)
+    grads = WL.make_grads(wl, 1, DEV)
+    jumpy = A.ApolloStepper(cfg, [w.clone() for w in weights], grads, device=DEV)
+    for t in (1, 2, 7, 3, 8):
+        jumpy.step(t, wl.lr)
+        fresh = A.ApolloStepper(cfg, [w.clone() for w in weights], grads, device=DEV)
+        fresh.step(t, wl.lr)
+        torch.cuda.synchronize()
+        for i in range(len(shapes)):
+            assert torch.equal(jumpy.debug(i, A.APOLLO_DBG_R), fresh.debug(i, A.APOLLO_DBG_R)), (t, i)
+        fresh.close()
+    # a step on another stream re-generates too (the copy was written in the first stream's order)
+    other = torch.cuda.Stream(device=DEV)
+    other.wait_stream(torch.cuda.current_stream(DEV))
+    rc = A.apollo_step(jumpy.handle, jumpy._tensors, 8, wl.lr, other.cuda_stream)
+    assert rc == A.APOLLO_OK
+    other.synchronize()
+    fresh = A.ApolloStepper(cfg, [w.clone() for w in weights], grads, device=DEV)
+    fresh.step(8, wl.lr)
+    torch.cuda.synchronize()
+    assert torch.equal(jumpy.debug(0, A.APOLLO_DBG_R), fresh.debug(0, A.APOLLO_DBG_R))
+    jumpy.close()
+    fresh.close()
