@@ -118,8 +118,8 @@ typedef struct {
  * load path), which is why it is not the default.  Steps recorded by apollo_profile_enable use the
  * serial schedule, which is the one that has phases to time. */
 
-/* APOLLO_Q8: group-wise 8-bit weights (Section 5.4 / Table 6 combine APOLLO with "int-8 weight
- * quantization", "group size of 128", and say no more; the reading taken is the usual asymmetric
+/* APOLLO_Q8: group-wise 8-bit weights (Section 5.4 / Table 6 combine APOLLO with 8-bit integer
+ * weights quantised in groups of 128, and say no more; the reading taken is the usual asymmetric
  * min/max group quantiser with optional stochastic rounding).  W is held as unsigned 8-bit codes
  * q (rows x cols, row-major, cols a multiple of 128) and, per group of 128 consecutive elements,
  * an fp32 pair (scale, zero) in apollo_tensor_t.w_meta:  w = zero + scale * q.  A step de-quantises,
@@ -138,7 +138,7 @@ typedef struct {
  * rows x cols row-major layout, which is also what apollo_debug_get delivers for M and V;
  * APOLLO_DBG_R is not available.  State: 2 rows cols elements + 1 norm per tensor. */
 
-/* Storage in bfloat16 (the paper trains "in BF16 data format" and sizes the state at 2 bytes per
+/* Storage in bfloat16 (the paper trains in the bfloat16 format and sizes the state at 2 bytes per
  * element, Table 3, without giving a rounding rule): arithmetic is fp32; a quantity kept in
  * bfloat16 is rounded to nearest, ties to even, when it is stored, and whatever is computed after
  * that uses the stored value (R~ is formed from the rounded moments), so the state alone

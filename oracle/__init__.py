@@ -11,8 +11,8 @@ Modules
              and the projection matrix P built from them (Algorithm 1, "P_t <- N_seed(0,1/r)").
   apollo  -- the step itself (Algorithm 1; low-rank moments and scaling factor of
              Section 4.1; tensor-wise factor of Section 4.2; norm-growth limiter of Section 3.2).
-  q8      -- group-wise 8-bit weight storage (Section 5.4 / Table 6: "int-8 weight quantization ...
-             group size of 128") and the stochastic rounding of its codes.
+  q8      -- group-wise 8-bit weight storage (Section 5.4 / Table 6: 8-bit integer weights,
+             groups of 128) and the stochastic rounding of its codes.
   adamw   -- element-wise AdamW (Section 3.1, Eq. 1, with decoupled weight decay) for the
              parameters that are not projected (embeddings, norm gains, output head).
 

@@ -11,7 +11,7 @@ ordinary gradient, so the update subtracts).
 Readings taken where the paper is silent or inconsistent:
   * Algorithm 1 assumes m <= n.  A stored tensor with more rows than columns is handled as its
     transpose: the smaller dimension is projected away, channels run along the larger one
-    (Section 3.2 groups "based on the larger dimension"; the state size 2nr+2 of Table 1 with
+    (Section 3.2 forms its channels along the larger dimension; the state size 2nr+2 of Table 1 with
     n the larger dimension agrees).
   * Adam's bias correction is applied (Algorithm 1 calls "AdamW(R_t, ...)"); eps is added after
     the bias-corrected square root.  bias_correction=False gives the literal Section 4.1 formula.
@@ -22,7 +22,7 @@ Readings taken where the paper is silent or inconsistent:
   * A channel whose projected gradient is exactly zero gets s_j = 0 (0/0 otherwise).
   * M^R, V^R are kept when P is re-sampled.
   * Steps are 1-based: P is re-sampled when (t-1) mod T == 0, epoch = (t-1) div T.
-  * Storage types.  The paper trains "in BF16 data format" and sizes its state at 2 bytes per
+  * Storage types.  The paper trains in the bfloat16 format and sizes its state at 2 bytes per
     element (Table 3), but gives no rounding rule.  Taken here: arithmetic in (at least) binary32;
     a quantity kept in bfloat16 (W with weight_dtype="bf16"; M^R, V^R with state_dtype="bf16") is
     rounded to nearest, ties to even, when it is stored, and everything computed after that uses
