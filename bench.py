@@ -89,7 +89,7 @@ def algorithmic_work(wl):
     }
 
 
-def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev):
+def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=True):
     cfg = make_cfg(A, wl)
     metas = None
     if wl.weight_dtype == torch.uint8:
@@ -154,7 +154,7 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev):
         "projection_tflops": work["projection"]["flops"] / (phase_ms["projection"] * 1e-3) / 1e12,
         "finite": finite, "state_gb": state_bytes / 1e9, "workspace_gb": ws_bytes / 1e9,
     }
-    if wl.rank % 32 == 0 and wl.projection != "identity" and wl.grad_dtype == torch.bfloat16:
+    if overlap_leg and wl.rank % 32 == 0 and wl.projection != "identity" and wl.grad_dtype == torch.bfloat16:
         # the optional two-stream schedule (shape groups as overlapping chains), same steps again
         cfg.schedule = A.APOLLO_SCHEDULE_OVERLAP
         st = A.ApolloStepper(cfg, weights, grads, device=dev, metas=metas)
@@ -256,6 +256,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-adamw-rest", action="store_true",
                     help="skip the element-wise AdamW launch on the non-projected parameters")
+    ap.add_argument("--no-overlap-leg", action="store_true",
+                    help="skip the extra, separately timed run of the optional two-stream schedule (for "
+                         "profiles of the default schedule alone)")
     ap.add_argument("--only-adamw-rest", action="store_true", help="run only that launch (for profiling it)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run the library's plain copy kernel on 4 GiB a few times (known traffic: "
@@ -292,7 +295,7 @@ def main():
     weights = WL.make_q8_weights(wl, dev) if wl.weight_dtype == torch.uint8 else WL.make_weights(wl, dev)
     grads = WL.make_grads(wl, 1, dev)
     torch.cuda.synchronize()
-    main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev)
+    main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg)
     also = []
     cur_wdt = wl.weight_dtype
     for name in [a for a in args.also.split(",") if a]:
@@ -303,7 +306,7 @@ def main():
             torch.cuda.empty_cache()
             weights = WL.make_q8_weights(wl2, dev) if wl2.weight_dtype == torch.uint8 else WL.make_weights(wl2, dev)
             cur_wdt = wl2.weight_dtype
-        r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev)
+        r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg)
         also.append({"workload": describe(wl2), "value": r2["value"], "unit": "params/s", "ms_per_step": r2["ms_per_step"],
                      "phase_ms": r2["phase_ms"], "overlap_schedule_ms_per_step": r2.get("overlap_schedule_ms_per_step"),
                      "roofline": r2["roofline"],
