@@ -259,6 +259,8 @@ def main():
     ap.add_argument("--no-overlap-leg", action="store_true",
                     help="skip the extra, separately timed run of the optional two-stream schedule (for "
                          "profiles of the default schedule alone)")
+    ap.add_argument("--library-gemm-context", type=int, default=0, metavar="RANK",
+                    help="also time torch.matmul on the projection's contraction at this rank (context only)")
     ap.add_argument("--only-adamw-rest", action="store_true", help="run only that launch (for profiling it)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run the library's plain copy kernel on 4 GiB a few times (known traffic: "
@@ -320,6 +322,12 @@ def main():
         del weights, grads
         torch.cuda.empty_cache()
         rest = measure_adamw_rest(A, torch, args.steps, args.warmup, dev)
+    lib = None
+    if args.library_gemm_context > 0:
+        if args.no_adamw_rest:
+            del weights, grads
+            torch.cuda.empty_cache()
+        lib = library_gemm_context(torch, wl, args.library_gemm_context, dev)
     out = {
         "metric": "APOLLO step params/s + % of HBM/MFMA roofline, LLaMA-7B-shaped params",
         "value": main_res["value"], "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -331,9 +339,49 @@ def main():
         "roofline": main_res["roofline"], "cpu_baseline": cpu, "phase_ms": main_res["phase_ms"],
         "overlap_schedule_ms_per_step": main_res.get("overlap_schedule_ms_per_step"),
         "whole_step_hbm_frac": main_res["whole_step_hbm_frac"], "projection_roofline": main_res["projection_roofline"],
-        "finite": main_res["finite"], "also": also, "adamw_rest": rest,
+        "finite": main_res["finite"], "also": also, "adamw_rest": rest, "library_gemm_context": lib,
     }
     print(json.dumps(out))
+
+
+def library_gemm_context(torch, wl, rank, dev, reps=20):
+    """Context only, never part of `value`: torch.matmul (the vendor GEMM library) on the same
+    contraction as the rank-`rank` projection of this workload's shape groups -- bf16 operands, bf16
+    output, no column sums, one batched call per group -- timed with events.  It shows what the
+    stock library reaches on this skinny shape (r x m by m x n per tensor) on the same chip."""
+    groups = {}
+    for s in wl.shapes:
+        groups[s] = groups.get(s, 0) + 1
+    out, total_ms, total_flops = [], 0.0, 0.0
+    for (rows, cols), count in sorted(groups.items()):
+        G = torch.randn(count, rows, cols, device=dev, dtype=torch.bfloat16) * wl.grad_scale
+        m = min(rows, cols)
+        P = torch.randn(rank, m, device=dev, dtype=torch.bfloat16) / math.sqrt(rank)
+        if rows <= cols:
+            R = torch.empty(count, rank, cols, device=dev, dtype=torch.bfloat16)
+            f = lambda: torch.matmul(P, G, out=R)
+        else:
+            Pt = P.t().contiguous()
+            R = torch.empty(count * rows, rank, device=dev, dtype=torch.bfloat16)
+            G2 = G.view(count * rows, cols)
+            f = lambda: torch.mm(G2, Pt, out=R)
+        for _ in range(3):
+            f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        flops = 2.0 * rank * rows * cols * count
+        out.append({"shape": "%dx%d x%d" % (rows, cols, count), "ms": ms, "tflops": flops / ms / 1e9})
+        total_ms += ms
+        total_flops += flops
+        del G, R
+        torch.cuda.empty_cache()
+    return {"kind": "torch.matmul, bf16 in and out, batched per shape group; context, not the product path",
+            "rank": rank, "ms": total_ms, "tflops": total_flops / total_ms / 1e9, "groups": out}
 
 
 def describe(wl):
