@@ -135,3 +135,24 @@ def test_step_on_q8_weights_by_hand_and_why_stochastic_rounding_is_there():
         moved[mode] = total / 200 / float(qw0.scale[0, 0])
     assert moved[q8.NEAREST] == pytest.approx(0.0, abs=1e-6)
     assert moved[q8.STOCHASTIC] == pytest.approx(0.3, abs=4 * np.sqrt(0.3 * 0.7 / 200))
+
+
+def test_step_draws_its_rounding_offsets_for_its_own_tensor_and_step():
+    """The offsets a step uses are the stream's values for (seed, tensor index, step number): the
+    Philox words are computed here directly, for two tensors and two steps, and must differ between
+    them (a step that passed another tensor's index or a shifted step number would reuse offsets)."""
+    rng = np.random.default_rng(6)
+    w0 = _rand_w(rng, rows=2, cols=128)
+    qw0, _ = q8.quantise(w0, np.full(w0.shape, 0.5))
+    G = rng.normal(size=(2, 128))
+    seen = []
+    for tensor_id, t in ((3, 5), (3, 4), (0, 5)):
+        cfg = apollo.Config(rank=1, nl_gamma=0.0, weight_dtype="q8", weight_rounding=q8.STOCHASTIC, seed=77)
+        W = q8.Q8Weights(qw0.codes.copy(), qw0.scale.copy(), qw0.zero.copy())
+        info = apollo.step(cfg, apollo.init_state(cfg, 2, 128), W, G, t, 1e-3, tensor_id=tensor_id)
+        o = np.arange(2 * 128 // 8, dtype=np.uint64)
+        words = np.stack(philox4x32_10(o, np.uint64(t), np.uint64(0x80000000 + tensor_id), np.uint64(0) * o, 77, 0), axis=-1)
+        u = np.stack([words & 0xFFFF, words >> 16], axis=-1).reshape(2, 128) / 65536.0
+        assert np.array_equal(info["q8_u"], u)
+        seen.append(u)
+    assert not np.array_equal(seen[0], seen[1]) and not np.array_equal(seen[0], seen[2])

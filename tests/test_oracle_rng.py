@@ -117,6 +117,21 @@ def test_cos_sin_accuracy_against_libm():
     assert np.max(np.abs(s - np.sin(th))) < 2e-7
 
 
+def test_pair_is_radius_times_cosine_then_radius_times_sine():
+    """Box-Muller's two outputs in their order: (rho cos theta, rho sin theta), against libm.  The two
+    orders have the same distribution, so only this pin tells them apart."""
+    n1, xa = _strided_words(59)
+    n2, xb = _strided_words(67)
+    k = min(len(n1), len(n2))
+    n1, xa, n2, xb = n1[:k], xa[:k], n2[::-1][:k].copy(), xb[::-1][:k].copy()
+    za, zb = gauss.gaussian_pair(xa, xb)
+    rho = np.sqrt(-2.0 * np.log((n1.astype(np.float64) + 1.0) / 2.0 ** 24))
+    th = 2.0 * np.pi * n2.astype(np.float64) / 2.0 ** 24
+    assert np.max(np.abs(za - rho * np.cos(th))) < 3e-6
+    assert np.max(np.abs(zb - rho * np.sin(th))) < 3e-6
+    assert np.max(np.abs(za - rho * np.sin(th))) > 1.0            # and not the other way round
+
+
 def test_low_byte_of_each_word_is_unused():
     xa = np.array([0x12345600, 0x123456FF], dtype=np.uint32)
     za, zb = gauss.gaussian_pair(xa, xa[::-1].copy())

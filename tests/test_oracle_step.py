@@ -212,6 +212,12 @@ def test_forced_side_overrides_the_shape_rule():
     assert st.M.shape == (2, 4)                         # channels are the 4 rows now
     info = apollo.step(cfg, st, np.zeros((4, 10)), G, 1, lr=1e-2)
     assert info["s"].shape == (4,) and not info["left"]
+    cfg = _cfg(rank=2, side="left")                     # and the other way: a tall tensor projected along its rows
+    st = apollo.init_state(cfg, 10, 4)
+    assert st.M.shape == (2, 4)                         # channels are the 4 columns
+    info = apollo.step(cfg, st, np.zeros((10, 4)), G.T.copy(), 1, lr=1e-2)
+    assert info["s"].shape == (4,) and info["left"]
+    assert apollo.is_left(10, 4) is False and apollo.is_left(10, 4, "left") is True
 
 
 # ------------------------------------------------------- identities from the appendix
@@ -510,9 +516,10 @@ def test_bf16_weights_round_after_the_update_and_small_updates_vanish():
 # ----------------------------------------------------------------------------- no projection (Section 3.2)
 def test_identity_projection_is_the_structured_rule_of_section_3_2_by_brute_force():
     """Full-rank moments of G, G~ = M^ / (sqrt(V^) + eps), s_j = ||G~[:, j]|| / ||G[:, j]|| (Eq. 2),
-    update G diag(s): scalar loops on a small tensor, both orientations."""
+    update G diag(s): scalar loops on a small tensor, both orientations and a square one (where a
+    sum over the wrong axis would still have the right length)."""
     rng = np.random.default_rng(8)
-    for rows, cols in ((3, 5), (5, 3)):
+    for rows, cols in ((3, 5), (5, 3), (4, 4)):
         cfg = _cfg(projection="identity", rank=99, nl_gamma=0.0, eps=1e-6)
         left = rows <= cols
         m, n = (rows, cols) if left else (cols, rows)
