@@ -298,6 +298,9 @@ def main():
     grads = WL.make_grads(wl, 1, dev)
     torch.cuda.synchronize()
     main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg)
+    cpu = None
+    if not args.no_cpu_baseline:      # before `weights` is replaced by another variant's storage type
+        cpu = cpu_baseline(A, WL, torch, wl, weights, grads)
     also = []
     cur_wdt = wl.weight_dtype
     for name in [a for a in args.also.split(",") if a]:
@@ -314,9 +317,6 @@ def main():
                      "roofline": r2["roofline"],
                      "whole_step_hbm_frac": r2["whole_step_hbm_frac"],
                      "projection_roofline": r2["projection_roofline"], "finite": r2["finite"]})
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(A, WL, torch, wl, weights, grads)
     rest = None
     if not args.no_adamw_rest:
         del weights, grads
