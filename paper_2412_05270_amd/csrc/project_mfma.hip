@@ -223,7 +223,11 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
   using C = Cfg<MT, WM>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   // XCD-aware numbering: block w runs on XCD w % 8; XCD x works through tensors x, x+8, ...
-  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  // Within a tensor the row tiles of one channel tile are neighbours on their XCD: they read the
+  // same tile of G at about the same time, so all but the first find it in that XCD's L2.
+  const int row_tiles = sp.r / C::RT;
+  const int xcd = blockIdx.x % kXcds, slot = (blockIdx.x / kXcds) / row_tiles;
+  const int row_tile = (blockIdx.x / kXcds) % row_tiles;
   const int tensor = xcd + kXcds * (slot / tiles);
   if (tensor >= count) return;
   const TensorView d(descs[tensor]);
@@ -238,7 +242,7 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
   // read the zero padding and are not stored.  With columns projected a channel is a stored row
   // and the tile ends exactly at n.
   cx.n0 = min((slot % tiles) * kNT, LEFT ? (d.n - kNT + 7) & ~7 : d.n - kNT);
-  cx.rbase = blockIdx.y * C::RT;
+  cx.rbase = row_tile * C::RT;
   cx.tid = threadIdx.x; cx.lane = cx.tid & 63; cx.wave = __builtin_amdgcn_readfirstlane(cx.tid >> 6);
   cx.wm = cx.wave / C::WN; cx.wn = cx.wave % C::WN;
   const int stages = cx.m / kKT;
@@ -302,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
       }
     }
   }
-  if (blockIdx.y == 0) {
+  if (row_tile == 0) {
     // lanes l and l + 32 hold the two k-halves of channel (tile, l % 32)
     const float t = sq + __shfl_xor(sq, 32, 64);
     const int j = cx.n0 + 32 * cx.tile_of(0) + lane;
@@ -323,7 +327,7 @@ hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, bool padded, 
   }
   const int tiles = (n + kNT - 1) / kNT;
   const int per_xcd = (count + kXcds - 1) / kXcds;
-  dim3 grid((unsigned)(kXcds * per_xcd * tiles), (unsigned)(sp.r / C::RT), 1);
+  dim3 grid((unsigned)(kXcds * per_xcd * tiles * (sp.r / C::RT)), 1, 1);
   hipLaunchKernelGGL((project_mfma_kernel<MT, WM, LEFT>), grid, dim3(kThreads), lds_bytes, st, d_descs, sp, tiles, count,
                      padded ? 1 : 0);
   return hipGetLastError();
