@@ -1,14 +1,16 @@
 // Low-rank Adam moments + scaling factors (Algorithm 1, steps 2-3; Section 4.1, Eq. 4; Section
 // 4.2), the per-tensor norm-growth limiter (Section 3.2, Eq. 3) and the scaled weight update
 // (Algorithm 1, step 4).
+#include <type_traits>
+
 #include "apollo_internal.h"
 
 namespace apollo {
 
 // ---------------------------------------------------------------------------------------------
-// Moments and norms.  Block = 64 channel groups x 4 rank lanes; a channel group is VEC (4, or 1
-// when n is not a multiple of 4) consecutive channels, so a wave touches 1 KB contiguous per row
-// of R, M^R, V^R.  Thread (c, q) walks rows q, q+4, ... of its channels, accumulating
+// Moments and norms.  Block = 64 channel groups x 4 rank lanes; a channel group is 4 consecutive
+// channels, so a wave touches 1 KB contiguous per row of R, M^R, V^R (when n is not a multiple of
+// 4 the quads are only element-aligned and the last group of a row is ragged).  Thread (c, q) walks rows q, q+4, ... of its channels, accumulating
 // a_j = sum R~^2 and b_j = sum R^2 in registers; the four rank lanes are combined through LDS in
 // a fixed order, then the channels of the block are reduced to four block partials.  No
 // atomics: results are run-to-run identical.  M^R, V^R and R are streamed (non-temporal).
@@ -16,13 +18,32 @@ namespace apollo {
 // VEC consecutive elements of a moment array at element index idx, as floats; the array is fp32
 // or bfloat16 (SB16).  Streamed (non-temporal).  idx is a multiple of VEC and the arrays are
 // aligned so that the VEC elements form one naturally aligned access.
-template <int VEC, bool SB16>
+template <int VEC, bool SB16, bool UA = false>
 __device__ __forceinline__ float __attribute__((ext_vector_type(VEC))) load_state(const APOLLO_GLOBAL void* base, size_t idx) {
   typedef float vec_t __attribute__((ext_vector_type(VEC)));
+  // UA: idx is any element index; the access is only aligned to its element type (the compiler
+  // then picks instructions that are valid for that alignment)
+  typedef float vec_ua_t __attribute__((ext_vector_type(VEC), aligned(4)));
+  typedef uint32_t u32x2_ua_t __attribute__((ext_vector_type(2), aligned(2)));
   if constexpr (!SB16) {
-    return __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(reinterpret_cast<const APOLLO_GLOBAL float*>(base) + idx));
+    if constexpr (UA) {
+      const vec_ua_t t = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_ua_t*>(reinterpret_cast<const APOLLO_GLOBAL float*>(base) + idx));
+      vec_t v;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[e] = t[e];
+      return v;
+    } else {
+      return __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(reinterpret_cast<const APOLLO_GLOBAL float*>(base) + idx));
+    }
   } else if constexpr (VEC == 4) {
-    const u32x2_t h = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x2_t*>(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(base) + idx));
+    u32x2_t h;
+    if constexpr (UA) {
+      const u32x2_ua_t t = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x2_ua_t*>(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(base) + idx));
+      h.x = t.x;
+      h.y = t.y;
+    } else {
+      h = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x2_t*>(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(base) + idx));
+    }
     vec_t v = {__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xFFFF0000u), __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xFFFF0000u)};
     return v;
   } else {
@@ -33,19 +54,56 @@ __device__ __forceinline__ float __attribute__((ext_vector_type(VEC))) load_stat
 }
 
 // The values are already bfloat16 numbers when SB16 (rounded by the caller): the store truncates.
-template <int VEC, bool SB16>
+template <int VEC, bool SB16, bool UA = false>
 __device__ __forceinline__ void store_state(APOLLO_GLOBAL void* base, size_t idx, float __attribute__((ext_vector_type(VEC))) v) {
   typedef float vec_t __attribute__((ext_vector_type(VEC)));
+  typedef float vec_ua_t __attribute__((ext_vector_type(VEC), aligned(4)));
+  typedef uint32_t u32x2_ua_t __attribute__((ext_vector_type(2), aligned(2)));
   if constexpr (!SB16) {
-    __builtin_nontemporal_store(v, reinterpret_cast<APOLLO_GLOBAL vec_t*>(reinterpret_cast<APOLLO_GLOBAL float*>(base) + idx));
+    if constexpr (UA) {
+      vec_ua_t t;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) t[e] = v[e];
+      __builtin_nontemporal_store(t, reinterpret_cast<APOLLO_GLOBAL vec_ua_t*>(reinterpret_cast<APOLLO_GLOBAL float*>(base) + idx));
+    } else {
+      __builtin_nontemporal_store(v, reinterpret_cast<APOLLO_GLOBAL vec_t*>(reinterpret_cast<APOLLO_GLOBAL float*>(base) + idx));
+    }
   } else if constexpr (VEC == 4) {
     u32x2_t h;
     h.x = (__float_as_uint(v[0]) >> 16) | (__float_as_uint(v[1]) & 0xFFFF0000u);
     h.y = (__float_as_uint(v[2]) >> 16) | (__float_as_uint(v[3]) & 0xFFFF0000u);
-    __builtin_nontemporal_store(h, reinterpret_cast<APOLLO_GLOBAL u32x2_t*>(reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base) + idx));
+    if constexpr (UA) {
+      u32x2_ua_t t;
+      t.x = h.x;
+      t.y = h.y;
+      __builtin_nontemporal_store(t, reinterpret_cast<APOLLO_GLOBAL u32x2_ua_t*>(reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base) + idx));
+    } else {
+      __builtin_nontemporal_store(h, reinterpret_cast<APOLLO_GLOBAL u32x2_t*>(reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base) + idx));
+    }
   } else {
     reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base)[idx] = (uint16_t)(__float_as_uint(v[0]) >> 16);
   }
+}
+
+// The first `cnt` (1..3) of four consecutive elements, one at a time: the ragged end of a row whose
+// length is not a multiple of 4.  Elements beyond cnt read as 0 and are not written.
+template <bool SB16>
+__device__ __forceinline__ f32x4_t load_state_part(const APOLLO_GLOBAL void* base, size_t idx, int cnt) {
+  f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int e = 0; e < 3; ++e)
+    if (e < cnt) v[e] = load_state<1, SB16>(base, idx + e)[0];
+  return v;
+}
+template <bool SB16>
+__device__ __forceinline__ void store_state_part(APOLLO_GLOBAL void* base, size_t idx, f32x4_t v, int cnt) {
+  typedef float one_t __attribute__((ext_vector_type(1)));
+#pragma unroll
+  for (int e = 0; e < 3; ++e)
+    if (e < cnt) {
+      one_t o = {v[e]};
+      store_state<1, SB16>(base, idx + e, o);
+    }
 }
 
 // RSRC: where R comes from.  0: the projection's scratch R (fp32).  1 / 2: no projection (Section 3.2,
@@ -57,8 +115,11 @@ __device__ __forceinline__ void store_state(APOLLO_GLOBAL void* base, size_t idx
 constexpr int kRG = 4;
 constexpr int kLanes = 256 / kRG;
 
-template <int VEC, bool SB16, int RSRC>
+// UA (with VEC = 4): n is not a multiple of 4, so a row of R, M^R, V^R starts at any element: the
+// quads are accessed with element alignment only, and the last thread of a row holds 1..3 channels.
+template <int VEC, bool SB16, int RSRC, bool UA = false>
 __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
+  static_assert(!UA || VEC == 4, "element-aligned quads");
   typedef float vec_t __attribute__((ext_vector_type(VEC)));
   __shared__ float red_a[kRG > 1 ? kRG - 1 : 1][kLanes * VEC], red_b[kRG > 1 ? kRG - 1 : 1][kLanes * VEC];
   __shared__ float blk[4][kLanes];
@@ -67,6 +128,29 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
   const int c = threadIdx.x % kLanes, q = threadIdx.x / kLanes;
   const int j0 = (blockIdx.x * kLanes + c) * VEC;
   const size_t slab_stride = (size_t)r * (size_t)n;
+  const int cnt = UA ? min(VEC, n - j0) : VEC;     // channels of this thread that exist (if j0 < n)
+  // VEC elements of an fp32 / moment / gradient array at element idx: one access, or the ragged end
+  auto ld = [&](auto sb16, const APOLLO_GLOBAL void* base, size_t idx) -> vec_t {
+    constexpr bool B = decltype(sb16)::value;
+    if constexpr (UA) {
+      if (cnt == VEC) return load_state<VEC, B, true>(base, idx);
+      return load_state_part<B>(base, idx, cnt);
+    } else {
+      return load_state<VEC, B>(base, idx);
+    }
+  };
+  auto st = [&](auto sb16, APOLLO_GLOBAL void* base, size_t idx, vec_t v) {
+    constexpr bool B = decltype(sb16)::value;
+    if constexpr (UA) {
+      if (cnt == VEC) store_state<VEC, B, true>(base, idx, v);
+      else store_state_part<B>(base, idx, v, cnt);
+    } else {
+      store_state<VEC, B>(base, idx, v);
+    }
+  };
+  using f32_tag = std::integral_constant<bool, false>;
+  using state_tag = std::integral_constant<bool, SB16>;
+  using grad_tag = std::integral_constant<bool, RSRC == 2>;
   float a[VEC], b[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) a[e] = b[e] = 0.f;
@@ -79,24 +163,23 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
       const size_t idx1 = two ? idx0 + (size_t)kRG * n : idx0;
       vec_t Rv[2], mo[2], vo[2];
       if constexpr (RSRC == 0) {
-        Rv[0] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx0));
-        Rv[1] = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + idx1));
+        Rv[0] = ld(f32_tag{}, d.R, idx0);
+        Rv[1] = ld(f32_tag{}, d.R, idx1);
       } else {
-        Rv[0] = load_state<VEC, RSRC == 2>(d.g, idx0);
-        Rv[1] = load_state<VEC, RSRC == 2>(d.g, idx1);
+        Rv[0] = ld(grad_tag{}, d.g, idx0);
+        Rv[1] = ld(grad_tag{}, d.g, idx1);
       }
-      mo[0] = load_state<VEC, SB16>(d.M, idx0);
-      mo[1] = load_state<VEC, SB16>(d.M, idx1);
-      vo[0] = load_state<VEC, SB16>(d.V, idx0);
-      vo[1] = load_state<VEC, SB16>(d.V, idx1);
+      mo[0] = ld(state_tag{}, d.M, idx0);
+      mo[1] = ld(state_tag{}, d.M, idx1);
+      vo[0] = ld(state_tag{}, d.V, idx0);
+      vo[1] = ld(state_tag{}, d.V, idx1);
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         if (h == 1 && !two) break;
         const size_t idx = h ? idx1 : idx0;
         if (n_slabs > 1) {
-          for (int sl = 1; sl < n_slabs; ++sl)
-            Rv[h] += *reinterpret_cast<const APOLLO_GLOBAL vec_t*>(d.R + sl * slab_stride + idx);
-          *reinterpret_cast<APOLLO_GLOBAL vec_t*>(d.R + idx) = Rv[h];
+          for (int sl = 1; sl < n_slabs; ++sl) Rv[h] += ld(f32_tag{}, d.R, sl * slab_stride + idx);
+          st(f32_tag{}, d.R, idx, Rv[h]);
         }
         vec_t mn, vn;
 #pragma unroll
@@ -117,8 +200,8 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
           mn[e] = me;
           vn[e] = ve;
         }
-        store_state<VEC, SB16>(d.M, idx, mn);
-        store_state<VEC, SB16>(d.V, idx, vn);
+        st(state_tag{}, d.M, idx, mn);
+        st(state_tag{}, d.V, idx, vn);
       }
     }
   }
@@ -134,6 +217,7 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
   if (q == 0 && j0 < n) {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
+      if (UA && e >= cnt) break;
       const int j = j0 + e;
       float ae = a[e], be = b[e];
 #pragma unroll
@@ -176,7 +260,7 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
 }
 
 // Blocks adam_norms_kernel needs for n channels (= entries of the per-block partial sums, times 4).
-int adam_norms_blocks(int n) { return (n & 3) == 0 ? (n / 4 + kLanes - 1) / kLanes : (n + kLanes - 1) / kLanes; }
+int adam_norms_blocks(int n) { return ((n + 3) / 4 + kLanes - 1) / kLanes; }
 
 template <int RSRC>
 static hipError_t launch_adam_norms_t(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
@@ -186,8 +270,8 @@ static hipError_t launch_adam_norms_t(const TensorDesc* d_descs, int count, int 
     if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
     else hipLaunchKernelGGL((adam_norms_kernel<4, false, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
   } else {
-    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<1, true, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
-    else hipLaunchKernelGGL((adam_norms_kernel<1, false, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
+    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true, RSRC, true>), grid, dim3(256), 0, st, d_descs, sp);
+    else hipLaunchKernelGGL((adam_norms_kernel<4, false, RSRC, true>), grid, dim3(256), 0, st, d_descs, sp);
   }
   return hipGetLastError();
 }

@@ -31,7 +31,7 @@ struct TensorDesc {
   int32_t left;        // 1: m = rows (R = P G), 0: m = cols (R = G P^T)
   int32_t tensor_id;   // index in the caller's list: part of the generator's counter
   int32_t n_slabs;     // number of partial sums the projection kernel leaves along m
-  int32_t k2_blocks;   // blocks of the moment kernel (256 or 64 channels each)
+  int32_t k2_blocks;   // blocks of the moment kernel (256 channels each)
   int32_t ldg;         // row pitch, in elements, of the gradient the matrix-core projection reads (gpad or g)
 };
 
