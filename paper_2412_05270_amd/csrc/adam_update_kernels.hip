@@ -631,6 +631,25 @@ hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int col
 // yields the eight 16-bit rounding offsets.  cols is a multiple of 128: a group never straddles a
 // row, and a 16-lane group is either whole or absent at the end of the tensor.
 // ---------------------------------------------------------------------------------------------
+// min (MAX = false) or max over each aligned run of 16 lanes, in every lane of the run, by DPP lane
+// permutations: swap within pairs, swap the pairs of a quad, mirror each half of the row, mirror the
+// row.  A lane whose partner is inactive keeps its own value.
+template <bool MAX>
+__device__ __forceinline__ float row16_reduce(float v) {
+#define APOLLO_ROW_STEP(ctrl)                                                                              \
+  {                                                                                                        \
+    const int self = __builtin_bit_cast(int, v);                                                           \
+    const float o = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(self, self, ctrl, 0xF, 0xF, false)); \
+    v = MAX ? fmaxf(v, o) : fminf(v, o);                                                                   \
+  }
+  APOLLO_ROW_STEP(0xB1)    // quad_perm [1,0,3,2]
+  APOLLO_ROW_STEP(0x4E)    // quad_perm [2,3,0,1]
+  APOLLO_ROW_STEP(0x141)   // row_half_mirror
+  APOLLO_ROW_STEP(0x140)   // row_mirror
+#undef APOLLO_ROW_STEP
+  return v;
+}
+
 template <bool BF16, int CHAN>
 __global__ __launch_bounds__(256) void update_q8_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
                                                         FastDiv div_cols) {
@@ -663,24 +682,24 @@ __global__ __launch_bounds__(256) void update_q8_kernel(const TensorDesc* __rest
   load_elems<8, BF16, false>(d.g, e0, g);
   const u32x2_t codes = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x2_t*>(d.w) + oct);
   const size_t group = e0 >> 7;
-  const float scale = d.w_meta[2 * group], zero = d.w_meta[2 * group + 1];
+  // w' = w (1 - lr lambda) - k g with w = zero + scale q: the decay goes into the group's pair once
+  const float keep = 1.f - decay;
+  const float scale = d.w_meta[2 * group] * keep, zero = d.w_meta[2 * group + 1] * keep;
   float w[8];
   float lo = 3.4e38f, hi = -3.4e38f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const uint32_t q = ((e < 4 ? codes.x : codes.y) >> (8 * (e & 3))) & 0xFFu;
-    const float wo = __builtin_fmaf(scale, (float)q, zero);
-    w[e] = wo - __builtin_fmaf(k[e], g[e], decay * wo);
+    w[e] = __builtin_fmaf(-k[e], g[e], __builtin_fmaf(scale, (float)q, zero));
     lo = fminf(lo, w[e]);
     hi = fmaxf(hi, w[e]);
   }
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) {
-    lo = fminf(lo, __shfl_xor(lo, off, 64));
-    hi = fmaxf(hi, __shfl_xor(hi, off, 64));
-  }
+  // a group is the 16 lanes of one DPP row: butterfly by lane permutations within the row (pairs,
+  // quads, mirrored halves, mirrored row); every lane ends with the group's min and max
+  lo = row16_reduce<false>(lo);
+  hi = row16_reduce<true>(hi);
   const float range = hi - lo;
-  const float inv = range > 0.f ? 255.f / range : 0.f;
+  const float inv = range > 0.f ? 255.f * __builtin_amdgcn_rcpf(range) : 0.f;
   float u[8];
   if (sp.q8_stochastic) {
     uint32_t c[4] = {(uint32_t)oct, sp.step_lo, 0x80000000u | (uint32_t)d.tensor_id, (uint32_t)(oct >> 32)};
@@ -697,10 +716,10 @@ __global__ __launch_bounds__(256) void update_q8_kernel(const TensorDesc* __rest
   uint32_t out[2] = {0u, 0u};
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const float x = (w[e] - lo) * inv;
-    uint32_t q = (uint32_t)__builtin_floorf(x + u[e]);
-    q = q > 255u ? 255u : q;
-    out[e >> 2] |= q << (8 * (e & 3));
+    // floor(x + u), then the conversion that saturates to 0..255 and places the byte (its own
+    // rounding, to nearest, has nothing left to round)
+    const float y = __builtin_floorf(__builtin_fmaf(w[e] - lo, inv, u[e]));
+    out[e >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(y, e & 3, out[e >> 2]);
   }
   u32x2_t packed = {out[0], out[1]};
   __builtin_nontemporal_store(packed, reinterpret_cast<APOLLO_GLOBAL u32x2_t*>(d.w) + oct);
