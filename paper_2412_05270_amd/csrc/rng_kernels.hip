@@ -54,7 +54,7 @@ hipError_t launch_fill_projection(const TensorDesc* d_descs, int count, int r, i
 // Copy of a bf16 gradient whose row length is not a multiple of eight elements into a scratch
 // matrix with rows padded (zeros) to ldg elements, so that every row starts on a 16-byte boundary
 // as the direct-to-LDS loads of the matrix-core projection need.  One thread per eight output
-// elements; the source is read element by element because its rows have no common alignment.
+// elements, read with one element-aligned 16-byte load (the source rows have no common alignment).
 __global__ __launch_bounds__(256) void pad_gradient_kernel(const TensorDesc* __restrict__ descs, int rows, int cols,
                                                            int ldg) {
   const TensorView d(descs[blockIdx.y]);
@@ -65,8 +65,16 @@ __global__ __launch_bounds__(256) void pad_gradient_kernel(const TensorDesc* __r
   const int c0 = 8 * (int)(t % (size_t)oct_per_row);
   const APOLLO_GLOBAL uint16_t* src = reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(d.g) + (size_t)row * cols;
   uint32_t h[8];
+  if (c0 + 8 <= cols) {
+    // one 16-byte load that is only element-aligned (the rows have no common alignment)
+    typedef uint16_t u16x8_ua_t __attribute__((ext_vector_type(8), aligned(2)));
+    const u16x8_ua_t v = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u16x8_ua_t*>(src + c0));
 #pragma unroll
-  for (int e = 0; e < 8; ++e) h[e] = c0 + e < cols ? (uint32_t)src[c0 + e] : 0u;
+    for (int e = 0; e < 8; ++e) h[e] = v[e];
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = c0 + e < cols ? (uint32_t)src[c0 + e] : 0u;
+  }
   reinterpret_cast<APOLLO_GLOBAL u32x4_t*>(d.gpad)[t] =
       mk_u4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
 }
