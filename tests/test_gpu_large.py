@@ -44,3 +44,64 @@ def test_full_size_q8_mini():
     wl = WL.workload("llama7b_mini_q8")
     _run(wl, 2, 1e-5, check_ids=_first_and_last_layer(wl), progress=True)
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("shape,rank", [((2048, 589824), 64), ((589824, 2048), 64), ((2048, 589824), 1),
+                                        ((589824, 2048), 1)])
+def test_one_tensor_beyond_four_gibibytes_on_sampled_channels(shape, rank):
+    """A single tensor of 1.2 G elements (W 4.8 GB, G 2.4 GB: element and byte offsets beyond 2^31 and
+    2^32, channel counts far above any LLaMA shape), both orientations, matrix-core and rank-1
+    projection.  With channel-wise factors and the limiter off every channel is independent of the
+    others, so the oracle steps a sub-tensor made of sampled channels (same seed, tensor index and
+    projected dimension, hence the same P) and must agree with those channels of the big one."""
+    import numpy as np
+    import paper_2412_05270_amd as A
+    from oracle import apollo as O
+    from parity_util import TOL_BF16, assert_close, condition_factors, f32, make_configs, to_host_f64
+    dev = "cuda:0"
+    rows, cols = shape
+    left = rows <= cols
+    n = cols if left else rows
+    wl = WL.Workload("huge_%dx%d_r%d" % (rows, cols, rank), 61, [shape], torch.bfloat16, "normal", 1e-2, rank=rank,
+                     refresh_interval=200, steps=2, lr=1e-2, weight_decay=0.01, nl_gamma=0.0)
+    cfg, ocfg = make_configs(wl, side="left" if left else "right")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(6100 + rank + rows % 7)
+    W = torch.randn(shape, generator=gen, device=dev, dtype=torch.float32)
+    W *= wl.w_std
+    G = torch.empty(shape, device=dev, dtype=torch.bfloat16)
+    rng = np.random.default_rng(5)
+    J = np.unique(np.concatenate([[0, 1, 2, 3, 254, 255, 256, 257, n - 258, n - 257, n - 256, n - 255, n - 2, n - 1],
+                                  rng.integers(0, n, size=114)]))
+    Jd = torch.as_tensor(J, device=dev)
+    take = (lambda x: x[:, Jd]) if left else (lambda x: x[Jd, :])
+    st = A.ApolloStepper(cfg, [W], [G], device=dev)
+    state = O.init_state(ocfg, *((rows, len(J)) if left else (len(J), cols)))
+    tol = TOL_BF16
+    for t in (1, 2):
+        for r0 in range(0, rows, 65536):              # gradients in slabs: no second 4.8 GB temporary
+            r1 = min(rows, r0 + 65536)
+            G[r0:r1] = (torch.randn((r1 - r0, cols), generator=gen, device=dev, dtype=torch.float32) * wl.grad_scale).to(torch.bfloat16)
+        before = to_host_f64(take(W))
+        st.step(t, wl.lr)
+        torch.cuda.synchronize()
+        W_sub = before.copy()
+        info = O.step(ocfg, state, W_sub, to_host_f64(take(G)), t, f32(wl.lr), tensor_id=0, grad_is_bf16=True)
+        f_chan, _ = condition_factors(info, state, ocfg, t, tol)
+        tag = "%s step %d " % (wl.name, t)
+        assert_close(tag + "colsq", to_host_f64(st.debug(0, A.APOLLO_DBG_COLSQ)[Jd]), info["colsq"], tol)
+        assert_close(tag + "R", to_host_f64(st.debug(0, A.APOLLO_DBG_R)[:, Jd]), info["R"], tol)
+        assert_close(tag + "M", to_host_f64(st.debug(0, A.APOLLO_DBG_M)[:, Jd]), state.M, tol)
+        assert_close(tag + "V", to_host_f64(st.debug(0, A.APOLLO_DBG_V)[:, Jd]), state.V, tol)
+        assert_close(tag + "s", to_host_f64(st.debug(0, A.APOLLO_DBG_S)[Jd]), info["s"], 0.0,
+                     extra_abs=tol * f_chan * np.abs(info["s"]))
+        after = to_host_f64(take(W))
+        dw_ref = W_sub - before
+        f_dw = f_chan[None, :] if left else f_chan[:, None]
+        rms_dw = float(np.sqrt(np.mean(dw_ref * dw_ref)))
+        assert_close(tag + "dW", after - before, dw_ref, 0.0,
+                     extra_abs=tol * f_dw * (np.abs(dw_ref) + rms_dw) + np.abs(after) * 2.0 ** -24)
+        print("%s: step %d compared on %d channels" % (wl.name, t, len(J)), flush=True)
+    st.close()
+    del W, G, st
+    torch.cuda.empty_cache()
