@@ -20,6 +20,7 @@ pytestmark = pytest.mark.gpu
     ("llama13b_r256", 2),
     ("llama7b_mini_bf16", 2),       # bfloat16 W and moments (valid-rounding checks)
     ("llama7b_r256_bf16", 2),
+    ("llama7b_identity", 2),        # the structured rule without projection: full-rank moments
 ])
 def test_full_size_sets(name, steps):
     wl = WL.workload(name)
