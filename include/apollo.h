@@ -31,6 +31,10 @@
  *   - Functions returning apollo_status_t return APOLLO_OK (0) or a negative code; argument
  *     errors are detected before anything is launched.  apollo_last_error() gives the text.
  *   - `g` is the ordinary gradient (d loss / d W); the step subtracts.
+ *   - Threads: different handles may be used from different host threads at the same time.  The
+ *     calls on one handle must not overlap (the handle keeps the descriptor table, the profiling
+ *     events and the error text), and two steps of one handle on different streams are ordered by
+ *     the caller (they share the state and the workspace).
  */
 #ifndef APOLLO_H_
 #define APOLLO_H_

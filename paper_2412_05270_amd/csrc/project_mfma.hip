@@ -22,6 +22,8 @@
 // for each direct-to-LDS load separately); vmcnt is therefore managed by hand: every stage
 // issues the same number of loads per wave, and "stage s+1 has landed" is vmcnt(loads of one
 // stage) because the only younger loads are those of stage s+2.
+#include <atomic>
+
 #include "apollo_internal.h"
 
 namespace apollo {
@@ -318,12 +320,12 @@ template <int MT, int WM, bool LEFT>
 hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, bool padded, const StepParams& sp, hipStream_t st) {
   using C = Cfg<MT, WM>;
   const int lds_bytes = kRing * C::STAGE_BYTES;
-  static bool attr_done = false;
-  if (!attr_done) {
+  static std::atomic<bool> attr_done{false};   // (two threads arriving together both set the attribute: harmless)
+  if (!attr_done.load(std::memory_order_acquire)) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&project_mfma_kernel<MT, WM, LEFT>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   const int tiles = (n + kNT - 1) / kNT;
   const int per_xcd = (count + kXcds - 1) / kXcds;
