@@ -43,6 +43,47 @@ def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(A.ApolloAdamwConfig) == 24
 
 
+def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
+    """The header compiles as C99 on its own; the sizes, field offsets and constants a C caller gets
+    are the ones the ctypes binding uses."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "probe.c"
+    src.write_text("""
+#include <stdio.h>
+#include <stddef.h>
+#include "apollo.h"
+int main(void) {
+  printf("%zu %zu %zu %zu %zu\\n", sizeof(apollo_shape_t), sizeof(apollo_config_t), sizeof(apollo_tensor_t),
+         sizeof(apollo_flat_shape_t), sizeof(apollo_adamw_config_t));
+  printf("%zu %zu %zu %zu %zu %zu %zu\\n", offsetof(apollo_config_t, seed), offsetof(apollo_config_t, beta1),
+         offsetof(apollo_config_t, refresh_interval), offsetof(apollo_config_t, weight_dtype),
+         offsetof(apollo_config_t, schedule), offsetof(apollo_tensor_t, w_meta), offsetof(apollo_shape_t, grad_dtype));
+  printf("%d %d %d %d %d %d %d %d %d %d\\n", APOLLO_BF16, APOLLO_Q8, APOLLO_TENSOR, APOLLO_SIDE_RIGHT, APOLLO_PROJ_IDENTITY,
+         APOLLO_ROUND_STOCHASTIC, APOLLO_SCHEDULE_OVERLAP, APOLLO_DBG_COLSQ, APOLLO_EUNSUPPORTED, APOLLO_ESTATE);
+  return 0;
+}
+""".replace("\\\\", "\\"))
+    exe = tmp_path / "probe"
+    subprocess.run([cc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    sizes = [int(x) for x in out[0].split()]
+    assert sizes == [C.sizeof(A.ApolloShape), C.sizeof(A.ApolloConfig), C.sizeof(A.ApolloTensor),
+                     C.sizeof(A.ApolloFlatShape), C.sizeof(A.ApolloAdamwConfig)]
+    offs = [int(x) for x in out[1].split()]
+    assert offs == [A.ApolloConfig.seed.offset, A.ApolloConfig.beta1.offset, A.ApolloConfig.refresh_interval.offset,
+                    A.ApolloConfig.weight_dtype.offset, A.ApolloConfig.schedule.offset, A.ApolloTensor.w_meta.offset,
+                    A.ApolloShape.grad_dtype.offset]
+    consts = [int(x) for x in out[2].split()]
+    assert consts == [A.APOLLO_BF16, A.APOLLO_Q8, A.APOLLO_TENSOR, A.APOLLO_SIDE_RIGHT, A.APOLLO_PROJ_IDENTITY,
+                      A.APOLLO_ROUND_STOCHASTIC, A.APOLLO_SCHEDULE_OVERLAP, A.APOLLO_DBG_COLSQ, A.APOLLO_EUNSUPPORTED,
+                      A.APOLLO_ESTATE]
+
+
 def test_state_bytes_follow_table_1():
     # 2 n r moments + 1 norm per tensor, n the larger dimension; blocks 256-byte aligned
     shapes = [(8, 20, A.APOLLO_F32), (20, 8, A.APOLLO_BF16)]
