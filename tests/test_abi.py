@@ -66,7 +66,7 @@ int main(void) {
          APOLLO_ROUND_STOCHASTIC, APOLLO_SCHEDULE_OVERLAP, APOLLO_DBG_COLSQ, APOLLO_EUNSUPPORTED, APOLLO_ESTATE);
   return 0;
 }
-""".replace("\\\\", "\\"))
+""")
     exe = tmp_path / "probe"
     subprocess.run([cc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
                    check=True)
