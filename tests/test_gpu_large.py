@@ -106,3 +106,69 @@ def test_one_tensor_beyond_four_gibibytes_on_sampled_channels(shape, rank):
     st.close()
     del W, G, st
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["llama7b_mini", "llama7b_r256", "llama1b"])
+def test_every_tensor_of_a_full_set_at_step_one(name):
+    """The oracle follows a handful of tensors of a full-size set; this covers ALL of them, every
+    element, for the first step, where Algorithm 1 has a short closed form (M = (1 - beta1) R,
+    V = (1 - beta2) R^2, so R~ = R / (|R| + eps), and the limiter has no history: c = 1).  The
+    definition is written out with torch in fp64 on the device -- P from the library's generator
+    view (itself compared bit for bit with the oracle elsewhere), R = P G, column norms, factors,
+    the update -- and compared under the same tolerance.  It is a property check beside the oracle
+    parity, not a replacement: it catches what depends on a tensor's position in the list."""
+    import math
+    import paper_2412_05270_amd as A
+    from parity_util import TOL_BF16, f32, make_configs
+    dev = "cuda:0"
+    wl = WL.workload(name)
+    cfg, _ = make_configs(wl)
+    tol = TOL_BF16
+    weights = WL.make_weights(wl, dev)
+    grads = WL.make_grads(wl, 1, dev)
+    before = [w.clone() for w in weights]
+    st = A.ApolloStepper(cfg, weights, grads, device=dev)
+    st.step(1, wl.lr)
+    torch.cuda.synchronize()
+    b1, b2, eps, alpha, lr = f32(wl.beta1), f32(wl.beta2), f32(wl.eps), f32(wl.scale), f32(wl.lr)
+    r = wl.rank
+
+    def check(tag, got, ref, extra=0.0):
+        got, ref = got.double(), ref.double()
+        assert got.shape == ref.shape, (tag, got.shape, ref.shape)
+        rms = float(ref.pow(2).mean().sqrt())
+        bad = (got - ref).abs() > tol * (ref.abs() + rms) + extra
+        assert not bool(bad.any()), "%s: %d of %d elements off" % (tag, int(bad.sum()), bad.numel())
+
+    for i, (rows, cols) in enumerate(wl.shapes):
+        left = rows <= cols
+        Gm = grads[i].double() if left else grads[i].double().t()
+        z = st.projection(i, 1, True).double()
+        R = (z @ Gm) / math.sqrt(r)
+        colsq = (Gm * Gm).sum(0)
+        Rt = (R * (1.0 - b1) / (1.0 - b1)) / (((1.0 - b2) * R * R / (1.0 - b2)).sqrt() + eps)
+        a, b = (Rt * Rt).sum(0), (R * R).sum(0)
+        if wl.mode == "tensor":
+            s = (a.sum().sqrt() / b.sum().sqrt()).reshape(1)
+            s_full = s.expand(Gm.shape[1])
+        else:
+            s = torch.where(b > 0, a.sqrt() / b.sqrt(), torch.zeros_like(b))
+            s_full = s
+        norm = alpha * (s_full * s_full * colsq).sum().sqrt()
+        dW = -lr * alpha * (Gm * s_full[None, :])
+        dW = dW if left else dW.t()
+        tag = "%s tensor %d " % (name, i)
+        check(tag + "R", st.debug(i, A.APOLLO_DBG_R), R)
+        check(tag + "colsq", st.debug(i, A.APOLLO_DBG_COLSQ), colsq)
+        check(tag + "M", st.debug(i, A.APOLLO_DBG_M), (1.0 - b1) * R)
+        check(tag + "V", st.debug(i, A.APOLLO_DBG_V), (1.0 - b2) * R * R)
+        check(tag + "s", st.debug(i, A.APOLLO_DBG_S), s)
+        check(tag + "norm", st.debug(i, A.APOLLO_DBG_NORM), norm.reshape(1))
+        check(tag + "c", st.debug(i, A.APOLLO_DBG_C), torch.ones(1, device=dev, dtype=torch.float64))
+        check(tag + "dW", weights[i].double() - before[i].double(), dW, extra=weights[i].double().abs() * 2.0 ** -24)
+        del Gm, z, R, Rt, dW
+        if i % 56 == 55:
+            print("%s: %d tensors compared" % (name, i + 1), flush=True)
+    st.close()
+    del weights, grads, before, st
+    torch.cuda.empty_cache()
