@@ -16,7 +16,8 @@ import paper_2412_05270_amd as A
 from oracle import apollo as O
 from oracle import q8 as Q
 from paper_2412_05270_amd import workloads as WL
-from parity_util import TOL_BF16, TOL_F32, assert_close, condition_factors, f32, make_configs, to_host_f64
+from parity_util import (TOL_BF16, TOL_F32, assert_close, assert_rounds_within, condition_factors, f32, make_configs,
+                         to_host_f64)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -26,6 +27,7 @@ def _run(wl, steps, lr, check_ids=None, progress=False):
     bf16 = wl.grad_dtype == torch.bfloat16
     tol = TOL_BF16 if bf16 else TOL_F32
     cfg, ocfg = make_configs(wl)
+    state_bf16 = wl.state_dtype == torch.bfloat16
     if check_ids is None:
         # initial weights: N(0, w_std^2) quantised on the host (nearest)
         check_ids = list(range(len(wl.shapes)))
@@ -64,11 +66,22 @@ def _run(wl, steps, lr, check_ids=None, progress=False):
             n_ch = max(rows, cols)
             adopt = lambda s, c, s_gpu=s_gpu, c_gpu=c_gpu, n_ch=n_ch: (
                 s_gpu if wl.mode == "channel" else np.full(n_ch, s_gpu[0]), c_gpu)
+            adopt_mv = None
+            if state_bf16:
+                # bfloat16 moments: the library's roundings are checked against the oracle's unrounded
+                # values and then adopted (as in the bfloat16-storage tests)
+                M_gpu, V_gpu = to_host_f64(st.debug(i, A.APOLLO_DBG_M)), to_host_f64(st.debug(i, A.APOLLO_DBG_V))
+
+                def adopt_mv(M_exact, V_exact, M_gpu=M_gpu, V_gpu=V_gpu, tag=tag):
+                    assert_rounds_within(tag + "M", M_gpu, M_exact, tol)
+                    assert_rounds_within(tag + "V", V_gpu, V_exact, tol)
+                    return M_gpu, V_gpu
             info = O.step(ocfg, states[i], Wq, to_host_f64(grads[i]), t, f32(lr), tensor_id=i, grad_is_bf16=bf16,
-                          adopt_factors=adopt)
+                          adopt_factors=adopt, adopt_moments=adopt_mv)
             f_chan, f_norm = condition_factors(info, states[i], ocfg, t, tol)
-            assert_close(tag + "M", to_host_f64(st.debug(i, A.APOLLO_DBG_M)), states[i].M, tol)
-            assert_close(tag + "V", to_host_f64(st.debug(i, A.APOLLO_DBG_V)), states[i].V, tol)
+            if not state_bf16:
+                assert_close(tag + "M", to_host_f64(st.debug(i, A.APOLLO_DBG_M)), states[i].M, tol)
+                assert_close(tag + "V", to_host_f64(st.debug(i, A.APOLLO_DBG_V)), states[i].V, tol)
             s_ref = info["s"] if wl.mode == "channel" else info["s"][:1]
             f_s = f_chan if wl.mode == "channel" else f_chan[:1]
             assert_close(tag + "s", s_gpu, s_ref, 0.0, extra_abs=tol * f_s * np.abs(s_ref))
@@ -113,6 +126,14 @@ def test_mini_q8_weights_fp32_gradients(rounding):
     wl = WL.Workload("q8_mini_" + rounding, 52, SHAPES, torch.float32, "normal", 1e-2, rank=1, mode="tensor",
                      scale=math.sqrt(128.0), refresh_interval=3, steps=5, lr=5e-5, weight_dtype=torch.uint8,
                      weight_rounding=rounding)
+    assert _run(wl, wl.steps, wl.lr) > 0
+
+
+def test_q8_weights_with_bfloat16_moments():
+    """The paper's low-memory setting: 8-bit weights together with optimizer states in bfloat16."""
+    wl = WL.Workload("q8_bf16_state", 53, SHAPES, torch.bfloat16, "normal", 1e-2, rank=32, refresh_interval=3,
+                     steps=4, lr=5e-4, weight_dtype=torch.uint8, weight_rounding="stochastic",
+                     state_dtype=torch.bfloat16)
     assert _run(wl, wl.steps, wl.lr) > 0
 
 
