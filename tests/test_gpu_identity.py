@@ -55,3 +55,35 @@ def test_state_size_and_unavailable_views():
     # a constant gradient of ones: G~ = 1 / (1 + eps) at step 1, s_j = 1 / (1 + eps), update lr * s
     assert torch.allclose(w[0], torch.full_like(w[0], -1e-3), rtol=1e-5)
     st.close()
+
+
+@pytest.mark.parametrize("rank", [16, 64, 256])
+def test_low_rank_factors_track_the_full_rank_ones_by_sqrt_r_over_m(rank):
+    """What this mode is for (Section 4.1, Theorem 4.1): the channel factors computed in the random
+    rank-r space approximate the full-rank factors of Section 3.2 up to the constant sqrt(r / m).
+    Both are taken from the library on the same gradients over several steps; the mean ratio over
+    the channels must be sqrt(r / m) within a few per cent (the spread of a single channel is about
+    1 / sqrt(2 r)), in both orientations."""
+    dev = "cuda:0"
+    for shape in ((1024, 2048), (2048, 1024)):
+        m, n = min(shape), max(shape)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4400 + rank)
+        W = [torch.zeros(shape, device=dev), torch.zeros(shape, device=dev)]
+        G = torch.empty(shape, device=dev, dtype=BF)
+        common = dict(mode=A.APOLLO_CHANNEL, seed=7, beta1=0.9, beta2=0.999, eps=1e-8, scale=1.0, weight_decay=0.0,
+                      nl_gamma=0.0, refresh_interval=200, bias_correction=1, side=A.APOLLO_SIDE_AUTO)
+        low = A.ApolloStepper(A.ApolloConfig(rank=rank, **common), [W[0]], [G], device=dev)
+        full = A.ApolloStepper(A.ApolloConfig(rank=1, projection=A.APOLLO_PROJ_IDENTITY, **common), [W[1]], [G], device=dev)
+        for t in range(1, 6):
+            G.copy_((torch.randn(shape, generator=gen, device=dev) * 1e-2).to(BF))
+            low.step(t, 1e-3)
+            full.step(t, 1e-3)
+            ratio = low.debug(0, A.APOLLO_DBG_S).double() / full.debug(0, A.APOLLO_DBG_S).double()
+            assert ratio.numel() == n
+            mean = float(ratio.mean()) / math.sqrt(rank / m)
+            spread = float(ratio.std()) / math.sqrt(rank / m)
+            assert abs(mean - 1.0) < 0.05, (shape, rank, t, mean)
+            assert spread < 2.5 / math.sqrt(2.0 * rank), (shape, rank, t, spread)
+        low.close()
+        full.close()
