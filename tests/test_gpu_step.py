@@ -230,3 +230,16 @@ def test_projection_scratch_follows_jumps_of_the_step_number():
     assert torch.equal(jumpy.debug(0, A.APOLLO_DBG_R), fresh.debug(0, A.APOLLO_DBG_R))
     jumpy.close()
     fresh.close()
+
+
+@pytest.mark.parametrize("grad_scale", [1e-17, 1e-13, 1e-8, 1e4, 1e15])
+@pytest.mark.parametrize("mode,rank,scale", [("channel", 32, 1.0), ("tensor", 1, math.sqrt(128.0))])
+def test_gradient_scales_far_from_one(grad_scale, mode, rank, scale):
+    """Adam's normalisation makes the update independent of the gradient's scale; the fp32
+    arithmetic has to carry that over the range bf16 gradients can take (squares of 1e-17 gradients
+    are 1e-34, those of 1e15 gradients 1e30: both still inside fp32's range; for small gradients
+    eps = 1e-8 is no longer negligible against sqrt(V), which the oracle models as well)."""
+    shapes = [(64, 264), (264, 64), (128, 520)]
+    wl = WL.Workload("scale_%g_%s" % (grad_scale, mode), 14, shapes, torch.bfloat16, "normal", grad_scale, rank=rank,
+                     mode=mode, scale=scale, refresh_interval=2, steps=4, lr=1e-2, weight_decay=0.01)
+    run_parity(wl, list(range(len(shapes))), wl.steps)
