@@ -243,3 +243,14 @@ def test_gradient_scales_far_from_one(grad_scale, mode, rank, scale):
     wl = WL.Workload("scale_%g_%s" % (grad_scale, mode), 14, shapes, torch.bfloat16, "normal", grad_scale, rank=rank,
                      mode=mode, scale=scale, refresh_interval=2, steps=4, lr=1e-2, weight_decay=0.01)
     run_parity(wl, list(range(len(shapes))), wl.steps)
+
+
+def test_thousands_of_small_tensors():
+    """A long tensor list (the descriptor table, the tensor index in the grid and in the random
+    stream's counter): 6000 small tensors of three shapes, the oracle following a few from the
+    beginning, the middle and the end."""
+    shapes = [(8, 16), (40, 8), (64, 264)] * 2000
+    wl = WL.Workload("many_small", 15, shapes, torch.bfloat16, "normal", 1e-2, rank=4, refresh_interval=2, steps=3,
+                     lr=1e-2)
+    ids = [0, 1, 2, 2999, 3000, 3001, 5997, 5998, 5999]
+    run_parity(wl, ids, wl.steps)
