@@ -254,3 +254,8 @@ def test_thousands_of_small_tensors():
                      lr=1e-2)
     ids = [0, 1, 2, 2999, 3000, 3001, 5997, 5998, 5999]
     run_parity(wl, ids, wl.steps)
+    # and a count per shape that is not a multiple of the eight XCDs, through the matrix-core projection
+    shapes = [(64, 264), (264, 64)] * 1501 + [(64, 264)]
+    wl = WL.Workload("many_small_r32", 16, shapes, torch.bfloat16, "normal", 1e-2, rank=32, refresh_interval=2,
+                     steps=2, lr=1e-2)
+    run_parity(wl, [0, 1, 1500, 1501, 3000, 3001, 3002], wl.steps)
