@@ -116,6 +116,20 @@ __device__ __forceinline__ void unpack8(const u32x4_t& v, float f[8]) {
   f[7] = __uint_as_float(v.w & 0xFFFF0000u);
 }
 
+// Eight consecutive gradient elements at octet index o of a row-major array, as floats, streamed:
+// one 16-byte load of bf16, or two of fp32.
+template <bool BF16>
+__device__ __forceinline__ void load_octet(const APOLLO_GLOBAL void* g, size_t o, float f[8]) {
+  if constexpr (BF16) {
+    unpack8(__builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(g) + o), f);
+  } else {
+    const APOLLO_GLOBAL f32x4_t* p = reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(g) + 2 * o;
+    const f32x4_t lo = __builtin_nontemporal_load(p), hi = __builtin_nontemporal_load(p + 1);
+    f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w;
+    f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
+  }
+}
+
 // Generates z[i0 .. i0+count) (count % 4 == 0 or the tail beyond m ignored) into zs[0 .. count).
 __device__ __forceinline__ void gen_z_to_lds(float* zs, int i0, int count, int m, const StepParams& sp,
                                              uint32_t tensor_id, bool round_bf16) {
@@ -141,6 +155,7 @@ __device__ __forceinline__ void gen_z_to_lds(float* zs, int i0, int count, int m
 // combined through LDS.  Output: partial R and colsq of this slab.
 constexpr int kMiniSlabRowsMax = 1024;
 
+template <bool BF16>
 __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
                                                                  int slab_rows) {
   __shared__ float zs[kMiniSlabRowsMax];
@@ -150,7 +165,7 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int i0 = blockIdx.y * slab_rows;
   const int i1 = min(rows, i0 + slab_rows);
-  gen_z_to_lds(zs, i0, i1 - i0, rows, sp, (uint32_t)d.tensor_id, true);
+  gen_z_to_lds(zs, i0, i1 - i0, rows, sp, (uint32_t)d.tensor_id, BF16);
   __syncthreads();
   const int cv = blockIdx.x * 64 + tx;          // column octet
   const bool active = cv * 8 < cols;
@@ -158,30 +173,26 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = sq[e] = 0.f;
   if (active) {
-    const APOLLO_GLOBAL u32x4_t* gp = reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(d.g) + (size_t)cv;
-    const size_t stride = (size_t)(cols >> 3);
+    const size_t stride = (size_t)(cols >> 3);      // octets per row
     int i = i0 + ty;
     for (; i + 12 < i1; i += 16) {
-      u32x4_t v[4];
+      float f[4][8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(gp + (size_t)(i + 4 * u) * stride);
+      for (int u = 0; u < 4; ++u) load_octet<BF16>(d.g, (size_t)(i + 4 * u) * stride + (size_t)cv, f[u]);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const float z = zs[i + 4 * u - i0];
-        float f[8];
-        unpack8(v[u], f);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          acc[e] = __builtin_fmaf(z, f[e], acc[e]);
-          sq[e] = __builtin_fmaf(f[e], f[e], sq[e]);
+          acc[e] = __builtin_fmaf(z, f[u][e], acc[e]);
+          sq[e] = __builtin_fmaf(f[u][e], f[u][e], sq[e]);
         }
       }
     }
     for (; i < i1; i += 4) {
-      const u32x4_t v = __builtin_nontemporal_load(gp + (size_t)i * stride);
-      const float z = zs[i - i0];
       float f[8];
-      unpack8(v, f);
+      load_octet<BF16>(d.g, (size_t)i * stride + (size_t)cv, f);
+      const float z = zs[i - i0];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         acc[e] = __builtin_fmaf(z, f[e], acc[e]);
@@ -222,38 +233,36 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+template <bool BF16>
 __global__ __launch_bounds__(256) void project_rank1_right_kernel(const TensorDesc* __restrict__ descs,
                                                                   StepParams sp) {
   extern __shared__ float zs[];
   const TensorView d(descs[blockIdx.z]);
   const int rows = d.rows, cols = d.cols;
-  gen_z_to_lds(zs, 0, cols, cols, sp, (uint32_t)d.tensor_id, true);
+  gen_z_to_lds(zs, 0, cols, cols, sp, (uint32_t)d.tensor_id, BF16);
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nv = cols >> 3;
-  const APOLLO_GLOBAL u32x4_t* gbase = reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(d.g);
   const int row_begin = blockIdx.x * kMiniRightRowsPerBlock + wave * (kMiniRightRowsPerBlock / 4);
   const int row_end = min(rows, row_begin + kMiniRightRowsPerBlock / 4);
   for (int i = row_begin; i < row_end; i += 4) {
     float acc[4] = {0.f, 0.f, 0.f, 0.f}, sq[4] = {0.f, 0.f, 0.f, 0.f};
     for (int v0 = lane; v0 < nv; v0 += 64) {
-      u32x4_t v[4];
+      float fv[4][8];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int ii = min(i + u, rows - 1);
-        v[u] = __builtin_nontemporal_load(gbase + (size_t)ii * nv + v0);
+        load_octet<BF16>(d.g, (size_t)ii * nv + v0, fv[u]);
       }
       const f32x4_t za = reinterpret_cast<const f32x4_t*>(zs)[2 * v0];
       const f32x4_t zb = reinterpret_cast<const f32x4_t*>(zs)[2 * v0 + 1];
       const float z[8] = {za.x, za.y, za.z, za.w, zb.x, zb.y, zb.z, zb.w};
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        float f[8];
-        unpack8(v[u], f);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          acc[u] = __builtin_fmaf(z[e], f[e], acc[u]);
-          sq[u] = __builtin_fmaf(f[e], f[e], sq[u]);
+          acc[u] = __builtin_fmaf(z[e], fv[u][e], acc[u]);
+          sq[u] = __builtin_fmaf(fv[u][e], fv[u][e], sq[u]);
         }
       }
     }
@@ -270,7 +279,8 @@ __global__ __launch_bounds__(256) void project_rank1_right_kernel(const TensorDe
 }
 
 bool project_rank1_supported(int rows, int cols, bool left, bool bf16) {
-  if (!bf16 || (cols & 7) != 0) return false;
+  (void)bf16;
+  if ((cols & 7) != 0) return false;
   if (!left && cols > kMiniRightMaxM) return false;
   (void)rows;
   return true;
@@ -278,14 +288,15 @@ bool project_rank1_supported(int rows, int cols, bool left, bool bf16) {
 
 hipError_t launch_project_rank1(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
                                 int n_slabs, const StepParams& sp, hipStream_t st) {
-  (void)bf16;
   if (left) {
     const int slab_rows = (((rows + n_slabs - 1) / n_slabs) + 3) & ~3;   // multiple of 4: slabs start on a quad
     dim3 grid((unsigned)((cols / 8 + 63) / 64), (unsigned)n_slabs, (unsigned)count);
-    hipLaunchKernelGGL(project_rank1_left_kernel, grid, dim3(256), 0, st, d_descs, sp, slab_rows);
+    if (bf16) hipLaunchKernelGGL(project_rank1_left_kernel<true>, grid, dim3(256), 0, st, d_descs, sp, slab_rows);
+    else hipLaunchKernelGGL(project_rank1_left_kernel<false>, grid, dim3(256), 0, st, d_descs, sp, slab_rows);
   } else {
     dim3 grid((unsigned)((rows + kMiniRightRowsPerBlock - 1) / kMiniRightRowsPerBlock), 1, (unsigned)count);
-    hipLaunchKernelGGL(project_rank1_right_kernel, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sp);
+    if (bf16) hipLaunchKernelGGL(project_rank1_right_kernel<true>, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sp);
+    else hipLaunchKernelGGL(project_rank1_right_kernel<false>, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sp);
   }
   return hipGetLastError();
 }
