@@ -222,6 +222,20 @@ apollo_status_t apollo_debug_gauss_parts(uint32_t first, int64_t count, void* ra
  * calibrate hardware byte counters when profiling. */
 apollo_status_t apollo_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/* Which projection kernel serves tensor `tensor` (decided in apollo_init from shape, gradient type,
+ * rank and side; pure host arithmetic, nothing is launched).  Writes one of APOLLO_PATH_* to *path
+ * and, if `padded_copy` is not NULL, 1 there when the step first copies the gradient to rows padded
+ * to 16 bytes (bf16 gradients, rows projected, odd row length).  For callers and tests that want to
+ * know that a shape runs where they expect it to run. */
+enum {
+  APOLLO_PATH_RANK1 = 0,        /* streaming mat-vec kernels (rank 1, row length a multiple of 8)   */
+  APOLLO_PATH_MATRIX_CORE = 1,  /* bf16 MFMA kernel (bf16 gradients, rank a multiple of 32, projected
+                                   dimension a multiple of 64, at least 256 channels)              */
+  APOLLO_PATH_GENERAL = 2,      /* fp32 FMA kernel, any shape, rank and gradient type              */
+  APOLLO_PATH_NONE = 3          /* APOLLO_PROJ_IDENTITY: nothing is projected                      */
+};
+apollo_status_t apollo_debug_path(const apollo_handle_t* h, int32_t tensor, int32_t* path, int32_t* padded_copy);
+
 /* Phase timing for benchmarks.  After apollo_profile_enable(h, 1) every apollo_step records
  * HIP events on its stream around its five phases: [0] P scratch fill, [1] projection R = P G,
  * [2] low-rank moments + factors, [3] limiter scalars, [4] weight update.  apollo_profile_read

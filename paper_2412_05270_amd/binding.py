@@ -17,6 +17,7 @@ APOLLO_SCHEDULE_SERIAL, APOLLO_SCHEDULE_OVERLAP = 0, 1
 APOLLO_CHANNEL, APOLLO_TENSOR = 0, 1
 APOLLO_SIDE_AUTO, APOLLO_SIDE_LEFT, APOLLO_SIDE_RIGHT = 0, 1, 2
 APOLLO_PROJ_RANDOM, APOLLO_PROJ_IDENTITY = 0, 1
+APOLLO_PATH_RANK1, APOLLO_PATH_MATRIX_CORE, APOLLO_PATH_GENERAL, APOLLO_PATH_NONE = 0, 1, 2, 3
 (APOLLO_DBG_M, APOLLO_DBG_V, APOLLO_DBG_S, APOLLO_DBG_NORM, APOLLO_DBG_C, APOLLO_DBG_R,
  APOLLO_DBG_COLSQ) = range(7)
 
@@ -92,6 +93,8 @@ def load_library():
     lib.apollo_debug_gauss_parts.argtypes = [u32, i64, vp, vp, vp, vp]
     lib.apollo_debug_copy.restype = i32
     lib.apollo_debug_copy.argtypes = [vp, vp, sz, vp]
+    lib.apollo_debug_path.restype = i32
+    lib.apollo_debug_path.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.apollo_profile_enable.restype = i32
     lib.apollo_profile_enable.argtypes = [vp, i32]
     lib.apollo_profile_read.restype = i32
@@ -176,6 +179,13 @@ def apollo_debug_fill_projection(handle, tensor, step, out_ptr, dtype, stream=No
 
 def apollo_debug_get(handle, tensor, what, out_ptr, nbytes, stream=None):
     return load_library().apollo_debug_get(handle, tensor, what, out_ptr, nbytes, stream)
+
+
+def apollo_debug_path(handle, tensor):
+    """-> (status, APOLLO_PATH_*, padded_copy)"""
+    path, padded = C.c_int32(-1), C.c_int32(0)
+    rc = load_library().apollo_debug_path(handle, tensor, C.byref(path), C.byref(padded))
+    return rc, path.value, padded.value
 
 
 def apollo_debug_philox(ctr_ptr, key0, key1, out_ptr, count, stream=None):
@@ -382,6 +392,13 @@ class ApolloStepper:
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_last_error(self.handle))
         return out
+
+    def path(self, tensor):
+        """(APOLLO_PATH_*, padded_copy) of one tensor."""
+        rc, path, padded = apollo_debug_path(self.handle, tensor)
+        if rc != APOLLO_OK:
+            raise ApolloError(rc, apollo_last_error(self.handle))
+        return path, padded
 
     def projection(self, tensor, step, bf16):
         torch = self.torch

@@ -534,6 +534,20 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   return APOLLO_OK;
 }
 
+apollo_status_t apollo_debug_path(const apollo_handle_t* h, int32_t tensor, int32_t* path, int32_t* padded_copy) {
+  if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
+  if (tensor < 0 || tensor >= (int32_t)h->plan.t.size() || !path) return APOLLO_EINVAL;
+  const TensorPlan& t = h->plan.t[tensor];
+  switch (t.path) {
+    case Path::kRank1: *path = APOLLO_PATH_RANK1; break;
+    case Path::kMfma: *path = APOLLO_PATH_MATRIX_CORE; break;
+    case Path::kGeneric: *path = APOLLO_PATH_GENERAL; break;
+    case Path::kIdentity: *path = APOLLO_PATH_NONE; break;
+  }
+  if (padded_copy) *padded_copy = t.pad_g ? 1 : 0;
+  return APOLLO_OK;
+}
+
 apollo_status_t apollo_profile_enable(apollo_handle_t* h, int32_t on) {
   if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
   h->profiling = on != 0;

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(apollo_[a-z_]+)\s*\(", header))
     assert {"apollo_init", "apollo_step", "apollo_state_bytes", "apollo_workspace_bytes", "apollo_destroy",
             "apollo_debug_fill_projection", "apollo_debug_get", "apollo_state_offsets", "apollo_last_error",
-            "apollo_debug_philox", "apollo_debug_gauss_parts", "apollo_debug_copy", "apollo_profile_enable",
+            "apollo_debug_philox", "apollo_debug_gauss_parts", "apollo_debug_copy", "apollo_debug_path", "apollo_profile_enable",
             "apollo_profile_read", "apollo_adamw_state_bytes", "apollo_adamw_state_offsets",
             "apollo_adamw_workspace_bytes", "apollo_adamw_init", "apollo_adamw_step", "apollo_adamw_last_error",
             "apollo_adamw_destroy"} <= names

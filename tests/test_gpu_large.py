@@ -172,3 +172,33 @@ def test_every_tensor_of_a_full_set_at_step_one(name):
     st.close()
     del weights, grads, before, st
     torch.cuda.empty_cache()
+
+
+def test_full_size_sets_run_on_the_kernels_meant_for_them():
+    """No silent fallback: every tensor of the benchmark's sets is served by the projection kernel
+    written for it (the library reports its choice per tensor)."""
+    import paper_2412_05270_amd as A
+    from parity_util import make_configs
+    dev = "cuda:0"
+    expect = {"llama60m": A.APOLLO_PATH_MATRIX_CORE, "llama1b": A.APOLLO_PATH_MATRIX_CORE,
+              "llama7b_mini": A.APOLLO_PATH_RANK1, "llama7b_r256": A.APOLLO_PATH_MATRIX_CORE,
+              "llama13b_mini": A.APOLLO_PATH_RANK1, "llama13b_r256": A.APOLLO_PATH_MATRIX_CORE,
+              "llama7b_mini_q8": A.APOLLO_PATH_RANK1, "llama7b_identity": A.APOLLO_PATH_NONE,
+              "single256": A.APOLLO_PATH_GENERAL}
+    for name, path in expect.items():
+        wl = WL.workload(name)
+        cfg, _ = make_configs(wl)
+        weights = [torch.empty(s, dtype=wl.weight_dtype, device=dev) for s in wl.shapes]
+        grads = [torch.empty(s, dtype=wl.grad_dtype, device=dev) for s in wl.shapes]
+        metas = None
+        if wl.weight_dtype == torch.uint8:
+            metas = [torch.empty((s[0] * s[1] // 128, 2), dtype=torch.float32, device=dev) for s in wl.shapes]
+        st = A.ApolloStepper(cfg, weights, grads, device=dev, metas=metas)
+        for i, (rows, cols) in enumerate(wl.shapes):
+            got, padded = st.path(i)
+            assert got == path, (name, i, (rows, cols), got)
+            # only the 1B set's 2048 x 5461 tensors (rows projected, odd row length) need the padded copy
+            assert padded == int(name == "llama1b" and (rows, cols) == (2048, 5461)), (name, i, (rows, cols), padded)
+        st.close()
+        del weights, grads, metas, st
+        torch.cuda.empty_cache()
