@@ -96,3 +96,50 @@ def test_rejects_bad_arguments():
         adamw.step(adamw.Config(), st, np.zeros(4), np.zeros(4), 1, 0.1)
     with pytest.raises(ValueError):
         adamw.step(adamw.Config(), st, np.zeros(3, dtype=np.float32), np.zeros(3), 1, 0.1)
+
+
+def test_bfloat16_storage_rounds_on_store_and_computes_from_what_is_stored():
+    """store_dtype="bf16" by hand on one element with beta = 0 (so M = g, V = g^2 exactly before
+    rounding): g = 1 + 2^-10 is not a bfloat16 number (spacing 2^-7 above 1), so M is stored as 1 and
+    V = g^2 = 1 + 2^-9 + 2^-20 as 1; the update uses the STORED moments, 1 / (sqrt(1) + 0) = 1, not
+    g / |g|; the new weight 1 - 2^-9 - 2^-10 is 3/4 of the way from 1 down to the next bfloat16
+    below it (spacing 2^-8 there) and is stored as 1 - 2^-8."""
+    cfg = adamw.Config(beta1=0.0, beta2=0.0, eps=0.0, bias_correction=False, store_dtype="bf16")
+    st = adamw.init_state(1)
+    W = np.array([1.0])
+    g = np.array([1.0 + 2.0 ** -10])
+    u = adamw.step(cfg, st, W, g, 1, 2.0 ** -9 + 2.0 ** -10)
+    assert st.M_exact[0] == g[0] and st.M[0] == 1.0
+    assert st.V_exact[0] == g[0] ** 2 and st.V[0] == 1.0
+    assert u[0] == 1.0
+    assert st.W_exact[0] == 1.0 - 2.0 ** -9 - 2.0 ** -10 and W[0] == 1.0 - 2.0 ** -8
+    # the same step kept in fp32 (fp64 here) rounds nothing
+    cfg32 = adamw.Config(beta1=0.0, beta2=0.0, eps=0.0, bias_correction=False)
+    st, W = adamw.init_state(1), np.array([1.0])
+    adamw.step(cfg32, st, W, g, 1, 2.0 ** -9 + 2.0 ** -10)
+    assert st.M[0] == g[0] and W[0] == 1.0 - 2.0 ** -9 - 2.0 ** -10
+
+
+def test_bfloat16_storage_stays_within_half_an_ulp_per_step_and_adopts_roundings():
+    rng = np.random.default_rng(17)
+    cfg = adamw.Config(weight_decay=0.1, store_dtype="bf16")
+    ref = adamw.Config(weight_decay=0.1)
+    W = rng.normal(size=300)
+    W = np.asarray(torch.tensor(W).to(torch.bfloat16).double())       # starts as bfloat16 numbers
+    st = adamw.init_state(300)
+    for t in range(1, 6):
+        g = rng.normal(size=300) * 1e-2
+        Wr, sr = W.copy(), adamw.init_state(300)
+        sr.M, sr.V = st.M.copy(), st.V.copy()
+        adamw.step(ref, sr, Wr, g, t, 1e-2)                           # the same step without rounding
+        adamw.step(cfg, st, W, g, t, 1e-2)
+        for got, exact in ((st.M, sr.M), (st.V, sr.V)):
+            assert np.all(np.abs(got - exact) <= np.abs(exact) * 2.0 ** -8)      # half a unit in the last of 8 bits
+            assert np.array_equal(np.asarray(torch.tensor(got).to(torch.bfloat16).double()), got)
+        assert np.array_equal(np.asarray(torch.tensor(W).to(torch.bfloat16).double()), W)
+        assert np.all(np.abs(W - st.W_exact) <= np.abs(st.W_exact) * 2.0 ** -8)
+    # adopt_moments: what the hook returns is what is stored and what the update is formed from
+    st2, W2 = adamw.init_state(2), np.zeros(2)
+    u = adamw.step(adamw.Config(beta1=0.0, beta2=0.0, eps=0.0, bias_correction=False), st2, W2, np.array([3.0, -4.0]), 1, 1.0,
+                   adopt_moments=lambda M, V: (np.array([6.0, -4.0]), V))
+    assert st2.M.tolist() == [6.0, -4.0] and u.tolist() == [2.0, -1.0]
