@@ -172,13 +172,17 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
     return res
 
 
-def measure_adamw_rest(A, torch, steps, warmup, dev):
+def measure_adamw_rest(A, torch, steps, warmup, dev, store_bf16=False, also_bf16=True):
     """The element-wise AdamW launch on the parameters of a LLaMA-7B that APOLLO does not project:
-    the 32000 x 4096 embedding and output head and the 65 norm gains; bf16 gradients, fp32 W/M/V.
-    Algorithmic traffic per parameter: W 8 B, M and V 16 B, G 2 B."""
+    the 32000 x 4096 embedding and output head and the 65 norm gains; bf16 gradients, W/M/V in fp32
+    (or, store_bf16, in bfloat16).  Algorithmic traffic per parameter: W 8 B, M and V 16 B (4 and 8
+    in bfloat16), G 2 B."""
     sizes = [32000 * 4096] * 2 + [4096] * 65
     gen = torch.Generator(device=dev).manual_seed(7)
     weights = [torch.randn(n, generator=gen, device=dev) * 0.02 for n in sizes]
+    if store_bf16:
+        weights = [w.to(torch.bfloat16) for w in weights]
+    per_param = 14.0 if store_bf16 else 26.0
     grads = [(torch.randn(n, generator=gen, device=dev) * 1e-3).to(torch.bfloat16) for n in sizes]
     cfg = A.ApolloAdamwConfig(beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, bias_correction=1, reserved=0)
     st = A.AdamwStepper(cfg, weights, grads, device=dev)
@@ -193,16 +197,22 @@ def measure_adamw_rest(A, torch, steps, warmup, dev):
     torch.cuda.synchronize()
     ms = ev[0].elapsed_time(ev[1]) / steps
     n = sum(sizes)
-    finite = bool(torch.isfinite(weights[0][:4096]).all())
+    finite = bool(torch.isfinite(weights[0][:4096].float()).all())
     st.close()
-    gbs = 26.0 * n / (ms * 1e-3) / 1e9
-    return {"workload": "llama7b_rest: embedding + output head (32000x4096 each) + 65 norm gains, bf16 gradients, "
-                        "fp32 W/M/V, element-wise AdamW", "params": n, "ms_per_step": ms,
-            "value": n / (ms * 1e-3), "unit": "params/s",
-            "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                         "traffic": measured_traffic("llama7b_rest", "adamw_kernel"), "kernel": "adamw_kernel",
-                         "algorithmic": 26.0 * n, "launches_per_step": 1},
-            "finite": finite}
+    gbs = per_param * n / (ms * 1e-3) / 1e9
+    res = {"workload": "llama7b_rest: embedding + output head (32000x4096 each) + 65 norm gains, bf16 gradients, "
+                       "%s W/M/V, element-wise AdamW" % ("bf16" if store_bf16 else "fp32"), "params": n, "ms_per_step": ms,
+           "value": n / (ms * 1e-3), "unit": "params/s",
+           "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                        "traffic": None if store_bf16 else measured_traffic("llama7b_rest", "adamw_kernel"),
+                        "kernel": "adamw_kernel", "algorithmic": per_param * n, "launches_per_step": 1},
+           "finite": finite}
+    del weights, grads, st
+    torch.cuda.empty_cache()
+    if not store_bf16 and also_bf16:
+        b16 = measure_adamw_rest(A, torch, steps, warmup, dev, store_bf16=True)
+        res["bf16_storage"] = {k: b16[k] for k in ("ms_per_step", "value", "roofline", "finite")}
+    return res
 
 
 def cpu_baseline(A, WL, torch, wl, weights, grads, budget_s=20.0):
@@ -291,7 +301,7 @@ def main():
                                                "bytes_written": nbytes}}))
         return
     if args.only_adamw_rest:
-        print(json.dumps({"adamw_rest": measure_adamw_rest(A, torch, args.steps, args.warmup, dev)}))
+        print(json.dumps({"adamw_rest": measure_adamw_rest(A, torch, args.steps, args.warmup, dev, also_bf16=False)}))   # one variant: for profiling
         return
     wl = WL.workload(args.workload)
     weights = WL.make_q8_weights(wl, dev) if wl.weight_dtype == torch.uint8 else WL.make_weights(wl, dev)

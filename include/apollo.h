@@ -269,7 +269,9 @@ typedef struct apollo_adamw_handle apollo_adamw_handle_t; /* opaque, host-side *
 typedef struct {
   int64_t numel;        /* elements of the tensor (any shape, handled flat), 1 .. 2^40         */
   int32_t grad_dtype;   /* APOLLO_F32 or APOLLO_BF16                                           */
-  int32_t reserved;     /* set to 0                                                            */
+  int32_t store_dtype;  /* APOLLO_F32 (0, default) or APOLLO_BF16: element type of this tensor's
+                           W, M and V (bfloat16: rounded to nearest even when stored, later
+                           arithmetic from the stored values, as for apollo_config_t)          */
 } apollo_flat_shape_t;
 
 typedef struct {
@@ -280,8 +282,9 @@ typedef struct {
   int32_t reserved;         /* set to 0                                                         */
 } apollo_adamw_config_t;
 
-/* Bytes of state: per tensor, in list order, each block on a 256-byte boundary: M[numel] fp32,
- * V[numel] fp32 (V starts on a 256-byte boundary too).  0 on invalid arguments. */
+/* Bytes of state: per tensor, in list order, each block on a 256-byte boundary: M[numel],
+ * V[numel] in the tensor's store_dtype (V starts on a 256-byte boundary too).  0 on invalid
+ * arguments. */
 size_t apollo_adamw_state_bytes(const apollo_flat_shape_t* shapes, int32_t n_tensors);
 
 /* Byte offsets of one tensor's M and V in the state buffer (either output may be NULL). */
@@ -301,7 +304,7 @@ apollo_status_t apollo_adamw_init(apollo_adamw_handle_t** out, const apollo_adam
                                   size_t workspace_bytes, int32_t zero_state, void* hip_stream);
 
 /* One AdamW step of every tensor at 1-based step `step` with learning rate `lr`: tensors[k].w
- * (DEVICE fp32, updated in place) and tensors[k].g (DEVICE, grad_dtype, read only), both with
+ * (DEVICE, store_dtype, updated in place) and tensors[k].g (DEVICE, grad_dtype, read only), both with
  * numel elements and 16-byte aligned.  Enqueues on `hip_stream`, does not synchronise. */
 apollo_status_t apollo_adamw_step(apollo_adamw_handle_t* h, const apollo_tensor_t* tensors,
                                   int32_t n_tensors, int64_t step, float lr, void* hip_stream);

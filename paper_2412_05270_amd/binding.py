@@ -40,7 +40,7 @@ class ApolloTensor(C.Structure):
 
 
 class ApolloFlatShape(C.Structure):
-    _fields_ = [("numel", C.c_int64), ("grad_dtype", C.c_int32), ("reserved", C.c_int32)]
+    _fields_ = [("numel", C.c_int64), ("grad_dtype", C.c_int32), ("store_dtype", C.c_int32)]
 
 
 class ApolloAdamwConfig(C.Structure):
@@ -219,7 +219,7 @@ def apollo_destroy(handle):
 def _flat_shape_array(shapes):
     arr = (ApolloFlatShape * len(shapes))()
     for i, s in enumerate(shapes):
-        arr[i] = s if isinstance(s, ApolloFlatShape) else ApolloFlatShape(s[0], s[1], 0)
+        arr[i] = s if isinstance(s, ApolloFlatShape) else ApolloFlatShape(s[0], s[1], s[2] if len(s) > 2 else APOLLO_F32)
     return arr
 
 
@@ -277,9 +277,11 @@ class AdamwStepper:
         self.weights, self.grads = list(weights), list(grads)
         self.shapes = []
         for w, g in zip(self.weights, self.grads):
-            assert w.dtype == torch.float32 and w.is_contiguous() and g.is_contiguous()
+            # a bfloat16 weight tensor keeps its moments in bfloat16 as well (store_dtype)
+            assert w.dtype in (torch.float32, torch.bfloat16) and w.is_contiguous() and g.is_contiguous()
             assert g.shape == w.shape and g.dtype in (torch.float32, torch.bfloat16)
-            self.shapes.append((w.numel(), APOLLO_BF16 if g.dtype == torch.bfloat16 else APOLLO_F32))
+            self.shapes.append((w.numel(), APOLLO_BF16 if g.dtype == torch.bfloat16 else APOLLO_F32,
+                                APOLLO_BF16 if w.dtype == torch.bfloat16 else APOLLO_F32))
         sb = apollo_adamw_state_bytes(self.shapes)
         wb = apollo_adamw_workspace_bytes(self.shapes)
         if sb == 0 or wb == 0:
@@ -301,13 +303,16 @@ class AdamwStepper:
             raise ApolloError(rc, apollo_adamw_last_error(self.handle))
 
     def moments(self, tensor):
-        """(M, V) of one tensor as fp32 views into the state buffer."""
+        """(M, V) of one tensor as views into the state buffer, in the tensor's storage type."""
         rc, mo, vo = apollo_adamw_state_offsets(self.shapes, tensor)
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_adamw_last_error())
         n = self.shapes[tensor][0]
-        f = self.state.view(self.torch.float32)
-        return f[mo // 4: mo // 4 + n], f[vo // 4: vo // 4 + n]
+        if self.shapes[tensor][2] == APOLLO_BF16:
+            f, e = self.state.view(self.torch.bfloat16), 2
+        else:
+            f, e = self.state.view(self.torch.float32), 4
+        return f[mo // e: mo // e + n], f[vo // e: vo // e + n]
 
     def close(self):
         if self.handle is not None:

@@ -33,7 +33,7 @@ int fail(std::string& dst, int code, const char* fmt, long long a = 0, long long
 struct FlatPlan {
   struct T {
     uint64_t numel;
-    bool bf16;
+    bool bf16, store16;
     size_t st_m, st_v;
     uint32_t first_block, n_blocks;
   };
@@ -55,14 +55,18 @@ int make_flat_plan(const apollo_flat_shape_t* shapes, int32_t n, FlatPlan& plan,
     if (s.numel > kMaxNumel) return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: more than 2^40 elements", k);
     if (s.grad_dtype != APOLLO_F32 && s.grad_dtype != APOLLO_BF16)
       return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: gradient dtype %lld is neither fp32 nor bf16", k, s.grad_dtype);
+    if (s.store_dtype != APOLLO_F32 && s.store_dtype != APOLLO_BF16)
+      return fail(err, APOLLO_EUNSUPPORTED, "tensor %lld: storage dtype %lld is neither fp32 nor bf16", k, s.store_dtype);
     FlatPlan::T& t = plan.t[k];
     t.numel = (uint64_t)s.numel;
     t.bf16 = s.grad_dtype == APOLLO_BF16;
+    t.store16 = s.store_dtype == APOLLO_BF16;
+    const size_t elem = t.store16 ? 2 : sizeof(float);
     st = align_up(st);
     t.st_m = st;
-    st = align_up(st + t.numel * sizeof(float));
+    st = align_up(st + t.numel * elem);
     t.st_v = st;
-    st += t.numel * sizeof(float);
+    st += t.numel * elem;
     const uint64_t nb = (t.numel + kAdamwBlockElems - 1) / kAdamwBlockElems;
     t.first_block = (uint32_t)blocks;
     t.n_blocks = (uint32_t)nb;
@@ -169,11 +173,12 @@ apollo_status_t apollo_adamw_init(apollo_adamw_handle_t** out, const apollo_adam
     const FlatPlan::T& t = h->plan.t[k];
     AdamwDesc& d = h->desc[k];
     std::memset(&d, 0, sizeof d);
-    d.m = reinterpret_cast<float*>(h->state + t.st_m);
-    d.v = reinterpret_cast<float*>(h->state + t.st_v);
+    d.m = h->state + t.st_m;
+    d.v = h->state + t.st_v;
     d.numel = t.numel;
     d.first_block = t.first_block;
     d.bf16 = t.bf16 ? 1u : 0u;
+    d.store16 = t.store16 ? 1u : 0u;
     for (uint32_t b = 0; b < t.n_blocks; ++b) table[t.first_block + b] = (uint32_t)k;
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -214,7 +219,7 @@ apollo_status_t apollo_adamw_step(apollo_adamw_handle_t* h, const apollo_tensor_
   hipError_t e;
   if (changed) {
     for (int32_t k = 0; k < n; ++k) {
-      h->desc[k].w = static_cast<float*>(tensors[k].w);
+      h->desc[k].w = tensors[k].w;
       h->desc[k].g = tensors[k].g;
       h->last[k] = tensors[k];
     }

@@ -103,13 +103,14 @@ __host__ __device__ inline size_t p_index(int kk, int i, int r) {
 
 // One flat parameter tensor of the element-wise AdamW path (Section 3.1, Eq. 1).
 struct AdamwDesc {
-  float* w;              // numel fp32, updated in place
+  void* w;               // numel, fp32 or bf16 (store16), updated in place
   const void* g;         // numel, bf16 or fp32
-  float* m;              // state: first moment
-  float* v;              // state: second moment
+  void* m;               // state: first moment, fp32 or bf16 (store16)
+  void* v;               // state: second moment
   uint64_t numel;
   uint32_t first_block;  // index of the tensor's first block in the launch
-  uint32_t bf16;         // gradient is bf16
+  uint16_t bf16;         // gradient is bf16
+  uint16_t store16;      // W, M, V are bf16
 };
 
 struct AdamwParams {

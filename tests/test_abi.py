@@ -193,6 +193,12 @@ def test_adamw_state_layout():
     assert A.apollo_adamw_workspace_bytes([(1024, 0)]) == 256 + 256
     assert A.apollo_adamw_workspace_bytes([(1025, 0)] * 7) == 512 + 256
     assert A.apollo_adamw_workspace_bytes([(1024 * 200, 1)]) == 256 + 1024
+    # bfloat16 storage halves a tensor's state
+    mixed = [(100, A.APOLLO_F32, A.APOLLO_BF16), (100, A.APOLLO_F32, A.APOLLO_F32)]
+    assert A.apollo_adamw_state_bytes(mixed) == 256 + 256 + 512 + 512
+    assert A.apollo_adamw_state_offsets(mixed, 0) == (0, 0, 256)
+    assert A.apollo_adamw_state_offsets(mixed, 1) == (0, 512, 1024)
+    assert A.apollo_adamw_state_bytes([(100, A.APOLLO_F32, 5)]) == 0 and "storage" in A.apollo_adamw_last_error()
 
 
 def test_adamw_bad_arguments_are_rejected_before_any_launch():

@@ -8,7 +8,7 @@ import torch
 
 import paper_2412_05270_amd as A
 from oracle import adamw as O
-from parity_util import TOL_BF16, TOL_F32, assert_close, f32
+from parity_util import TOL_BF16, TOL_F32, assert_close, assert_rounds_within, f32
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -34,9 +34,12 @@ def _fill(gen, grads, scale):
         g.copy_((torch.randn(g.numel(), generator=gen, device=DEV) * scale).to(g.dtype))
 
 
-def _run(sizes, dtypes, steps, lr, seed=3, grad_scale=1e-3, **kw):
+def _run(sizes, dtypes, steps, lr, seed=3, grad_scale=1e-3, store_bf16=False, **kw):
     cfg, ocfg = _configs(**kw)
     gen, weights, grads = _make(sizes, dtypes, seed)
+    if store_bf16:
+        weights = [w.to(torch.bfloat16) for w in weights]
+        ocfg.store_dtype = "bf16"
     st = A.AdamwStepper(cfg, weights, grads, device=DEV)
     W = [w.double().cpu().numpy() for w in weights]
     ost = [O.init_state(n) for n in sizes]
@@ -47,9 +50,26 @@ def _run(sizes, dtypes, steps, lr, seed=3, grad_scale=1e-3, **kw):
         torch.cuda.synchronize()
         for i in range(len(sizes)):
             tol = TOL_BF16 if dtypes[i] == torch.bfloat16 else TOL_F32
-            W[i] = before[i].copy()      # each step starts from the library's fp32 weight
-            O.step(ocfg, ost[i], W[i], grads[i].double().cpu().numpy(), t, f32(lr))
+            W[i] = before[i].copy()      # each step starts from the library's stored weight
             m, v = st.moments(i)
+            if store_bf16:
+                # bfloat16 storage: the library's stored moments must be valid roundings of the oracle's
+                # unrounded ones; the oracle then continues from them, and the stored weight must be a
+                # valid rounding of its unrounded new weight
+                m_gpu, v_gpu = m.double().cpu().numpy(), v.double().cpu().numpy()
+                tag = "[%d] step %d" % (i, t)
+
+                def adopt(M_exact, V_exact, m_gpu=m_gpu, v_gpu=v_gpu, tag=tag, tol=tol):
+                    assert_rounds_within("M" + tag, m_gpu, M_exact, tol)
+                    assert_rounds_within("V" + tag, v_gpu, V_exact, tol)
+                    return m_gpu, v_gpu
+                O.step(ocfg, ost[i], W[i], grads[i].double().cpu().numpy(), t, f32(lr), adopt_moments=adopt)
+                dw = ost[i].W_exact - before[i]
+                rms = float(np.sqrt(np.mean(dw * dw)))
+                assert_rounds_within("W" + tag, weights[i].double().cpu().numpy(), ost[i].W_exact, 0.0,
+                                     extra_abs=tol * (np.abs(dw) + rms) + np.abs(before[i]) * 2.0 ** -24)
+                continue
+            O.step(ocfg, ost[i], W[i], grads[i].double().cpu().numpy(), t, f32(lr))
             assert_close("M[%d] step %d" % (i, t), m.double().cpu().numpy(), ost[i].M, tol)
             assert_close("V[%d] step %d" % (i, t), v.double().cpu().numpy(), ost[i].V, tol)
             got = weights[i].double().cpu().numpy()
@@ -70,6 +90,13 @@ def test_fp32_gradients_all_size_classes():
 
 def test_bf16_gradients_with_weight_decay():
     _run(SIZES, [torch.bfloat16] * len(SIZES), steps=5, lr=1e-2, weight_decay=0.1)
+
+
+@pytest.mark.parametrize("gdt", [torch.bfloat16, torch.float32])
+def test_bfloat16_storage_of_weights_and_moments(gdt):
+    """W, M and V kept in bfloat16 (the paper's all-bfloat16 setting for the non-projected parameters
+    too): stored values are checked as valid roundings of the oracle's unrounded ones."""
+    _run(SIZES, [gdt] * len(SIZES), 5, 1e-2, seed=9, weight_decay=0.05, store_bf16=True)
 
 
 def test_mixed_dtypes_without_bias_correction():
