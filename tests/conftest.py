@@ -12,6 +12,10 @@ GOLDEN = os.path.join(ROOT, "tests", "golden")
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the in-tree library; when nothing is built yet (a fresh checkout), build it once
+    from paper_2412_05270_amd import build, library_path
+    if not os.path.exists(library_path()):
+        build.build(verbose=False)
 
 
 def read_golden(name):
