@@ -259,3 +259,12 @@ def test_thousands_of_small_tensors():
     wl = WL.Workload("many_small_r32", 16, shapes, torch.bfloat16, "normal", 1e-2, rank=32, refresh_interval=2,
                      steps=2, lr=1e-2)
     run_parity(wl, [0, 1, 1500, 1501, 3000, 3001, 3002], wl.steps)
+
+
+def test_matrix_core_projection_at_rank_1024():
+    """Four row tiles of 256 per channel tile (they share a tile of G on one XCD), the rank equal to
+    the projected dimension of the smaller tensors."""
+    shapes = [(1024, 1280), (1280, 1024), (2048, 1032)]
+    wl = WL.Workload("mfma_r1024", 17, shapes, torch.bfloat16, "normal", 1e-2, rank=1024, refresh_interval=2,
+                     steps=3, lr=1e-2)
+    run_parity(wl, list(range(len(shapes))), wl.steps)
