@@ -202,3 +202,54 @@ def test_full_size_sets_run_on_the_kernels_meant_for_them():
         st.close()
         del weights, grads, metas, st
         torch.cuda.empty_cache()
+
+
+def test_every_tensor_of_the_full_8bit_set_at_step_one():
+    """All 224 tensors of the 8-bit set (nearest rounding, where the offsets are a constant), first
+    step, every group and element: with the library's own tensor factor (its value is compared with
+    the oracle elsewhere), the new (scale, zero) of every group must be the range and minimum of
+    the updated real weights, and every code floor(x + 1/2) of its real position x -- evaluated with
+    torch in fp64 on the device; a code whose x + 1/2 lies within 1e-3 of an integer may go either way."""
+    import paper_2412_05270_amd as A
+    from parity_util import f32, make_configs
+    dev = "cuda:0"
+    wl = WL.workload("llama7b_mini_q8_nearest")
+    cfg, _ = make_configs(wl)
+    codes, metas = WL.make_q8_weights(wl, dev)
+    grads = WL.make_grads(wl, 1, dev)
+    before = [(c.clone(), m.clone()) for c, m in zip(codes, metas)]
+    st = A.ApolloStepper(cfg, codes, grads, device=dev, metas=metas)
+    lr = 3e-3                      # moves a typical weight by about one code step
+    st.step(1, lr)
+    torch.cuda.synchronize()
+    alpha = f32(wl.scale)
+    moved = 0
+    for i, (rows, cols) in enumerate(wl.shapes):
+        c0, m0 = before[i]
+        groups = rows * cols // 128
+        scale0, zero0 = m0[:, 0].double(), m0[:, 1].double()
+        w = zero0[:, None] + scale0[:, None] * c0.reshape(groups, 128).double()
+        s = float(st.debug(i, A.APOLLO_DBG_S)[0])
+        c = float(st.debug(i, A.APOLLO_DBG_C)[0])
+        wn = w - f32(lr) * alpha * c * s * grads[i].reshape(groups, 128).double()
+        lo, hi = wn.min(dim=1).values, wn.max(dim=1).values
+        rng = hi - lo
+        tag = "tensor %d " % i
+        slack = (wn.abs().max(dim=1).values + w.abs().max(dim=1).values) * 2.0 ** -21
+        assert bool(((metas[i][:, 1].double() - lo).abs() <= slack).all()), tag + "zero"
+        assert bool(((metas[i][:, 0].double() - rng / 255.0).abs() <= slack / 255.0 + rng * 1e-6).all()), tag + "scale"
+        x = torch.where(rng[:, None] > 0, (wn - lo[:, None]) / (rng[:, None] / 255.0), torch.zeros_like(wn))
+        got = codes[i].reshape(groups, 128).double()
+        lo_c = torch.clamp(torch.floor(x + 0.5 - 1e-3), 0, 255)
+        hi_c = torch.clamp(torch.floor(x + 0.5 + 1e-3), 0, 255)
+        bad = (got < lo_c) | (got > hi_c)
+        assert not bool(bad.any()), tag + "%d codes outside their interval" % int(bad.sum())
+        assert float((lo_c == hi_c).double().mean()) > 0.99, tag + "intervals too wide"
+        moved += int((got != c0.reshape(groups, 128).double()).sum())
+        del w, wn, x, got, lo_c, hi_c
+        if i % 56 == 55:
+            print("llama7b_mini_q8_nearest: %d tensors compared" % (i + 1), flush=True)
+    assert moved > wl.n_params // 4          # the step did change the codes
+    st.close()
+    del codes, metas, grads, before, st
+    torch.cuda.empty_cache()
