@@ -108,7 +108,7 @@ def test_one_tensor_beyond_four_gibibytes_on_sampled_channels(shape, rank):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name", ["llama7b_mini", "llama7b_r256", "llama1b"])
+@pytest.mark.parametrize("name", ["llama7b_mini", "llama7b_r256", "llama1b", "llama7b_identity"])
 def test_every_tensor_of_a_full_set_at_step_one(name):
     """The oracle follows a handful of tensors of a full-size set; this covers ALL of them, every
     element, for the first step, where Algorithm 1 has a short closed form (M = (1 - beta1) R,
@@ -132,6 +132,7 @@ def test_every_tensor_of_a_full_set_at_step_one(name):
     torch.cuda.synchronize()
     b1, b2, eps, alpha, lr = f32(wl.beta1), f32(wl.beta2), f32(wl.eps), f32(wl.scale), f32(wl.lr)
     r = wl.rank
+    identity = wl.projection == "identity"
 
     def check(tag, got, ref, extra=0.0):
         got, ref = got.double(), ref.double()
@@ -143,8 +144,10 @@ def test_every_tensor_of_a_full_set_at_step_one(name):
     for i, (rows, cols) in enumerate(wl.shapes):
         left = rows <= cols
         Gm = grads[i].double() if left else grads[i].double().t()
-        z = st.projection(i, 1, True).double()
-        R = (z @ Gm) / math.sqrt(r)
+        if identity:
+            R = Gm                                  # no projection: the moments are those of G itself
+        else:
+            R = (st.projection(i, 1, True).double() @ Gm) / math.sqrt(r)
         colsq = (Gm * Gm).sum(0)
         Rt = (R * (1.0 - b1) / (1.0 - b1)) / (((1.0 - b2) * R * R / (1.0 - b2)).sqrt() + eps)
         a, b = (Rt * Rt).sum(0), (R * R).sum(0)
@@ -158,15 +161,17 @@ def test_every_tensor_of_a_full_set_at_step_one(name):
         dW = -lr * alpha * (Gm * s_full[None, :])
         dW = dW if left else dW.t()
         tag = "%s tensor %d " % (name, i)
-        check(tag + "R", st.debug(i, A.APOLLO_DBG_R), R)
+        own = (lambda x: x) if (left or not identity) else (lambda x: x.t())   # full-rank moments: the tensor's layout
+        if not identity:
+            check(tag + "R", st.debug(i, A.APOLLO_DBG_R), R)
         check(tag + "colsq", st.debug(i, A.APOLLO_DBG_COLSQ), colsq)
-        check(tag + "M", st.debug(i, A.APOLLO_DBG_M), (1.0 - b1) * R)
-        check(tag + "V", st.debug(i, A.APOLLO_DBG_V), (1.0 - b2) * R * R)
+        check(tag + "M", st.debug(i, A.APOLLO_DBG_M), own((1.0 - b1) * R))
+        check(tag + "V", st.debug(i, A.APOLLO_DBG_V), own((1.0 - b2) * R * R))
         check(tag + "s", st.debug(i, A.APOLLO_DBG_S), s)
         check(tag + "norm", st.debug(i, A.APOLLO_DBG_NORM), norm.reshape(1))
         check(tag + "c", st.debug(i, A.APOLLO_DBG_C), torch.ones(1, device=dev, dtype=torch.float64))
         check(tag + "dW", weights[i].double() - before[i].double(), dW, extra=weights[i].double().abs() * 2.0 ** -24)
-        del Gm, z, R, Rt, dW
+        del Gm, R, Rt, dW
         if i % 56 == 55:
             print("%s: %d tensors compared" % (name, i + 1), flush=True)
     st.close()
