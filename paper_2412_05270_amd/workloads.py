@@ -169,3 +169,16 @@ def make_grads(wl, step, device, out=None, boost=1.0):
         else:
             res.append(g)
     return res
+
+
+def dyadic_values(shape, gen, device, exp_lo=-1, exp_hi=0, significand_bits=8, dtype=torch.bfloat16):
+    """Random values +-(1 + k / 2^(b-1)) * 2^e with k uniform in [0, 2^(b-1)) and e uniform in
+    [exp_lo, exp_hi]: numbers with a b-bit significand (b <= 8: exact in bfloat16) and a narrow
+    exponent range, so that sums and products of a few of them are exact in binary32.  Inputs for
+    the tests of the storage rounding, where both sides must agree to the last bit."""
+    b = significand_bits
+    k = torch.randint(0, 1 << (b - 1), shape, generator=gen, device=device).to(torch.float32)
+    e = torch.randint(exp_lo, exp_hi + 1, shape, generator=gen, device=device).to(torch.float32)
+    sign = torch.randint(0, 2, shape, generator=gen, device=device).to(torch.float32) * 2.0 - 1.0
+    v = sign * (1.0 + k / float(1 << (b - 1))) * torch.pow(torch.tensor(2.0, device=device), e)
+    return v.to(dtype)

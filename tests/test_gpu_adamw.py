@@ -60,8 +60,9 @@ def _run(sizes, dtypes, steps, lr, seed=3, grad_scale=1e-3, store_bf16=False, **
                 tag = "[%d] step %d" % (i, t)
 
                 def adopt(M_exact, V_exact, m_gpu=m_gpu, v_gpu=v_gpu, tag=tag, tol=tol):
-                    assert_rounds_within("M" + tag, m_gpu, M_exact, tol)
-                    assert_rounds_within("V" + tag, v_gpu, V_exact, tol)
+                    # (one fused multiply-add per moment: the unrounded values differ by binary32 rounding only)
+                    assert_rounds_within("M" + tag, m_gpu, M_exact, 1e-6, min_pinned=0.9)
+                    assert_rounds_within("V" + tag, v_gpu, V_exact, 1e-6, min_pinned=0.9)
                     return m_gpu, v_gpu
                 O.step(ocfg, ost[i], W[i], grads[i].double().cpu().numpy(), t, f32(lr), adopt_moments=adopt)
                 dw = ost[i].W_exact - before[i]
