@@ -195,6 +195,35 @@ apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg,
 apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, int32_t n_tensors,
                             int64_t step, float lr, void* hip_stream);
 
+/* For callers that cannot allocate device memory or call anything that does (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): one step of Algorithm 1 on a short
+ * tensor list, the same kernels and results as apollo_init(..., zero_state, ...) followed by
+ * apollo_step on a fresh handle, but with no handle and no workspace argument.  The scratch lives
+ * in a static device array of APOLLO_NOALLOC_SCRATCH_BYTES inside the library (one copy per GPU,
+ * held until the process ends); the tensor descriptors reach the device as kernel arguments.  The
+ * call makes no hipMalloc, hipFree, hipHostMalloc, event or stream creation and no memset or copy
+ * engine request: it only launches kernels on `hip_stream`.
+ *   - `state` (DEVICE, 256-byte aligned, >= apollo_state_bytes(cfg, shapes, n_tensors)) is the
+ *     caller's, with the layout documented at apollo_state_bytes; it is zero-filled first (by a
+ *     kernel) if `zero_state` is not 0, otherwise it holds what the previous step left.
+ *   - At most APOLLO_NOALLOC_MAX_TENSORS tensors per call, and apollo_workspace_bytes(cfg, shapes,
+ *     n_tensors) must not exceed APOLLO_NOALLOC_SCRATCH_BYTES: otherwise APOLLO_EUNSUPPORTED, with
+ *     the sizes in apollo_last_error(NULL), and nothing is launched.  (One LLaMA-7B layer fits at
+ *     rank 1; larger lists go through apollo_init / apollo_step, or layer by layer.)
+ *   - The device of `hip_stream` must be the current device.  `cfg->schedule` is ignored (serial).
+ *   - P is generated in every call (the scratch keeps nothing from one call to the next), the
+ *     random stream and every result are the ones apollo_step gives for the same (seed, step,
+ *     tensor index in the list).
+ *   - All calls on one GPU share that GPU's scratch: two calls whose kernels may overlap in time
+ *     (different streams without an ordering between them, different host threads) race; calls
+ *     on one stream are safe. */
+#define APOLLO_NOALLOC_SCRATCH_BYTES (32 * 1024 * 1024)
+#define APOLLO_NOALLOC_MAX_TENSORS 64
+apollo_status_t apollo_step_noalloc(const apollo_config_t* cfg, const apollo_shape_t* shapes,
+                                    const apollo_tensor_t* tensors, int32_t n_tensors, void* state,
+                                    size_t state_bytes, int32_t zero_state, int64_t step, float lr,
+                                    void* hip_stream);
+
 /* Writes the unit-variance projection z (P = z / sqrt(r)) that `step` would use for tensor
  * `tensor`, as a row-major r x m matrix of `dtype` (APOLLO_F32: the fp32 variates; APOLLO_BF16:
  * rounded to bf16, nearest-even) into `out` (DEVICE, r*m elements). */

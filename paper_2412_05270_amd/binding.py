@@ -83,6 +83,8 @@ def load_library():
     lib.apollo_init.argtypes = [C.POINTER(vp), cfgp, shp, i32, vp, sz, vp, sz, i32, vp]
     lib.apollo_step.restype = i32
     lib.apollo_step.argtypes = [vp, C.POINTER(ApolloTensor), i32, i64, f32, vp]
+    lib.apollo_step_noalloc.restype = i32
+    lib.apollo_step_noalloc.argtypes = [cfgp, shp, C.POINTER(ApolloTensor), i32, vp, sz, i32, i64, f32, vp]
     lib.apollo_debug_fill_projection.restype = i32
     lib.apollo_debug_fill_projection.argtypes = [vp, i32, i64, vp, i32, vp]
     lib.apollo_debug_get.restype = i32
@@ -171,6 +173,23 @@ def apollo_step(handle, tensors, step, lr, stream=None, n_tensors=None):
         tensors = arr
     n = n_tensors if n_tensors is not None else (len(tensors) if tensors is not None else 0)
     return load_library().apollo_step(handle, tensors, n, step, lr, stream)
+
+
+APOLLO_NOALLOC_SCRATCH_BYTES = 32 * 1024 * 1024
+APOLLO_NOALLOC_MAX_TENSORS = 64
+
+
+def apollo_step_noalloc(cfg, shapes, tensors, state_ptr, state_bytes, zero_state, step, lr, stream=None):
+    """tensors: a ctypes array of ApolloTensor (or a list of (w_ptr, g_ptr[, w_meta_ptr]))."""
+    if tensors is not None and not isinstance(tensors, C.Array):
+        arr = (ApolloTensor * len(tensors))()
+        for i, t in enumerate(tensors):
+            arr[i] = ApolloTensor(*t)
+        tensors = arr
+    return load_library().apollo_step_noalloc(C.byref(cfg) if cfg is not None else None,
+                                              _shape_array(shapes) if shapes is not None else None, tensors,
+                                              len(shapes) if shapes is not None else 0, state_ptr, state_bytes,
+                                              1 if zero_state else 0, step, lr, stream)
 
 
 def apollo_debug_fill_projection(handle, tensor, step, out_ptr, dtype, stream=None):

@@ -1,8 +1,10 @@
 // Host side of the APOLLO step library: argument checking, buffer layout, the per-step launch
 // schedule.  The interface is documented in include/apollo.h.
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -267,6 +269,103 @@ int upload_descs(apollo_handle* h, hipStream_t st) {
   return APOLLO_OK;
 }
 
+// The launches of one shape group, phase by phase; `what` names the last one for error texts.
+struct GroupLaunches {
+  const apollo_config_t& cfg;
+  const TensorDesc* dd;        // DEVICE descriptor table
+  const StepParams& sp;
+  bool regenerate;             // write the scratch copy of P before projecting
+  const char* what;
+
+  // the transient copy of P (and of a gradient whose rows need padding) for the groups that read it from scratch
+  hipError_t fill(const Group& g, hipStream_t s) {
+    if (g.path == Path::kRank1 || g.path == Path::kIdentity) return hipSuccess;
+    what = "projection fill";
+    hipError_t r = regenerate ? launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, s) : hipSuccess;
+    if (r == hipSuccess && g.pad_g) {
+      what = "gradient padding";
+      r = launch_pad_gradient(dd + g.first, g.count, g.rows, g.cols, g.ldg, s);
+    }
+    return r;
+  }
+  // R = P G and the per-channel squared norms of G
+  hipError_t project(const Group& g, hipStream_t s) {
+    what = "projection";
+    if (g.path == Path::kIdentity) return hipSuccess;
+    if (g.path == Path::kRank1)
+      return launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sp, s);
+    if (g.path == Path::kMfma)
+      return launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, g.pad_g, sp, s);
+    return launch_project_generic(dd + g.first, g.count, g.n, g.bf16, sp, s);
+  }
+  // low-rank Adam moments, channel factors, block partial sums
+  hipError_t moments(const Group& g, hipStream_t s) {
+    what = "moment update";
+    const bool state_bf16 = cfg.state_dtype == APOLLO_BF16;
+    if (g.path == Path::kIdentity)
+      return launch_adam_identity(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, state_bf16, sp, s);
+    return launch_adam_norms(dd + g.first, g.count, g.n, state_bf16, sp, s);
+  }
+  hipError_t update(const Group& g, hipStream_t s) {
+    what = "weight update";
+    if (cfg.weight_dtype == APOLLO_Q8)
+      return launch_update_q8(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, sp, s);
+    return launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, cfg.weight_dtype == APOLLO_BF16, sp, s);
+  }
+};
+
+// Fills the descriptor of tensor k (descriptor-table order is the plan's) from the plan and the two buffers.
+void fill_desc(TensorDesc& d, const TensorPlan& t, int32_t k, char* state, char* ws) {
+  std::memset(&d, 0, sizeof d);
+  d.M = state + t.st_m;
+  d.V = state + t.st_v;
+  d.prev_norm = reinterpret_cast<float*>(state + t.st_norm);
+  d.P = (t.path == Path::kRank1 || t.path == Path::kIdentity) ? nullptr : static_cast<void*>(ws + t.ws_p);
+  d.gpad = t.pad_g ? static_cast<void*>(ws + t.ws_gpad) : nullptr;
+  d.ldg = t.ldg;
+  d.R = reinterpret_cast<float*>(ws + t.ws_r);
+  d.colsq = reinterpret_cast<float*>(ws + t.ws_colsq);
+  d.s = reinterpret_cast<float*>(ws + t.ws_s);
+  d.partials = reinterpret_cast<float*>(ws + t.ws_partials);
+  d.scal = reinterpret_cast<float*>(ws + t.ws_scal);
+  d.rows = t.rows; d.cols = t.cols; d.m = t.m; d.n = t.n; d.m8 = t.m8;
+  d.left = t.left; d.tensor_id = k; d.n_slabs = t.n_slabs; d.k2_blocks = t.k2_blocks;
+}
+
+// Serial schedule of one step, phase by phase, every shape group in turn (the one that is timed
+// phase by phase when profiling: pev, if not null, are the six events around the five phases, the
+// first already recorded).
+hipError_t run_serial(GroupLaunches& L, const Plan& plan, hipStream_t st, hipEvent_t* pev) {
+  hipError_t e = hipSuccess;
+  for (const Group& g : plan.groups) {
+    if (e != hipSuccess) break;
+    e = L.fill(g, st);
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[1], st);
+  for (const Group& g : plan.groups) {
+    if (e != hipSuccess) break;
+    e = L.project(g, st);
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[2], st);
+  for (const Group& g : plan.groups) {
+    if (e != hipSuccess) break;
+    e = L.moments(g, st);
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[3], st);
+  // per-tensor factor, norm and limiter, all tensors in one launch
+  if (e == hipSuccess) {
+    L.what = "limiter";
+    e = launch_finalize(L.dd, (int)plan.t.size(), L.sp, st);
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[4], st);
+  for (const Group& g : plan.groups) {
+    if (e != hipSuccess) break;
+    e = L.update(g, st);
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[5], st);
+  return e;
+}
+
 }  // namespace
 
 extern "C" {
@@ -323,21 +422,7 @@ apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg, c
   h->last.assign(n_tensors, apollo_tensor_t{nullptr, nullptr, nullptr});
   for (int32_t k = 0; k < n_tensors; ++k) {
     const TensorPlan& t = h->plan.t[k];
-    TensorDesc& d = h->desc[t.desc_index];
-    std::memset(&d, 0, sizeof d);
-    d.M = h->state + t.st_m;
-    d.V = h->state + t.st_v;
-    d.prev_norm = reinterpret_cast<float*>(h->state + t.st_norm);
-    d.P = (t.path == Path::kRank1 || t.path == Path::kIdentity) ? nullptr : static_cast<void*>(h->ws + t.ws_p);
-    d.gpad = t.pad_g ? static_cast<void*>(h->ws + t.ws_gpad) : nullptr;
-    d.ldg = t.ldg;
-    d.R = reinterpret_cast<float*>(h->ws + t.ws_r);
-    d.colsq = reinterpret_cast<float*>(h->ws + t.ws_colsq);
-    d.s = reinterpret_cast<float*>(h->ws + t.ws_s);
-    d.partials = reinterpret_cast<float*>(h->ws + t.ws_partials);
-    d.scal = reinterpret_cast<float*>(h->ws + t.ws_scal);
-    d.rows = t.rows; d.cols = t.cols; d.m = t.m; d.n = t.n; d.m8 = t.m8;
-    d.left = t.left; d.tensor_id = k; d.n_slabs = t.n_slabs; d.k2_blocks = t.k2_blocks;
+    fill_desc(h->desc[t.desc_index], t, k, h->state, h->ws);
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e = hipSuccess;
@@ -404,7 +489,6 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   const StepParams sp = make_step_params(h->cfg, step, lr);
   const TensorDesc* dd = reinterpret_cast<const TensorDesc*>(h->ws);
   hipError_t e = hipSuccess;
-  const char* what = "";
   hipEvent_t* pev = nullptr;              // six events around the five phases, when profiling
   if (h->profiling && h->prof_used + 6 <= 6 * 1024) {
     while (h->prof_events.size() < h->prof_used + 6 && e == hipSuccess) {
@@ -417,7 +501,6 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
     h->prof_used += 6;
     e = hipEventRecord(pev[0], st);
   }
-  const bool state_bf16 = h->cfg.state_dtype == APOLLO_BF16;
   // Algorithm 1 keeps P_t until the next re-sampling.  So does the scratch copy: it is generated
   // when the step's refresh epoch differs from the one the workspace holds (first step, every T
   // steps, after a jump in the step number) or when the caller switched streams (the copy was
@@ -425,37 +508,12 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   const int64_t epoch = (step - 1) / (int64_t)h->cfg.refresh_interval;
   const bool regenerate = epoch != h->p_epoch || st != h->p_stream;
   h->p_epoch = -1;                      // until this step is enqueued completely
-  auto fill = [&](const Group& g, hipStream_t s) -> hipError_t {
-    if (g.path == Path::kRank1 || g.path == Path::kIdentity) return hipSuccess;
-    what = "projection fill";
-    hipError_t r = regenerate ? launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, s) : hipSuccess;
-    if (r == hipSuccess && g.pad_g) {
-      what = "gradient padding";
-      r = launch_pad_gradient(dd + g.first, g.count, g.rows, g.cols, g.ldg, s);
-    }
-    return r;
-  };
-  auto project = [&](const Group& g, hipStream_t s) -> hipError_t {
-    what = "projection";
-    if (g.path == Path::kIdentity) return hipSuccess;
-    if (g.path == Path::kRank1)
-      return launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sp, s);
-    if (g.path == Path::kMfma)
-      return launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, g.pad_g, sp, s);
-    return launch_project_generic(dd + g.first, g.count, g.n, g.bf16, sp, s);
-  };
-  auto moments = [&](const Group& g, hipStream_t s) -> hipError_t {
-    what = "moment update";
-    if (g.path == Path::kIdentity)
-      return launch_adam_identity(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, state_bf16, sp, s);
-    return launch_adam_norms(dd + g.first, g.count, g.n, state_bf16, sp, s);
-  };
-  auto update = [&](const Group& g, hipStream_t s) -> hipError_t {
-    what = "weight update";
-    if (h->cfg.weight_dtype == APOLLO_Q8)
-      return launch_update_q8(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, sp, s);
-    return launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, h->cfg.weight_dtype == APOLLO_BF16, sp, s);
-  };
+  GroupLaunches L{h->cfg, dd, sp, regenerate, ""};
+  const char*& what = L.what;
+  auto fill = [&](const Group& g, hipStream_t s) { return L.fill(g, s); };
+  auto project = [&](const Group& g, hipStream_t s) { return L.project(g, s); };
+  auto moments = [&](const Group& g, hipStream_t s) { return L.moments(g, s); };
+  auto update = [&](const Group& g, hipStream_t s) { return L.update(g, s); };
 
   if (h->overlap && !pev) {
     // Overlapped schedule.  Each shape group is a chain fill -> projection -> moments -> limiter ->
@@ -497,37 +555,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
     return APOLLO_OK;
   }
 
-  // Serial schedule, phase by phase (also the one that is timed phase by phase when profiling).
-  // (a) the transient copy of P for the groups that read it from scratch
-  for (const Group& g : h->plan.groups) {
-    if (e != hipSuccess) break;
-    e = fill(g, st);
-  }
-  if (pev && e == hipSuccess) e = hipEventRecord(pev[1], st);
-  // (b) R = P G and the per-channel squared norms of G
-  for (const Group& g : h->plan.groups) {
-    if (e != hipSuccess) break;
-    e = project(g, st);
-  }
-  if (pev && e == hipSuccess) e = hipEventRecord(pev[2], st);
-  // (c) low-rank Adam moments, channel factors, block partial sums
-  for (const Group& g : h->plan.groups) {
-    if (e != hipSuccess) break;
-    e = moments(g, st);
-  }
-  if (pev && e == hipSuccess) e = hipEventRecord(pev[3], st);
-  // (d) per-tensor factor, norm and limiter
-  if (e == hipSuccess) {
-    e = launch_finalize(dd, n, sp, st);
-    what = "limiter";
-  }
-  if (pev && e == hipSuccess) e = hipEventRecord(pev[4], st);
-  // (e) W update
-  for (const Group& g : h->plan.groups) {
-    if (e != hipSuccess) break;
-    e = update(g, st);
-  }
-  if (pev && e == hipSuccess) e = hipEventRecord(pev[5], st);
+  if (e == hipSuccess) e = run_serial(L, h->plan, st, pev);
   if (e != hipSuccess) return hip_fail(h->err, e, what);
   h->p_epoch = epoch;
   h->p_stream = st;
@@ -647,6 +675,132 @@ apollo_status_t apollo_debug_copy(void* dst, const void* src, size_t bytes, void
     return fail(g_last_error, APOLLO_EINVAL, "bad arguments (16-byte aligned pointers, bytes a multiple of 16)");
   const hipError_t e = launch_copy(dst, src, bytes, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return hip_fail(g_last_error, e, "copy (debug)");
+  return APOLLO_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// apollo_step_noalloc: the step with its scratch in a static device array instead of a caller's
+// workspace, for callers that cannot allocate.
+// ---------------------------------------------------------------------------------------------
+}  // extern "C"
+
+// The scratch of apollo_step_noalloc: one copy per GPU the library runs on, held until the process
+// ends.  In host code the name is only a stand-in for the symbol: the device address comes from
+// hipGetSymbolAddress (noalloc_scratch below) and is what every launch and copy receives.
+static __device__ __align__(256) unsigned char scratch[APOLLO_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up once per device).
+int noalloc_scratch(unsigned char** out, std::string& err) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(err, e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(err, APOLLO_EUNSUPPORTED, "device index %lld outside 0..63", dev);
+  unsigned char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (!p) {
+      void* sym = nullptr;
+      e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !sym) return hip_fail(err, e, "hipGetSymbolAddress(scratch)");
+      p = static_cast<unsigned char*>(sym);
+      g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+  }
+  *out = p;
+  return APOLLO_OK;
+}
+
+// Descriptors travel to the device as a kernel argument (no staging buffer, no copy engine): up to
+// kPackDescs per launch, read word by word from the kernel-argument segment.
+constexpr int kPackDescs = 16;
+struct DescPack {
+  TensorDesc d[kPackDescs];
+};
+static_assert(sizeof(DescPack) <= 3072 && sizeof(TensorDesc) % 4 == 0, "descriptor pack must fit the kernel arguments");
+
+__global__ __launch_bounds__(64) void stage_descs_kernel(DescPack pack, TensorDesc* dst, int count) {
+  (void)pack;   // first argument: offset 0 of the kernel-argument segment
+  typedef __attribute__((address_space(4))) const uint32_t karg_word_t;
+  karg_word_t* src = (karg_word_t*)__builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t* out = reinterpret_cast<uint32_t*>(dst);
+  const int words = count * (int)(sizeof(TensorDesc) / 4);
+  for (int i = threadIdx.x; i < words; i += 64) out[i] = src[i];
+}
+
+}  // namespace
+
+extern "C" {
+
+apollo_status_t apollo_step_noalloc(const apollo_config_t* cfg, const apollo_shape_t* shapes,
+                                    const apollo_tensor_t* tensors, int32_t n_tensors, void* state,
+                                    size_t state_bytes, int32_t zero_state, int64_t step, float lr,
+                                    void* hip_stream) {
+  std::string& err = g_last_error;
+  if (n_tensors > APOLLO_NOALLOC_MAX_TENSORS)
+    return fail(err, APOLLO_EUNSUPPORTED, "apollo_step_noalloc takes at most %lld tensors per call, %lld given",
+                APOLLO_NOALLOC_MAX_TENSORS, n_tensors);
+  Plan plan;
+  int rc = make_plan(cfg, shapes, n_tensors, plan, err);
+  if (rc != APOLLO_OK) return rc;
+  if (!tensors || !state) return fail(err, APOLLO_EINVAL, "null tensor list or state buffer");
+  if ((uintptr_t)state & (kAlign - 1)) return fail(err, APOLLO_ESTATE, "state not 256-byte aligned");
+  if (state_bytes < plan.state_bytes)
+    return fail(err, APOLLO_ESTATE, "state buffer has %lld bytes, %lld needed", (long long)state_bytes, (long long)plan.state_bytes);
+  if (plan.workspace_bytes > (size_t)APOLLO_NOALLOC_SCRATCH_BYTES)
+    return fail(err, APOLLO_EUNSUPPORTED,
+                "this tensor list needs %lld bytes of scratch, the static scratch of apollo_step_noalloc holds %lld: "
+                "pass fewer or smaller tensors per call, or use apollo_init / apollo_step with a workspace",
+                (long long)plan.workspace_bytes, (long long)APOLLO_NOALLOC_SCRATCH_BYTES);
+  if (step < 1) return fail(err, APOLLO_EINVAL, "step %lld < 1 (steps are 1-based)", step);
+  if (!std::isfinite(lr)) return fail(err, APOLLO_EINVAL, "learning rate is not finite");
+  for (int32_t k = 0; k < n_tensors; ++k) {
+    if (!tensors[k].w || !tensors[k].g) return fail(err, APOLLO_EINVAL, "tensor %lld: null w or g", k);
+    if (((uintptr_t)tensors[k].w | (uintptr_t)tensors[k].g) & 15u)
+      return fail(err, APOLLO_EINVAL, "tensor %lld: w / g not 16-byte aligned", k);
+    if (cfg->weight_dtype == APOLLO_Q8 && (!tensors[k].w_meta || ((uintptr_t)tensors[k].w_meta & 7u)))
+      return fail(err, APOLLO_EINVAL, "tensor %lld: w_meta null or not 8-byte aligned", k);
+  }
+  unsigned char* ws = nullptr;
+  rc = noalloc_scratch(&ws, err);
+  if (rc != APOLLO_OK) return rc;
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  TensorDesc* dd = reinterpret_cast<TensorDesc*>(ws);
+  DescPack pack;
+  for (int32_t first = 0; first < n_tensors; first += kPackDescs) {
+    const int32_t cnt = std::min<int32_t>(kPackDescs, n_tensors - first);
+    std::memset(&pack, 0, sizeof pack);
+    for (int32_t k = 0; k < n_tensors; ++k) {        // descriptor-table order is the plan's (grouped by shape)
+      const TensorPlan& t = plan.t[k];
+      if (t.desc_index < first || t.desc_index >= first + cnt) continue;
+      TensorDesc& d = pack.d[t.desc_index - first];
+      fill_desc(d, t, k, static_cast<char*>(state), reinterpret_cast<char*>(ws));
+      d.w = tensors[k].w;
+      d.w_meta = static_cast<float*>(tensors[k].w_meta);
+      d.g = tensors[k].g;
+    }
+    hipLaunchKernelGGL(stage_descs_kernel, dim3(1), dim3(64), 0, st, pack, dd + first, (int)cnt);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(err, e, "descriptor staging");
+  }
+  hipError_t e = hipSuccess;
+  if (zero_state) {
+    e = launch_fill_zero(state, plan.state_bytes, st);
+    if (e != hipSuccess) return hip_fail(err, e, "state fill");
+  }
+  const StepParams sp = make_step_params(*cfg, step, lr);
+  // the scratch is shared by every call on this GPU and keeps nothing between calls: P is generated
+  // in every call (nothing else in it is read before it is written within a step)
+  GroupLaunches L{*cfg, dd, sp, true, ""};
+  e = run_serial(L, plan, st, nullptr);
+  if (e != hipSuccess) return hip_fail(err, e, L.what);
   return APOLLO_OK;
 }
 

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
     assert {"apollo_init", "apollo_step", "apollo_state_bytes", "apollo_workspace_bytes", "apollo_destroy",
             "apollo_debug_fill_projection", "apollo_debug_get", "apollo_state_offsets", "apollo_last_error",
             "apollo_debug_philox", "apollo_debug_gauss_parts", "apollo_debug_copy", "apollo_debug_path", "apollo_profile_enable",
-            "apollo_profile_read", "apollo_adamw_state_bytes", "apollo_adamw_state_offsets",
+            "apollo_profile_read", "apollo_step_noalloc", "apollo_adamw_state_bytes", "apollo_adamw_state_offsets",
             "apollo_adamw_workspace_bytes", "apollo_adamw_init", "apollo_adamw_step", "apollo_adamw_last_error",
             "apollo_adamw_destroy"} <= names
     for n in names:
@@ -172,6 +172,34 @@ def test_null_handle_calls_fail_cleanly():
     assert A.apollo_debug_fill_projection(None, 0, 1, 16, A.APOLLO_F32) == A.APOLLO_EINVAL
     assert A.apollo_debug_gauss_parts(1 << 24, 1, 16, 16, 16) == A.APOLLO_EINVAL
     A.apollo_destroy(None)
+
+
+def test_noalloc_step_rejects_oversized_and_bad_requests_before_any_launch():
+    """Every check of apollo_step_noalloc comes before its first GPU call: too many tensors, a list whose
+    scratch exceeds the static array, and the argument errors of apollo_init / apollo_step."""
+    cfg = _cfg(rank=4)
+    one = [(8, 8, 0)]
+    ptrs = [(4096, 8192)]                                    # fake aligned pointers: never touched
+    sb = A.apollo_state_bytes(cfg, one)
+    many = one * (A.APOLLO_NOALLOC_MAX_TENSORS + 1)
+    assert A.apollo_step_noalloc(cfg, many, ptrs * len(many), 256, 1 << 30, 1, 1, 0.1) == A.APOLLO_EUNSUPPORTED
+    assert "at most 64" in A.apollo_last_error()
+    # four LLaMA-7B matrices at rank 1024 need more scratch (their P alone) than the static array holds
+    big = [(4096, 11008, A.APOLLO_BF16)] * 4
+    need = A.apollo_workspace_bytes(_cfg(rank=1024), big)
+    assert need > A.APOLLO_NOALLOC_SCRATCH_BYTES
+    assert A.apollo_step_noalloc(_cfg(rank=1024), big, ptrs * 4, 256, 1 << 40, 1, 1, 0.1) == A.APOLLO_EUNSUPPORTED
+    msg = A.apollo_last_error()
+    assert str(need) in msg and str(A.APOLLO_NOALLOC_SCRATCH_BYTES) in msg
+    assert A.apollo_step_noalloc(cfg, one, ptrs, 256, sb - 1, 1, 1, 0.1) == A.APOLLO_ESTATE
+    assert A.apollo_step_noalloc(cfg, one, ptrs, 264, sb, 1, 1, 0.1) == A.APOLLO_ESTATE
+    assert A.apollo_step_noalloc(cfg, one, ptrs, None, sb, 1, 1, 0.1) == A.APOLLO_EINVAL
+    assert A.apollo_step_noalloc(cfg, one, None, 256, sb, 1, 1, 0.1) == A.APOLLO_EINVAL
+    assert A.apollo_step_noalloc(cfg, one, ptrs, 256, sb, 1, 0, 0.1) == A.APOLLO_EINVAL            # step < 1
+    assert A.apollo_step_noalloc(cfg, one, ptrs, 256, sb, 1, 1, float("nan")) == A.APOLLO_EINVAL
+    assert A.apollo_step_noalloc(cfg, one, [(4100, 8192)], 256, sb, 1, 1, 0.1) == A.APOLLO_EINVAL  # misaligned W
+    assert A.apollo_step_noalloc(_cfg(rank=0), one, ptrs, 256, sb, 1, 1, 0.1) == A.APOLLO_EINVAL
+    assert A.apollo_step_noalloc(None, one, ptrs, 256, sb, 1, 1, 0.1) == A.APOLLO_EINVAL
 
 
 # ------------------------------------------------------------------ element-wise AdamW entry points
