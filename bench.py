@@ -11,8 +11,12 @@ kernel phase that takes the most time (algorithmic bytes or flops per step divid
 phase's HIP-event time, against the MI355X peak); "cpu_baseline" is the fp64 oracle timed on
 the host cores on a bounded sample of the same workload; "also" carries the same measurement
 for further variants on the same shapes (rank 256, which the benchmark definition asks for as well;
-bfloat16 and 8-bit storage); "adamw_rest" the element-wise AdamW launch on the model's non-projected
-parameters.
+bfloat16 and 8-bit storage) and for the benchmark definition's other full-size configurations (LLaMA-1B
+shapes at rank 512; LLaMA-13B shapes, Mini and rank 256, five timed steps of which the first re-samples
+P); "adamw_rest" the element-wise AdamW launch on the model's non-projected parameters.  Every step
+gets freshly drawn gradients (seed = 1000 * config + step); they are generated between the timed
+steps, outside the timed region: each step is bracketed by a device synchronisation on both sides,
+and the K bracketed times are added.
 """
 import argparse
 import json
@@ -31,26 +35,41 @@ KERNEL_OF_PHASE = {"projection_fill": "fill_projection_kernel", "projection": "p
                    "adam_norms": "adam_norms_kernel", "limiter": "finalize_kernel", "update": "update_kernel"}
 
 
-def measured_traffic(workload, kernel):
+def measured_traffic(workload, kernel, live_us=None):
     """HBM bytes per step of `kernel` from the committed rocprofv3 FETCH_SIZE + WRITE_SIZE summary of
     this workload (profiles/<workload>_hbm_traffic.txt, counters scaled by the copy-kernel
-    calibration), or None when there is no such summary."""
+    calibration), or None when there is no such summary -- or when the summary is stale: it records
+    the kernel's time per step in the profiled run ("kernel_us_per_step <kernel>: t"), and if the time
+    measured live in this run (live_us) differs from that by more than 15 % the kernel has changed
+    since it was profiled and its byte counts are not reported."""
     path = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % workload)
     names = [kernel]
     if "{" in kernel:  # "a_{x,y}_b" names the kernels a_x_b and a_y_b: their bytes add
         head, rest = kernel.split("{", 1)
         alts, tail = rest.split("}", 1)
         names = [head + a + tail for a in alts.split(",")]
-    found = {}
+    found, prof_us = {}, {}
     try:
         with open(path) as fh:
             for line in fh:
                 for nm in names:
                     if line.startswith("traffic_bytes_per_step %s:" % nm):
                         found[nm] = int(line.split(":")[1])
+                    if line.startswith("kernel_us_per_step %s:" % nm):
+                        prof_us[nm] = float(line.split(":")[1])
     except OSError:
         return None
-    return sum(found.values()) if len(found) == len(names) else None
+    if len(found) != len(names):
+        return None
+    if live_us is not None:
+        if len(prof_us) != len(names):
+            return None
+        t = sum(prof_us.values())
+        if abs(t - live_us) > 0.15 * max(t, live_us):
+            print("bench: profiles/%s_hbm_traffic.txt is stale for %s (%.0f us per step there, %.0f us now): "
+                  "traffic not reported" % (workload, kernel, t, live_us), file=sys.stderr)
+            return None
+    return sum(found.values())
 
 
 def make_cfg(A, wl, seed=20241205):
@@ -89,26 +108,39 @@ def algorithmic_work(wl):
     }
 
 
-def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=True):
+def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=True, first_step=1):
+    """Times `steps` steps after `warmup` untimed ones, step numbers first_step, first_step + 1, ...
+    Every step (warm-up and timed) first gets freshly drawn gradients into the same buffers (seed =
+    1000 * config + step), generated outside the timed region; a timed step is bracketed by a device
+    synchronisation on both sides (host clock) and by events on the stream (device time)."""
     cfg = make_cfg(A, wl)
     metas = None
     if wl.weight_dtype == torch.uint8:
         weights, metas = weights
     st = A.ApolloStepper(cfg, weights, grads, device=dev, metas=metas)
-    for t in range(1, warmup + 1):
+    # does the projection kernel also update the moments (one kernel for Algorithm 1's steps 1-3)?
+    fused = all(st.path(i)[0] == A.APOLLO_PATH_MATRIX_CORE for i in range(len(wl.shapes)))
+    t = first_step
+    for _ in range(warmup):
+        WL.make_grads(wl, t, dev, out=grads)
         st.step(t, wl.lr)
+        t += 1
     torch.cuda.synchronize()
-    # the timed region: exactly `steps` steps (default, serial schedule), with the per-phase events on
     A.apollo_profile_enable(st.handle, True)
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]   # (the stepper uses torch's current stream)
-    t0 = time.perf_counter()
-    marks[0].record()
-    for k, t in enumerate(range(warmup + 1, warmup + steps + 1)):
+    e0 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]   # (the stepper uses torch's current stream)
+    e1 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    wall = 0.0
+    for k in range(steps):
+        WL.make_grads(wl, t, dev, out=grads)
+        torch.cuda.synchronize()
+        h0 = time.perf_counter()
+        e0[k].record()
         st.step(t, wl.lr)
-        marks[k + 1].record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    per_step = [marks[k].elapsed_time(marks[k + 1]) for k in range(steps)]
+        e1[k].record()
+        torch.cuda.synchronize()
+        wall += time.perf_counter() - h0
+        t += 1
+    per_step = [e0[k].elapsed_time(e1[k]) for k in range(steps)]
     rc, ms, n = A.apollo_profile_read(st.handle)
     assert rc == 0 and n == steps, (rc, n)
     A.apollo_profile_enable(st.handle, False)
@@ -117,9 +149,12 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
     st.close()
     del st
     torch.cuda.empty_cache()
-    sec = (t1 - t0) / steps
+    sec = wall / steps
     phase_ms = {p: ms[i] / steps for i, p in enumerate(PHASES)}
     work = algorithmic_work(wl)
+    if fused:   # the moments are read and written by the projection kernel: their bytes belong to its phase
+        work["projection"]["bytes"] += work["adam_norms"]["bytes"]
+        work["adam_norms"]["bytes"] = 0.0
     dom = max(("projection", "adam_norms", "update"), key=lambda p: phase_ms[p])
     w = work[dom]
     t_dom = phase_ms[dom] * 1e-3
@@ -136,8 +171,11 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
         roof["kernel"] = "update_q8_kernel"
     if dom == "projection" and wl.rank == 1:
         roof["kernel"] = "project_rank1_left_kernel + project_rank1_right_kernel"
-    roof["traffic"] = measured_traffic(wl.name, roof["kernel"] if dom == "update" else KERNEL_OF_PHASE[dom])
-    roof["traffic_note"] = "HBM bytes read + written per step (all launches of the kernel), rocprofv3 counters, profiles/"
+    roof["traffic"] = measured_traffic(wl.name, roof["kernel"] if dom == "update" else KERNEL_OF_PHASE[dom]
+                                       if not (dom == "projection" and wl.rank == 1) else "project_rank1_{left,right}_kernel",
+                                       live_us=phase_ms[dom] * 1e3)
+    roof["traffic_note"] = ("HBM bytes read + written per step (all launches of the kernel), rocprofv3 counters, profiles/; "
+                            "null when there is no summary or the kernel's time has moved away from the profiled one")
     roof["algorithmic"] = w["bytes"]
     roof["phase"] = dom
     roof["ms_per_step"] = phase_ms[dom]
@@ -145,36 +183,50 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
     pw = work["projection"]
     t_proj = phase_ms["projection"] * 1e-3
     proj = {"kernel": "project_mfma_kernel" if wl.rank > 1 else "project_rank1_{left,right}_kernel",
+            "fused_with_moment_update": fused,
             "ms_per_step": phase_ms["projection"],
             "hbm": {"achieved": pw["bytes"] / t_proj / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": pw["bytes"] / t_proj / 1e9 / HBM_PEAK_GBS},
             "mfma": {"achieved": pw["flops"] / t_proj / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": pw["flops"] / t_proj / 1e12 / MFMA_BF16_PEAK_TFLOPS},
-            "traffic": measured_traffic(wl.name, "project_mfma_kernel") if wl.rank > 1 else None}
+            "traffic": measured_traffic(wl.name, "project_mfma_kernel", live_us=phase_ms["projection"] * 1e3) if wl.rank > 1 else None}
     res = {
         "projection_roofline": proj,
-        "value": wl.n_params / sec, "ms_per_step": sec * 1e3, "min_ms_per_step": min(per_step), "phase_ms": phase_ms,
+        "value": wl.n_params / sec, "ms_per_step": sec * 1e3, "device_ms_per_step": sum(per_step) / steps,
+        "min_ms_per_step": min(per_step), "phase_ms": phase_ms,
         "roofline": roof,
         "whole_step_hbm_frac": work["total_bytes"] / sec / 1e9 / HBM_PEAK_GBS,
         "projection_tflops": work["projection"]["flops"] / (phase_ms["projection"] * 1e-3) / 1e12,
         "finite": finite, "state_gb": state_bytes / 1e9, "workspace_gb": ws_bytes / 1e9,
+        "first_timed_step": first_step + warmup,
     }
     if overlap_leg and wl.rank % 32 == 0 and wl.projection != "identity" and wl.grad_dtype == torch.bfloat16:
-        # the optional two-stream schedule (shape groups as overlapping chains), same steps again
+        # the optional two-stream schedule (shape groups as overlapping chains): the last gradients again
         cfg.schedule = A.APOLLO_SCHEDULE_OVERLAP
         st = A.ApolloStepper(cfg, weights, grads, device=dev, metas=metas)
-        for t in range(1, warmup + 1):
-            st.step(t, wl.lr)
+        for k in range(warmup):
+            st.step(first_step + k, wl.lr)
         torch.cuda.synchronize()
         p0 = time.perf_counter()
-        for t in range(warmup + 1, warmup + steps + 1):
-            st.step(t, wl.lr)
+        for k in range(steps):
+            st.step(first_step + warmup + k, wl.lr)
         torch.cuda.synchronize()
         res["overlap_schedule_ms_per_step"] = (time.perf_counter() - p0) / steps * 1e3
         st.close()
         del st
         torch.cuda.empty_cache()
     return res
+
+
+def entry_of(wl, r):
+    """One workload's measurement as it appears under "also"."""
+    return {"workload": describe(wl), "benchmark_config": wl.config_id, "value": r["value"], "unit": "params/s",
+            "ms_per_step": r["ms_per_step"], "device_ms_per_step": r["device_ms_per_step"],
+            "min_ms_per_step": r["min_ms_per_step"], "first_timed_step": r["first_timed_step"],
+            "phase_ms": r["phase_ms"], "overlap_schedule_ms_per_step": r.get("overlap_schedule_ms_per_step"),
+            "roofline": r["roofline"], "whole_step_hbm_frac": r["whole_step_hbm_frac"],
+            "projection_roofline": r["projection_roofline"], "state_gb": r["state_gb"], "workspace_gb": r["workspace_gb"],
+            "finite": r["finite"]}
 
 
 def measure_adamw_rest(A, torch, steps, warmup, dev, store_bf16=False, also_bf16=True):
@@ -221,8 +273,9 @@ def measure_adamw_rest(A, torch, steps, warmup, dev, store_bf16=False, also_bf16
 
 
 def cpu_baseline(A, WL, torch, wl, weights, grads, budget_s=20.0):
-    """The oracle as it stands, timed on the host: one tensor of each distinct shape of the first
-    layer, as many steps as fit the budget (at least one)."""
+    """The oracle as it stands, timed on the host: one tensor of each distinct shape from the first
+    and from the last layer (the tensor index enters the random stream), as many steps as fit the
+    budget (at least one)."""
     import numpy as np
     from oracle import apollo as O
     f32 = lambda v: float(np.float32(v))
@@ -234,6 +287,7 @@ def cpu_baseline(A, WL, torch, wl, weights, grads, budget_s=20.0):
         if s not in seen:
             seen.add(s)
             ids.append(i)
+    ids = ids + [len(wl.shapes) - 7 + i for i in ids]
     Ws = [weights[i].cpu().double().numpy() for i in ids]
     Gs = [grads[i].cpu().float().double().numpy() for i in ids]
     sts = [O.init_state(ocfg, *wl.shapes[i]) for i in ids]
@@ -256,8 +310,8 @@ def cpu_baseline(A, WL, torch, wl, weights, grads, budget_s=20.0):
     except Exception:
         threads = os.cpu_count()
     return {"value": params / el, "unit": "params/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d step(s) on %d tensors (one per distinct shape of layer 0: %s), %.1f s, "
-                      "projection generation included" % (step, len(ids), [wl.shapes[i] for i in ids], el)}
+            "sample": "%d step(s) on %d tensors (one per distinct shape of the first and of the last layer: %s), "
+                      "%.1f s, projection generation included" % (step, len(ids), [wl.shapes[i] for i in ids], el)}
 
 
 def main():
@@ -268,6 +322,10 @@ def main():
     ap.add_argument("--workload", default="llama7b_mini")
     ap.add_argument("--also", default="llama7b_r256,llama7b_mini_bf16,llama7b_r256_bf16,llama7b_mini_q8",
                     help="further variants on the same shapes, comma separated ('' = none)")
+    ap.add_argument("--configs", default="llama1b,llama13b_mini,llama13b_r256",
+                    help="the benchmark definition's other full-size configurations, each on its own weights and "
+                         "gradients, reported under 'also' (comma separated, '' = none); the LLaMA-13B ones time five "
+                         "steps starting at step 201, which re-samples P (T = 200)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-adamw-rest", action="store_true",
                     help="skip the element-wise AdamW launch on the non-projected parameters")
@@ -310,7 +368,7 @@ def main():
         return
     wl = WL.workload(args.workload)
     weights = WL.make_q8_weights(wl, dev) if wl.weight_dtype == torch.uint8 else WL.make_weights(wl, dev)
-    grads = WL.make_grads(wl, 1, dev)
+    grads = [torch.empty(s, dtype=wl.grad_dtype, device=dev) for s in wl.shapes]
     torch.cuda.synchronize()
     main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg)
     cpu = None
@@ -327,29 +385,33 @@ def main():
             weights = WL.make_q8_weights(wl2, dev) if wl2.weight_dtype == torch.uint8 else WL.make_weights(wl2, dev)
             cur_wdt = wl2.weight_dtype
         r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg)
-        also.append({"workload": describe(wl2), "value": r2["value"], "unit": "params/s", "ms_per_step": r2["ms_per_step"],
-                     "min_ms_per_step": r2["min_ms_per_step"],
-                     "phase_ms": r2["phase_ms"], "overlap_schedule_ms_per_step": r2.get("overlap_schedule_ms_per_step"),
-                     "roofline": r2["roofline"],
-                     "whole_step_hbm_frac": r2["whole_step_hbm_frac"],
-                     "projection_roofline": r2["projection_roofline"], "finite": r2["finite"]})
+        also.append(entry_of(wl2, r2))
+    del weights, grads
+    torch.cuda.empty_cache()
+    for name in [a for a in args.configs.split(",") if a]:
+        wl3 = WL.workload(name)
+        w3 = WL.make_weights(wl3, dev)
+        g3 = [torch.empty(s, dtype=wl3.grad_dtype, device=dev) for s in wl3.shapes]
+        if wl3.config_id == 5:      # "P refreshed on step 1 and every 200 steps, 5 steps timed": the first timed step is 201
+            r3 = measure(A, WL, torch, wl3, w3, g3, 5, args.warmup, dev, False, first_step=201 - args.warmup)
+        else:
+            r3 = measure(A, WL, torch, wl3, w3, g3, args.steps, args.warmup, dev, False)
+        also.append(entry_of(wl3, r3))
+        del w3, g3
+        torch.cuda.empty_cache()
     rest = None
     if not args.no_adamw_rest:
-        del weights, grads
-        torch.cuda.empty_cache()
         rest = measure_adamw_rest(A, torch, args.steps, args.warmup, dev)
     lib = None
     if args.library_gemm_context > 0:
-        if args.no_adamw_rest:
-            del weights, grads
-            torch.cuda.empty_cache()
         lib = library_gemm_context(torch, wl, args.library_gemm_context, dev)
     out = {
         "metric": "APOLLO step params/s + % of HBM/MFMA roofline, LLaMA-7B-shaped params",
         "value": main_res["value"], "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": main_res["ms_per_step"], "min_ms_per_step": main_res["min_ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": main_res["ms_per_step"], "device_ms_per_step": main_res["device_ms_per_step"],
+        "min_ms_per_step": main_res["min_ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": describe(wl), "params": wl.n_params, "tensors": len(wl.shapes),
+        "config": {"workload": describe(wl), "benchmark_config": wl.config_id, "params": wl.n_params, "tensors": len(wl.shapes),
                    "grad_dtype": str(wl.grad_dtype).replace("torch.", ""), "state_gb": main_res["state_gb"],
                    "workspace_gb": main_res["workspace_gb"]},
         "roofline": main_res["roofline"], "cpu_baseline": cpu, "phase_ms": main_res["phase_ms"],

@@ -82,7 +82,10 @@ enum {
   APOLLO_DBG_S = 2,     /* scaling factor of the last step: n fp32 (channel) or 1 fp32 (tensor) */
   APOLLO_DBG_NORM = 3,  /* stored norm ||alpha G diag(s)||_F after limiting, 1 fp32            */
   APOLLO_DBG_C = 4,     /* limiter factor c in (0, 1] of the last step, 1 fp32                 */
-  APOLLO_DBG_R = 5,     /* R = P G of the last step, r x n fp32                               */
+  APOLLO_DBG_R = 5,     /* R = P G of the last step, r x n fp32.  For a tensor on
+                           APOLLO_PATH_MATRIX_CORE no R is kept: it is computed again into `out`
+                           from the gradient buffer passed to the last step, which must still
+                           hold that step's gradient                                            */
   APOLLO_DBG_COLSQ = 6  /* ||G[:,j]||^2 per channel of the last step, n fp32                   */
 };
 
@@ -169,7 +172,7 @@ apollo_status_t apollo_state_offsets(const apollo_config_t* cfg, const apollo_sh
                                      int32_t n_tensors, int32_t tensor, size_t* m_offset,
                                      size_t* v_offset, size_t* norm_offset);
 
-/* Bytes of scratch (the generated P, R, per-channel sums, factors, per-tensor scalars, the device
+/* Bytes of scratch (the generated P, R (except on APOLLO_PATH_MATRIX_CORE), per-channel sums, factors, per-tensor scalars, the device
  * descriptor table and, for a bf16 tensor whose rows are projected and whose row length is not a
  * multiple of 8, a copy of its gradient with rows padded to 16 bytes).  The library keeps P there
  * from one step to the next within a refresh interval (Algorithm 1 holds P_t until it is re-sampled)
@@ -259,7 +262,10 @@ apollo_status_t apollo_debug_copy(void* dst, const void* src, size_t bytes, void
 enum {
   APOLLO_PATH_RANK1 = 0,        /* streaming mat-vec kernels (rank 1, row length a multiple of 8)   */
   APOLLO_PATH_MATRIX_CORE = 1,  /* bf16 MFMA kernel (bf16 gradients, rank a multiple of 32, projected
-                                   dimension a multiple of 64, at least 256 channels)              */
+                                   dimension a multiple of 64, at least 256 channels): Algorithm 1's
+                                   steps 1-3 in one kernel -- the moment update and the channel norms
+                                   follow in the epilogue, R never leaves the registers and has no
+                                   scratch                                                         */
   APOLLO_PATH_GENERAL = 2,      /* fp32 FMA kernel, any shape, rank and gradient type              */
   APOLLO_PATH_NONE = 3          /* APOLLO_PROJ_IDENTITY: nothing is projected                      */
 };

@@ -185,16 +185,8 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           const float Re = Rv[h][e];
-          float me = __builtin_fmaf(sp.beta1, mo[h][e], sp.omb1 * Re);
-          float ve = __builtin_fmaf(sp.beta2, vo[h][e], sp.omb2 * (Re * Re));
-          if (SB16) {   // bfloat16 state: round now, and form R~ from what is stored
-            me = bf16_bits_to_f32(f32_to_bf16_bits(me));
-            ve = bf16_bits_to_f32(f32_to_bf16_bits(ve));
-          }
-          // hardware square root and reciprocal (1 ulp each) instead of the correctly rounded
-          // sequences: 3 instead of ~50 instructions per element of a kernel that otherwise only
-          // streams; the error (~3e-7 relative) is far below the fp32 rounding of the sums it enters
-          const float rt = (me * sp.inv_bc1) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(ve * sp.inv_bc2) + sp.eps);
+          float me, ve;
+          const float rt = adam_element<SB16>(sp, Re, mo[h][e], vo[h][e], me, ve);
           a[e] = __builtin_fmaf(rt, rt, a[e]);
           b[e] = __builtin_fmaf(Re, Re, b[e]);
           mn[e] = me;
@@ -296,13 +288,8 @@ __global__ __launch_bounds__(256) void adam_identity_rows_kernel(const TensorDes
   const int j = blockIdx.x * 4 + w;
   float a = 0.f, b = 0.f;
   auto element = [&](float g, float mo, float vo, float& mn, float& vn) {
-    float me = __builtin_fmaf(sp.beta1, mo, sp.omb1 * g);
-    float ve = __builtin_fmaf(sp.beta2, vo, sp.omb2 * (g * g));
-    if (SB16) {
-      me = bf16_bits_to_f32(f32_to_bf16_bits(me));
-      ve = bf16_bits_to_f32(f32_to_bf16_bits(ve));
-    }
-    const float rt = (me * sp.inv_bc1) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(ve * sp.inv_bc2) + sp.eps);
+    float me, ve;
+    const float rt = adam_element<SB16>(sp, g, mo, vo, me, ve);
     a = __builtin_fmaf(rt, rt, a);
     b = __builtin_fmaf(g, g, b);
     mn = me;

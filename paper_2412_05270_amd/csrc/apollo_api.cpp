@@ -34,6 +34,8 @@ struct TensorPlan {
   Path path;
   int32_t n_slabs, k2_blocks;
   bool pad_g;                                                   // projection reads a row-padded copy of g
+  bool fused;                                                   // the projection kernel also updates the moments (no R scratch)
+  int32_t row_tiles;                                            // its row tiles per channel tile
   int32_t ldg;                                                  // row pitch (elements) of what it reads
   size_t ws_gpad;
   size_t st_m, st_v, st_norm;                                   // offsets into the state buffer
@@ -47,8 +49,8 @@ struct Group {
   bool left, bf16;
   Path path;
   int32_t n_slabs;
-  bool pad_g;
-  int32_t ldg;
+  bool pad_g, fused;
+  int32_t ldg, row_tiles;
 };
 
 struct Plan {
@@ -121,6 +123,8 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     else
       t.path = Path::kGeneric;
     t.pad_g = t.path == Path::kMfma && project_mfma_needs_padding(t.rows, t.cols, t.left);
+    t.fused = t.path == Path::kMfma;
+    t.row_tiles = t.fused ? project_mfma_row_tiles(cfg->rank) : 1;
     t.ldg = t.pad_g ? (t.cols + 7) & ~7 : t.cols;
     t.n_slabs = 1;
     if (t.path == Path::kRank1 && t.left) {
@@ -129,8 +133,9 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
       if ((t.rows + sl - 1) / sl > 1020) sl = (t.rows + 1019) / 1020;
       t.n_slabs = sl;
     }
-    t.k2_blocks = adam_norms_blocks(t.n);
+    t.k2_blocks = adam_norms_blocks(t.n);                                 // blocks that leave four partial sums each
     if (identity && !t.left) t.k2_blocks = (t.n + 3) / 4;                 // of adam_identity_rows_kernel
+    if (t.fused) t.k2_blocks = project_mfma_tiles(t.n);                   // of the fused projection kernel
     const size_t rn = (size_t)t.r * (size_t)t.n * state_elem;
     st = align_up(st);
     t.st_m = st;
@@ -147,7 +152,7 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     const TensorPlan& a = plan.t[k];
     Group g{};
     g.rows = a.rows; g.cols = a.cols; g.m = a.m; g.n = a.n; g.m8 = a.m8;
-    g.left = a.left; g.bf16 = a.bf16; g.path = a.path; g.n_slabs = a.n_slabs; g.pad_g = a.pad_g; g.ldg = a.ldg;
+    g.left = a.left; g.bf16 = a.bf16; g.path = a.path; g.n_slabs = a.n_slabs; g.pad_g = a.pad_g; g.fused = a.fused; g.row_tiles = a.row_tiles; g.ldg = a.ldg;
     g.count = 0;
     const int32_t gi = (int32_t)plan.groups.size();
     for (int32_t j = k; j < n; ++j) {
@@ -177,7 +182,11 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     t.ws_gpad = ws;
     if (t.pad_g) ws = align_up(ws + (size_t)t.rows * t.ldg * 2);
     t.ws_r = ws;
-    if (t.path != Path::kIdentity) ws = align_up(ws + (size_t)t.n_slabs * cfg->rank * t.n * sizeof(float));
+    if (t.fused) {     // no R; with several row tiles per channel tile their channel sums
+      if (t.row_tiles > 1) ws = align_up(ws + (size_t)t.row_tiles * 2 * t.n * sizeof(float));
+    } else if (t.path != Path::kIdentity) {
+      ws = align_up(ws + (size_t)t.n_slabs * cfg->rank * t.n * sizeof(float));
+    }
     t.ws_colsq = ws;
     ws = align_up(ws + (size_t)t.n_slabs * t.n * sizeof(float));
     t.ws_s = ws;
@@ -294,13 +303,16 @@ struct GroupLaunches {
     if (g.path == Path::kIdentity) return hipSuccess;
     if (g.path == Path::kRank1)
       return launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sp, s);
-    if (g.path == Path::kMfma)
-      return launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, g.pad_g, sp, s);
+    if (g.path == Path::kMfma)     // (fused: Algorithm 1's steps 1-3 in one kernel, see moments())
+      return launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, g.pad_g, g.fused,
+                                 cfg.state_dtype == APOLLO_BF16, nullptr, sp, s);
     return launch_project_generic(dd + g.first, g.count, g.n, g.bf16, sp, s);
   }
   // low-rank Adam moments, channel factors, block partial sums
   hipError_t moments(const Group& g, hipStream_t s) {
     what = "moment update";
+    if (g.fused)                         // done in the projection kernel's epilogue, up to the sum over its row tiles
+      return g.row_tiles > 1 ? launch_channel_factors(dd + g.first, g.count, g.n, g.row_tiles, s) : hipSuccess;
     const bool state_bf16 = cfg.state_dtype == APOLLO_BF16;
     if (g.path == Path::kIdentity)
       return launch_adam_identity(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, state_bf16, sp, s);
@@ -323,7 +335,7 @@ void fill_desc(TensorDesc& d, const TensorPlan& t, int32_t k, char* state, char*
   d.P = (t.path == Path::kRank1 || t.path == Path::kIdentity) ? nullptr : static_cast<void*>(ws + t.ws_p);
   d.gpad = t.pad_g ? static_cast<void*>(ws + t.ws_gpad) : nullptr;
   d.ldg = t.ldg;
-  d.R = reinterpret_cast<float*>(ws + t.ws_r);
+  d.R = (t.path == Path::kIdentity || (t.fused && t.row_tiles == 1)) ? nullptr : reinterpret_cast<float*>(ws + t.ws_r);
   d.colsq = reinterpret_cast<float*>(ws + t.ws_colsq);
   d.s = reinterpret_cast<float*>(ws + t.ws_s);
   d.partials = reinterpret_cast<float*>(ws + t.ws_partials);
@@ -639,6 +651,18 @@ apollo_status_t apollo_debug_get(apollo_handle_t* h, int32_t tensor, int32_t wha
     case APOLLO_DBG_C: src = h->ws + t.ws_scal + sizeof(float); need = sizeof(float); break;
     case APOLLO_DBG_R:
       if (t.path == Path::kIdentity) return fail(h->err, APOLLO_EINVAL, "no projected gradient without a projection");
+      if (t.fused) {
+        // no R is kept for this tensor (the projection kernel consumes it in registers): compute it
+        // again into `out`, from the gradient buffer of the last step and the P the workspace holds
+        if (bytes != rn) return fail(h->err, APOLLO_EINVAL, "selector %lld holds %lld bytes, %lld given", what, (long long)rn, (long long)bytes);
+        if (!h->have_ptrs || h->p_epoch < 0) return fail(h->err, APOLLO_EINVAL, "no step has run on this handle yet");
+        StepParams sp = make_step_params(h->cfg, h->p_epoch * (int64_t)h->cfg.refresh_interval + 1, 0.f);
+        const hipError_t e = launch_project_mfma(reinterpret_cast<const TensorDesc*>(h->ws) + t.desc_index, 1, t.rows, t.cols,
+                                                 t.left, t.pad_g, false, false, static_cast<float*>(out), sp,
+                                                 static_cast<hipStream_t>(hip_stream));
+        if (e != hipSuccess) return hip_fail(h->err, e, "projection (debug)");
+        return APOLLO_OK;
+      }
       src = h->ws + t.ws_r; need = rn; break;
     case APOLLO_DBG_COLSQ: src = h->ws + t.ws_colsq; need = (size_t)t.n * sizeof(float); break;
     default: return fail(h->err, APOLLO_EINVAL, "unknown selector %lld", what);

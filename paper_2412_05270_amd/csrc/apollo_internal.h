@@ -20,7 +20,8 @@ struct TensorDesc {
   float* prev_norm;    // state: stored norm of the scaled gradient (limiter), 1 float
   void* P;             // scratch: unit-variance projection z, fragment-major (see p_index)
   void* gpad;          // scratch: copy of g with rows padded to ldg elements (16-byte aligned rows), or null
-  float* R;            // scratch: n_slabs partial copies of R, each r x n (slab 0 ends canonical)
+  float* R;            // scratch: n_slabs partial copies of R, each r x n (slab 0 ends canonical); matrix-core path:
+                       // no R, but with several row tiles per channel tile their sums a_j, b_j (2 n floats per row tile)
   float* colsq;        // scratch: n_slabs partial copies of sum_i G[i,j]^2, each n
   float* s;            // scratch: channel factors s_j, n floats
   float* partials;     // scratch: 4 floats per block of the moment kernel (sums of a_j, b_j, colsq_j, s_j^2 colsq_j)
@@ -94,6 +95,23 @@ struct TensorView {
         n_slabs(d.n_slabs), k2_blocks(d.k2_blocks), ldg(d.ldg) {}
 };
 
+// One element of the low-rank Adam update (Algorithm 1, step 2; Section 4.1): new moments from the
+// old ones and the projected gradient Re, and the Adam-normalised value R~ = M^ / (sqrt(V^) + eps).
+// With a bfloat16 state (SB16) the moments are rounded to nearest even first and R~ is formed from
+// what is stored.  Hardware square root and reciprocal (1 ulp each) instead of the correctly rounded
+// sequences: 3 instead of ~50 instructions per element of kernels that otherwise only stream; the
+// error (~3e-7 relative) is far below the binary32 rounding of the sums R~ enters.
+template <bool SB16>
+__device__ __forceinline__ float adam_element(const StepParams& sp, float Re, float mo, float vo, float& me, float& ve) {
+  me = __builtin_fmaf(sp.beta1, mo, sp.omb1 * Re);
+  ve = __builtin_fmaf(sp.beta2, vo, sp.omb2 * (Re * Re));
+  if (SB16) {
+    me = bf16_bits_to_f32(f32_to_bf16_bits(me));
+    ve = bf16_bits_to_f32(f32_to_bf16_bits(ve));
+  }
+  return (me * sp.inv_bc1) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(ve * sp.inv_bc2) + sp.eps);
+}
+
 // Element (kk, i) of the scratch projection: eight consecutive i of one row are contiguous, the
 // r rows of such an octet follow each other, octets follow along i.  A matrix-core A fragment
 // (32 or 16 rows x 8 i per lane) is then one contiguous, coalesced 16-byte load per lane.
@@ -134,8 +152,14 @@ hipError_t launch_project_generic(const TensorDesc* d_descs, int count, int n, b
 hipError_t launch_project_rank1(const TensorDesc* d_descs, int count, int rows, int cols, bool left,
                                 bool bf16, int n_slabs, const StepParams& sp, hipStream_t st);
 bool project_rank1_supported(int rows, int cols, bool left, bool bf16);
+// fused (the step): the kernel also performs the moment update and the channel sums, and the factors
+// when one block holds all rows of its channels (project_mfma_row_tiles(r) == 1; otherwise
+// launch_channel_factors follows).  Not fused (count must be 1): R is stored to r_override (debug view).
 hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool padded,
-                               const StepParams& sp, hipStream_t st);
+                               bool fused, bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st);
+hipError_t launch_channel_factors(const TensorDesc* d_descs, int count, int n, int row_tiles, hipStream_t st);
+int project_mfma_row_tiles(int r);
+int project_mfma_tiles(int n);
 bool project_mfma_needs_padding(int rows, int cols, bool left);
 hipError_t launch_pad_gradient(const TensorDesc* d_descs, int count, int rows, int cols, int ldg, hipStream_t st);
 bool project_mfma_supported(int rows, int cols, bool left, bool bf16, int r);

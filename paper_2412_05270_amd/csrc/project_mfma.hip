@@ -219,9 +219,38 @@ __device__ __forceinline__ void sched_kstep() {
   }
 }
 
-template <int MT, int WM, bool LEFT>
+// Moments of the fused epilogue: one element of M^R or V^R (fp32 or bfloat16) at element index idx,
+// streamed (non-temporal: the state is not touched again within the step).
+template <bool SB16>
+__device__ __forceinline__ float load_moment(const APOLLO_GLOBAL void* base, size_t idx) {
+  if constexpr (SB16)
+    return bf16_bits_to_f32(__builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(base) + idx));
+  else
+    return __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL float*>(base) + idx);
+}
+// (a bfloat16 moment has been rounded by adam_element: the store truncates)
+template <bool SB16>
+__device__ __forceinline__ void store_moment(APOLLO_GLOBAL void* base, size_t idx, float v) {
+  if constexpr (SB16)
+    __builtin_nontemporal_store((uint16_t)(__float_as_uint(v) >> 16), reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base) + idx);
+  else
+    __builtin_nontemporal_store(v, reinterpret_cast<APOLLO_GLOBAL float*>(base) + idx);
+}
+
+// FUSED (the step's kernel): the epilogue does not store R but carries on with Algorithm 1, steps 2-3,
+// on the accumulators: the low-rank Adam update of M^R, V^R for the block's RT rows (read, updated,
+// written back: the only pass over the state in the step), and a_j = sum_k R~[k,j]^2, b_j = sum_k
+// R[k,j]^2 over those rows (a lane sums its rows, lanes l and l+32 and then the WM waves that share a
+// channel are combined through LDS in a fixed order).  When the block holds all r rows (r = RT: rank
+// 32, 64, 128, 256) it goes on to the channel factor s_j (Eq. 4) and the four block sums the limiter
+// kernel consumes; with several row tiles per channel tile (rank 96, 192, 512, ...) it leaves a_j, b_j
+// per row tile in the scratch and channel_factors_kernel adds them up.  A wave's access to a row of
+// M^R / V^R covers 32 consecutive channels (128 bytes) per half-wave.  SB16: the state is bfloat16.
+// Not FUSED: R itself is stored, to r_override (the debug view: no R is kept by a step).
+template <int MT, int WM, bool LEFT, bool FUSED, bool SB16>
 __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
-                                                                    int tiles, int count, int padded) {
+                                                                    int tiles, int count, int padded,
+                                                                    float* __restrict__ r_override) {
   using C = Cfg<MT, WM>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   // XCD-aware numbering: block w runs on XCD w % 8; XCD x works through tensors x, x+8, ...
@@ -294,35 +323,181 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
   // epilogue: R = acc / sqrt(r); n-tile c of the block covers channels n0 + 32 c .. + 31
   const float scale = sp.rsqrt_r;
   const int lane = cx.lane, n = cx.n;
+  if constexpr (!FUSED) {
+    APOLLO_GLOBAL float* Rout = gptr(r_override);
 #pragma unroll
-  for (int a = 0; a < MT; ++a) {
+    for (int a = 0; a < MT; ++a) {
 #pragma unroll
-    for (int b = 0; b < C::NTW; ++b) {
-      const int j = cx.n0 + 32 * cx.tile_of(b) + (lane & 31);
-      if (j < n) {
+      for (int b = 0; b < C::NTW; ++b) {
+        const int j = cx.n0 + 32 * cx.tile_of(b) + (lane & 31);
+        if (j < n) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int i = cx.rbase + cx.wm * 32 * MT + a * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-          d.R[(size_t)i * n + j] = acc[a][b][v] * scale;
+          for (int v = 0; v < 16; ++v) {
+            const int i = cx.rbase + cx.wm * 32 * MT + a * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+            Rout[(size_t)i * n + j] = acc[a][b][v] * scale;
+          }
         }
       }
     }
-  }
-  if (row_tile == 0) {
-    // lanes l and l + 32 hold the two k-halves of channel (tile, l % 32)
-    const float t = sq + __shfl_xor(sq, 32, 64);
-    const int j = cx.n0 + 32 * cx.tile_of(0) + lane;
-    if (lane < 32 && j < n) d.colsq[j] = t;
+  } else {
+    __syncthreads();                    // every wave is past its last fragment read: the ring is free
+    float* red_a = reinterpret_cast<float*>(lds);        // [WM][kNT]
+    float* red_b = red_a + WM * kNT;                     // [WM][kNT]
+    float* csq = red_b + WM * kNT;                       // [kNT]
+    float* wsum = csq + kNT;                             // [4 waves][4]
+    // the shifted last tile overlaps its neighbour: channels below jmin are that tile's
+    const int jmin = (slot % tiles) * kNT;
+    {
+      // lanes l and l + 32 hold the two k-halves of channel (tile, l % 32)
+      const float t = sq + __shfl_xor(sq, 32, 64);
+      if (lane < 32) csq[32 * cx.tile_of(0) + lane] = t;
+    }
+#pragma unroll
+    for (int b = 0; b < C::NTW; ++b) {
+      const int jl = 32 * cx.tile_of(b) + (lane & 31);
+      const int j = cx.n0 + jl;
+      const bool valid = j >= jmin && j < n;
+      float a_sum = 0.f, b_sum = 0.f;
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        const size_t idx0 = (size_t)(cx.rbase + cx.wm * 32 * MT + a * 32 + (lane >> 5) * 4) * (size_t)n + (size_t)j;
+        float mo[16], vo[16];
+        if (valid) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const size_t idx = idx0 + (size_t)((v >> 2) * 8 + (v & 3)) * (size_t)n;
+            mo[v] = load_moment<SB16>(d.M, idx);
+            vo[v] = load_moment<SB16>(d.V, idx);
+          }
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const size_t idx = idx0 + (size_t)((v >> 2) * 8 + (v & 3)) * (size_t)n;
+            const float Re = acc[a][b][v] * scale;
+            float me, ve;
+            const float rt = adam_element<SB16>(sp, Re, mo[v], vo[v], me, ve);
+            a_sum = __builtin_fmaf(rt, rt, a_sum);
+            b_sum = __builtin_fmaf(Re, Re, b_sum);
+            store_moment<SB16>(d.M, idx, me);
+            store_moment<SB16>(d.V, idx, ve);
+          }
+        }
+      }
+      a_sum += __shfl_xor(a_sum, 32, 64);
+      b_sum += __shfl_xor(b_sum, 32, 64);
+      if (lane < 32) {
+        red_a[cx.wm * kNT + jl] = a_sum;
+        red_b[cx.wm * kNT + jl] = b_sum;
+      }
+    }
+    __syncthreads();
+    if (row_tiles > 1) {
+      // several row tiles share these channels: leave this tile's sums for channel_factors_kernel
+      if (cx.tid < kNT) {
+        const int jl = cx.tid, j = cx.n0 + jl;
+        if (j >= jmin && j < n) {
+          float ae = red_a[jl], be = red_b[jl];
+          if (WM > 1) {
+            ae += red_a[kNT + jl];
+            be += red_b[kNT + jl];
+          }
+          d.R[(size_t)(2 * row_tile) * n + j] = ae;
+          d.R[(size_t)(2 * row_tile + 1) * n + j] = be;
+          if (row_tile == 0) d.colsq[j] = csq[jl];
+        }
+      }
+      return;
+    }
+    // one thread per channel of the tile: factor, and the four sums over the block's own channels
+    if (cx.tid < kNT) {
+      const int jl = cx.tid, j = cx.n0 + jl;
+      float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+      if (j >= jmin && j < n) {
+        float ae = red_a[jl], be = red_b[jl];
+        if (WM > 1) {
+          ae += red_a[kNT + jl];
+          be += red_b[kNT + jl];
+        }
+        const float c2 = csq[jl];
+        const float sj = (be > 0.f) ? __builtin_sqrtf(ae) / __builtin_sqrtf(be) : 0.f;
+        d.s[j] = sj;
+        d.colsq[j] = c2;
+        t0 = ae;
+        t1 = be;
+        t2 = c2;
+        t3 = sj * sj * c2;
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        t0 += __shfl_xor(t0, off, 64);
+        t1 += __shfl_xor(t1, off, 64);
+        t2 += __shfl_xor(t2, off, 64);
+        t3 += __shfl_xor(t3, off, 64);
+      }
+      if (lane == 0) {
+        wsum[cx.wave * 4 + 0] = t0;
+        wsum[cx.wave * 4 + 1] = t1;
+        wsum[cx.wave * 4 + 2] = t2;
+        wsum[cx.wave * 4 + 3] = t3;
+      }
+    }
+    __syncthreads();
+    if (cx.tid < 4)
+      d.partials[(size_t)(slot % tiles) * 4 + cx.tid] =
+          ((wsum[cx.tid] + wsum[4 + cx.tid]) + wsum[8 + cx.tid]) + wsum[12 + cx.tid];
   }
 }
 
-template <int MT, int WM, bool LEFT>
-hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, bool padded, const StepParams& sp, hipStream_t st) {
+// Channel factors for ranks with several row tiles per channel tile: adds the row tiles' a_j, b_j (fixed
+// order), forms s_j (Eq. 4) and leaves the four block sums of 256 channels, as the fused epilogue does
+// when one block holds all rows.
+__global__ __launch_bounds__(kNT) void channel_factors_kernel(const TensorDesc* __restrict__ descs, int row_tiles) {
+  __shared__ float wsum[4][4];
+  const TensorView d(descs[blockIdx.y]);
+  const int n = d.n, j = blockIdx.x * kNT + threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+  if (j < n) {
+    float ae = 0.f, be = 0.f;
+    for (int rt = 0; rt < row_tiles; ++rt) {
+      ae += d.R[(size_t)(2 * rt) * n + j];
+      be += d.R[(size_t)(2 * rt + 1) * n + j];
+    }
+    const float c2 = d.colsq[j];
+    const float sj = (be > 0.f) ? __builtin_sqrtf(ae) / __builtin_sqrtf(be) : 0.f;
+    d.s[j] = sj;
+    t0 = ae;
+    t1 = be;
+    t2 = c2;
+    t3 = sj * sj * c2;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    t0 += __shfl_xor(t0, off, 64);
+    t1 += __shfl_xor(t1, off, 64);
+    t2 += __shfl_xor(t2, off, 64);
+    t3 += __shfl_xor(t3, off, 64);
+  }
+  if (lane == 0) {
+    wsum[wave][0] = t0;
+    wsum[wave][1] = t1;
+    wsum[wave][2] = t2;
+    wsum[wave][3] = t3;
+  }
+  __syncthreads();
+  if (threadIdx.x < 4)
+    d.partials[(size_t)blockIdx.x * 4 + threadIdx.x] =
+        ((wsum[0][threadIdx.x] + wsum[1][threadIdx.x]) + wsum[2][threadIdx.x]) + wsum[3][threadIdx.x];
+}
+
+template <int MT, int WM, bool LEFT, bool FUSED, bool SB16>
+hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, bool padded, float* r_override, const StepParams& sp,
+                      hipStream_t st) {
   using C = Cfg<MT, WM>;
   const int lds_bytes = kRing * C::STAGE_BYTES;
+  static_assert(!FUSED || kRing * C::STAGE_BYTES >= (int)((2 * WM + 1) * kNT + 16) * (int)sizeof(float), "epilogue sums fit the ring");
   static std::atomic<bool> attr_done{false};   // (two threads arriving together both set the attribute: harmless)
   if (!attr_done.load(std::memory_order_acquire)) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&project_mfma_kernel<MT, WM, LEFT>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&project_mfma_kernel<MT, WM, LEFT, FUSED, SB16>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_done.store(true, std::memory_order_release);
@@ -330,18 +505,27 @@ hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, bool padded, 
   const int tiles = (n + kNT - 1) / kNT;
   const int per_xcd = (count + kXcds - 1) / kXcds;
   dim3 grid((unsigned)(kXcds * per_xcd * tiles * (sp.r / C::RT)), 1, 1);
-  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, LEFT>), grid, dim3(kThreads), lds_bytes, st, d_descs, sp, tiles, count,
-                     padded ? 1 : 0);
+  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, LEFT, FUSED, SB16>), grid, dim3(kThreads), lds_bytes, st, d_descs, sp,
+                     tiles, count, padded ? 1 : 0, r_override);
   return hipGetLastError();
 }
 
+template <int MT, int WM, bool LEFT>
+hipError_t launch_variant(const TensorDesc* d_descs, int count, int n, bool padded, bool fused, bool state_bf16,
+                          float* r_override, const StepParams& sp, hipStream_t st) {
+  if (!fused) return launch_cfg<MT, WM, LEFT, false, false>(d_descs, count, n, padded, r_override, sp, st);
+  if (state_bf16) return launch_cfg<MT, WM, LEFT, true, true>(d_descs, count, n, padded, nullptr, sp, st);
+  return launch_cfg<MT, WM, LEFT, true, false>(d_descs, count, n, padded, nullptr, sp, st);
+}
+
 template <bool LEFT>
-hipError_t launch_side(const TensorDesc* d_descs, int count, int n, bool padded, const StepParams& sp, hipStream_t st) {
+hipError_t launch_side(const TensorDesc* d_descs, int count, int n, bool padded, bool fused, bool state_bf16,
+                       float* r_override, const StepParams& sp, hipStream_t st) {
   const int r = sp.r;
-  if (r % 256 == 0) return launch_cfg<4, 2, LEFT>(d_descs, count, n, padded, sp, st);
-  if (r % 128 == 0) return launch_cfg<2, 2, LEFT>(d_descs, count, n, padded, sp, st);
-  if (r % 64 == 0) return launch_cfg<1, 2, LEFT>(d_descs, count, n, padded, sp, st);
-  return launch_cfg<1, 1, LEFT>(d_descs, count, n, padded, sp, st);
+  if (r % 256 == 0) return launch_variant<4, 2, LEFT>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
+  if (r % 128 == 0) return launch_variant<2, 2, LEFT>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
+  if (r % 64 == 0) return launch_variant<1, 2, LEFT>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
+  return launch_variant<1, 1, LEFT>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
 }
 
 }  // namespace
@@ -363,10 +547,24 @@ bool project_mfma_needs_padding(int rows, int cols, bool left) {
   return left && (cols & 7) != 0;
 }
 
+// Row tiles per channel tile at rank r (the launcher picks the largest row tile that divides r).
+int project_mfma_row_tiles(int r) { return r % 256 == 0 ? r / 256 : r % 128 == 0 ? r / 128 : r % 64 == 0 ? r / 64 : r / 32; }
+
+// Channel tiles per tensor (= block sums left per tensor).
+int project_mfma_tiles(int n) { return (n + kNT - 1) / kNT; }
+
 hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool padded,
-                               const StepParams& sp, hipStream_t st) {
+                               bool fused, bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st) {
   const int n = left ? cols : rows;
-  return left ? launch_side<true>(d_descs, count, n, padded, sp, st) : launch_side<false>(d_descs, count, n, padded, sp, st);
+  if (fused == (r_override != nullptr) || (r_override && count != 1)) return hipErrorInvalidValue;
+  return left ? launch_side<true>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st)
+              : launch_side<false>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
+}
+
+hipError_t launch_channel_factors(const TensorDesc* d_descs, int count, int n, int row_tiles, hipStream_t st) {
+  hipLaunchKernelGGL(channel_factors_kernel, dim3((unsigned)project_mfma_tiles(n), (unsigned)count), dim3(kNT), 0, st, d_descs,
+                     row_tiles);
+  return hipGetLastError();
 }
 
 }  // namespace apollo
