@@ -196,6 +196,60 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt
     return out
 
 
+def first_step_closed_form(cfg, G, lr, z=None, xp=np):
+    """What Algorithm 1 gives at t = 1, written as the closed form it has there instead of as the
+    recurrence: with M^R_0 = V^R_0 = 0 the moments are M^R_1 = (1 - beta1) R and V^R_1 = (1 - beta2) R^2,
+    Adam's bias corrections at t = 1 are exactly 1 - beta1 and 1 - beta2, so R~ = R / (|R| + eps)
+    (without bias correction: R~ = (1 - beta1) R / (sqrt(1 - beta2) |R| + eps)); the limiter has no
+    stored norm yet, so c = 1; the weights start from W_0 and only the scaled gradient and the decay
+    move them.  Pinned against step() at t = 1 on small tensors; the GPU tests use it to cover every
+    tensor of a full-size set, where the recurrence would need the whole state on the host.
+
+    G: rows x cols, fp64.  z: the unit-variance projection, r x m (P = z / sqrt(r)); None with
+    projection="identity".  xp: the array namespace of G and z (numpy, or torch for arrays that live
+    on another device; only sqrt, abs, where, zeros_like and array methods common to both are used).
+    Returns R, colsq, M, V (as stored: r x n), s (n values; all equal for the tensor-wise factor), norm,
+    c and dW_grad = -lr * alpha * G diag(s) in the tensor's own orientation (the decay term
+    -lr * lambda * W_0 is the caller's to add: it needs W_0)."""
+    rows, cols = G.shape
+    left = is_left(rows, cols, cfg.side)
+    Gm = G if left else G.T
+    if cfg.projection == "identity":
+        R = Gm
+    else:
+        R = (z @ Gm) / float(np.sqrt(np.float64(cfg.rank)))
+    M = (1.0 - cfg.beta1) * R
+    V = (1.0 - cfg.beta2) * R * R
+    M, V = _stored_xp(M, cfg.state_dtype, xp), _stored_xp(V, cfg.state_dtype, xp)
+    bc1, bc2 = ((1.0 - cfg.beta1), (1.0 - cfg.beta2)) if cfg.bias_correction else (1.0, 1.0)
+    Rt = (M / bc1) / (xp.sqrt(V / bc2) + cfg.eps)
+    a = (Rt * Rt).sum(0)
+    b = (R * R).sum(0)
+    colsq = (Gm * Gm).sum(0)
+    if cfg.mode == CHANNEL:
+        safe = xp.where(b > 0, b, b + 1.0)
+        s = xp.where(b > 0, xp.sqrt(a) / xp.sqrt(safe), xp.zeros_like(b))
+    else:
+        bt = b.sum()
+        st = xp.sqrt(a.sum()) / xp.sqrt(bt) if float(bt) > 0 else 0.0 * bt
+        s = xp.zeros_like(b) + st
+    norm = cfg.scale * xp.sqrt((s * s * colsq).sum())
+    U = cfg.scale * (Gm * s[None, :])
+    if not left:
+        U = U.T
+    return {"R": R, "colsq": colsq, "M": M, "V": V, "s": s, "norm": norm, "c": 1.0, "dW_grad": -lr * U, "left": left}
+
+
+def _stored_xp(x, dtype, xp):
+    """stored() for either array namespace (bfloat16 rounding goes through the host for numpy's)."""
+    if dtype == "f32":
+        return x
+    if xp is np:
+        return stored(x, dtype)
+    import torch
+    return x.to(torch.float32).to(torch.bfloat16).to(x.dtype)
+
+
 def state_elements(cfg, shapes):
     """Number of stored optimizer-state scalars (Table 1: 2nr + 2 per tensor for APOLLO,
     2n + 2 for Mini at r = 1, n the larger dimension; the "+2" are the seed and the norm)."""

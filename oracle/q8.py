@@ -38,9 +38,32 @@ class Q8Weights:
             raise ValueError("row length must be a multiple of 128, one (scale, zero) per group")
 
     def dequantise(self):
-        rows, cols = self.codes.shape
-        q = self.codes.reshape(rows, cols // GROUP, GROUP).astype(np.float64)
-        return (self.zero[:, :, None] + self.scale[:, :, None] * q).reshape(rows, cols)
+        return dequantise_values(self.codes.astype(np.float64), self.scale, self.zero)
+
+
+def dequantise_values(codes, scale, zero):
+    """w = zero + scale * q for codes (rows, cols; as floating-point numbers) and per-group (rows,
+    cols / 128) scale and zero.  Uses array methods common to numpy and torch only, so that a test
+    can evaluate it on arrays that live on another device."""
+    rows, cols = codes.shape
+    q = codes.reshape(rows, cols // GROUP, GROUP)
+    return (zero.reshape(rows, cols // GROUP, 1) + scale.reshape(rows, cols // GROUP, 1) * q).reshape(rows, cols)
+
+
+def group_positions(w_exact, xp=np):
+    """The range of every group of 128 consecutive elements of a row and the real-valued code positions
+    in it: (lo, hi, x) with lo, hi of shape (rows, cols / 128) and x = 255 (w - lo) / (hi - lo) of shape
+    (rows, cols), 0 for a constant group.  xp: the array namespace (numpy or torch)."""
+    rows, cols = w_exact.shape
+    g = w_exact.reshape(rows, cols // GROUP, GROUP)
+    if xp is np:
+        lo, hi = g.min(axis=2), g.max(axis=2)
+    else:
+        lo, hi = g.min(dim=2).values, g.max(dim=2).values
+    rng = (hi - lo).reshape(rows, cols // GROUP, 1)
+    safe = xp.where(rng > 0, rng, rng + 1.0)
+    x = xp.where(rng > 0, (g - lo.reshape(rows, cols // GROUP, 1)) / (safe / 255.0), xp.zeros_like(g))
+    return lo, hi, x.reshape(rows, cols)
 
 
 def rounding_offsets(shape, mode, seed, tensor_id, step):
@@ -64,13 +87,9 @@ def quantise(w_exact, u):
     """Group-wise quantisation of the real matrix w_exact with rounding offsets u.
     Returns (Q8Weights, x) with x the real-valued code positions before rounding."""
     w_exact = np.asarray(w_exact, dtype=np.float64)
-    rows, cols = w_exact.shape
-    g = w_exact.reshape(rows, cols // GROUP, GROUP)
-    lo, hi = g.min(axis=2), g.max(axis=2)
+    lo, hi, x = group_positions(w_exact)
     zero = lo.astype(np.float32).astype(np.float64)                   # stored in fp32
     scale = ((hi - lo) / 255.0).astype(np.float32).astype(np.float64)
-    with np.errstate(divide="ignore", invalid="ignore"):
-        x = np.where(scale[:, :, None] > 0, (g - lo[:, :, None]) / ((hi - lo)[:, :, None] / 255.0), 0.0)
-    x = x.reshape(rows, cols)
+    x = np.where(np.repeat(scale, GROUP, axis=1) > 0, x, 0.0)         # a range that vanishes in fp32 counts as constant
     codes = np.minimum(255.0, np.floor(x + u)).astype(np.uint8)
     return Q8Weights(codes, scale, zero), x

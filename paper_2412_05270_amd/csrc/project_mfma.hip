@@ -25,6 +25,7 @@
 #include <atomic>
 
 #include "apollo_internal.h"
+#include "state_io.hpp"
 
 namespace apollo {
 
@@ -219,33 +220,14 @@ __device__ __forceinline__ void sched_kstep() {
   }
 }
 
-// Moments of the fused epilogue: one element of M^R or V^R (fp32 or bfloat16) at element index idx,
-// streamed (non-temporal: the state is not touched again within the step).
-template <bool SB16>
-__device__ __forceinline__ float load_moment(const APOLLO_GLOBAL void* base, size_t idx) {
-  if constexpr (SB16)
-    return bf16_bits_to_f32(__builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(base) + idx));
-  else
-    return __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL float*>(base) + idx);
-}
-// (a bfloat16 moment has been rounded by adam_element: the store truncates)
-template <bool SB16>
-__device__ __forceinline__ void store_moment(APOLLO_GLOBAL void* base, size_t idx, float v) {
-  if constexpr (SB16)
-    __builtin_nontemporal_store((uint16_t)(__float_as_uint(v) >> 16), reinterpret_cast<APOLLO_GLOBAL uint16_t*>(base) + idx);
-  else
-    __builtin_nontemporal_store(v, reinterpret_cast<APOLLO_GLOBAL float*>(base) + idx);
-}
-
 // FUSED (the step's kernel): the epilogue does not store R but carries on with Algorithm 1, steps 2-3,
 // on the accumulators: the low-rank Adam update of M^R, V^R for the block's RT rows (read, updated,
 // written back: the only pass over the state in the step), and a_j = sum_k R~[k,j]^2, b_j = sum_k
-// R[k,j]^2 over those rows (a lane sums its rows, lanes l and l+32 and then the WM waves that share a
-// channel are combined through LDS in a fixed order).  When the block holds all r rows (r = RT: rank
+// R[k,j]^2 over those rows (the tile passes through LDS so that the state is accessed in whole rows; a
+// lane sums its rows of four channels, the eight waves are combined through LDS in a fixed order).  When the block holds all r rows (r = RT: rank
 // 32, 64, 128, 256) it goes on to the channel factor s_j (Eq. 4) and the four block sums the limiter
 // kernel consumes; with several row tiles per channel tile (rank 96, 192, 512, ...) it leaves a_j, b_j
-// per row tile in the scratch and channel_factors_kernel adds them up.  A wave's access to a row of
-// M^R / V^R covers 32 consecutive channels (128 bytes) per half-wave.  SB16: the state is bfloat16.
+// per row tile in the scratch and channel_factors_kernel adds them up.  SB16: the state is bfloat16.
 // Not FUSED: R itself is stored, to r_override (the debug view: no R is kept by a step).
 template <int MT, int WM, bool LEFT, bool FUSED, bool SB16>
 __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
@@ -341,54 +323,153 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
     }
   } else {
     __syncthreads();                    // every wave is past its last fragment read: the ring is free
-    float* red_a = reinterpret_cast<float*>(lds);        // [WM][kNT]
-    float* red_b = red_a + WM * kNT;                     // [WM][kNT]
-    float* csq = red_b + WM * kNT;                       // [kNT]
+    // Two ways to the state, chosen by the row pitch n of M^R and V^R:
+    //  * n a multiple of 32: straight from the accumulators' own layout, a half-wave access = 32
+    //    consecutive channels of one row = one whole 128-byte line; no barrier, every wave on its own
+    //    (measured faster than the row pass below when the pieces are line-aligned: LLaMA-7B shapes
+    //    4.2 against 4.5 ms);
+    //  * otherwise (LLaMA-1B's 5461 channels): 128-byte pieces would straddle lines, and partially
+    //    written lines cost read-modify-write traffic (3.0 against 2.1 ms on those shapes), so the
+    //    accumulators go through LDS and M^R, V^R are accessed row by row: the R tile is laid out
+    //    row-major in LDS, one chunk of CH rows (the rows of one wave row) at a time, and every wave
+    //    walks whole rows of the chunk, a lane owning four consecutive channels -- one wave access =
+    //    256 consecutive channels = 1 KB of a row.
+    // Either way every wave ends with sums of a_j, b_j over the rows it handled, in red_a / red_b.
+    const bool direct = (n & 31) == 0;
+    float* red_a = reinterpret_cast<float*>(lds);        // [kWaves][kNT]: every wave's sums over its rows
+    float* red_b = red_a + kWaves * kNT;                 // [kWaves][kNT]
+    float* csq = red_b + kWaves * kNT;                   // [kNT]
     float* wsum = csq + kNT;                             // [4 waves][4]
     // the shifted last tile overlaps its neighbour: channels below jmin are that tile's
     const int jmin = (slot % tiles) * kNT;
-    {
-      // lanes l and l + 32 hold the two k-halves of channel (tile, l % 32)
-      const float t = sq + __shfl_xor(sq, 32, 64);
-      if (lane < 32) csq[32 * cx.tile_of(0) + lane] = t;
-    }
+    // lanes l and l + 32 hold the two k-halves of channel (fragment-0 tile, l % 32)
+    const float csq_own = sq + __shfl_xor(sq, 32, 64);
+    if (direct) {
+      // a wave holds sums for its own 32 NTW channels only: the rest of its row of red_a / red_b is zero
+      for (int i = cx.tid; i < 2 * kWaves * kNT; i += kThreads) red_a[i] = 0.f;
+      __syncthreads();
 #pragma unroll
-    for (int b = 0; b < C::NTW; ++b) {
-      const int jl = 32 * cx.tile_of(b) + (lane & 31);
-      const int j = cx.n0 + jl;
-      const bool valid = j >= jmin && j < n;
-      float a_sum = 0.f, b_sum = 0.f;
+      for (int b = 0; b < C::NTW; ++b) {
+        const int jl = 32 * cx.tile_of(b) + (lane & 31);
+        const int j = cx.n0 + jl;
+        const bool valid = j >= jmin && j < n;
+        float a_sum = 0.f, b_sum = 0.f;
 #pragma unroll
-      for (int a = 0; a < MT; ++a) {
-        const size_t idx0 = (size_t)(cx.rbase + cx.wm * 32 * MT + a * 32 + (lane >> 5) * 4) * (size_t)n + (size_t)j;
-        float mo[16], vo[16];
-        if (valid) {
+        for (int a = 0; a < MT; ++a) {
+          const size_t idx0 = (size_t)(cx.rbase + cx.wm * 32 * MT + a * 32 + (lane >> 5) * 4) * (size_t)n + (size_t)j;
+          typedef float one_t __attribute__((ext_vector_type(1)));
+          float mo[16], vo[16];
+          if (valid) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const size_t idx = idx0 + (size_t)((v >> 2) * 8 + (v & 3)) * (size_t)n;
-            mo[v] = load_moment<SB16>(d.M, idx);
-            vo[v] = load_moment<SB16>(d.V, idx);
+            for (int v = 0; v < 16; ++v) {
+              const size_t idx = idx0 + (size_t)((v >> 2) * 8 + (v & 3)) * (size_t)n;
+              mo[v] = load_state<1, SB16>(d.M, idx)[0];
+              vo[v] = load_state<1, SB16>(d.V, idx)[0];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const size_t idx = idx0 + (size_t)((v >> 2) * 8 + (v & 3)) * (size_t)n;
+              const float Re = acc[a][b][v] * scale;
+              float me, ve;
+              const float rt = adam_element<SB16>(sp, Re, mo[v], vo[v], me, ve);
+              a_sum = __builtin_fmaf(rt, rt, a_sum);
+              b_sum = __builtin_fmaf(Re, Re, b_sum);
+              one_t m1 = {me}, v1 = {ve};
+              store_state<1, SB16>(d.M, idx, m1);
+              store_state<1, SB16>(d.V, idx, v1);
+            }
           }
+        }
+        a_sum += __shfl_xor(a_sum, 32, 64);
+        b_sum += __shfl_xor(b_sum, 32, 64);
+        if (lane < 32) {
+          red_a[cx.wave * kNT + jl] = a_sum;
+          red_b[cx.wave * kNT + jl] = b_sum;
+        }
+      }
+    } else {
+      constexpr int CH = 32 * MT;
+      static_assert(CH * kNT * (int)sizeof(float) <= kRing * C::STAGE_BYTES, "a chunk of the R tile fits the ring");
+      float* tileR = reinterpret_cast<float*>(lds);        // [CH][kNT]
+      const int jl0 = 4 * lane, j0 = cx.n0 + jl0;          // this lane's four channels in the row pass
+      const int e_lo = max(0, jmin - j0), e_hi = min(4, n - j0);      // those of them that exist and are this tile's
+      const bool all4 = e_lo == 0 && e_hi == 4;
+      const bool quads_aligned = (n & 3) == 0;             // then every (row, j0) is a multiple of 4 elements
+      float a4[4] = {0.f, 0.f, 0.f, 0.f}, b4[4] = {0.f, 0.f, 0.f, 0.f};
+      auto load4 = [&](const APOLLO_GLOBAL void* base, size_t idx) -> f32x4_t {
+        if (all4) return quads_aligned ? load_state<4, SB16>(base, idx) : load_state<4, SB16, true>(base, idx);
+        f32x4_t v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const size_t idx = idx0 + (size_t)((v >> 2) * 8 + (v & 3)) * (size_t)n;
-            const float Re = acc[a][b][v] * scale;
-            float me, ve;
-            const float rt = adam_element<SB16>(sp, Re, mo[v], vo[v], me, ve);
-            a_sum = __builtin_fmaf(rt, rt, a_sum);
-            b_sum = __builtin_fmaf(Re, Re, b_sum);
-            store_moment<SB16>(d.M, idx, me);
-            store_moment<SB16>(d.V, idx, ve);
+        for (int e = 0; e < 4; ++e)
+          if (e >= e_lo && e < e_hi) v[e] = load_state<1, SB16>(base, idx + e)[0];
+        return v;
+      };
+      auto store4 = [&](APOLLO_GLOBAL void* base, size_t idx, f32x4_t v) {
+        if (all4) {
+          if (quads_aligned) store_state<4, SB16>(base, idx, v);
+          else store_state<4, SB16, true>(base, idx, v);
+          return;
+        }
+        typedef float one_t __attribute__((ext_vector_type(1)));
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (e >= e_lo && e < e_hi) {
+            one_t o = {v[e]};
+            store_state<1, SB16>(base, idx + e, o);
+          }
+      };
+#pragma unroll
+      for (int c = 0; c < WM; ++c) {
+        if (c > 0) __syncthreads();       // the previous chunk has been consumed
+        if (cx.wm == c) {
+#pragma unroll
+          for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int b = 0; b < C::NTW; ++b) {
+              float* col = tileR + (a * 32 + (lane >> 5) * 4) * kNT + 32 * cx.tile_of(b) + (lane & 31);
+#pragma unroll
+              for (int v = 0; v < 16; ++v) col[((v >> 2) * 8 + (v & 3)) * kNT] = acc[a][b][v] * scale;
+            }
+        }
+        __syncthreads();
+        if (e_lo < e_hi) {
+          const size_t row0 = (size_t)(cx.rbase + c * CH);
+          // wave w takes rows w, w + 8, ... of the chunk, four rows per trip (all loads of a trip first)
+          for (int rl = cx.wave; rl < CH; rl += 4 * kWaves) {
+            f32x4_t Rv[4], mo[4], vo[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int row = rl + kWaves * u;
+              const size_t idx = (row0 + row) * (size_t)n + (size_t)j0;
+              Rv[u] = *reinterpret_cast<const f32x4_t*>(tileR + row * kNT + jl0);
+              mo[u] = load4(d.M, idx);
+              vo[u] = load4(d.V, idx);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const size_t idx = (row0 + rl + kWaves * u) * (size_t)n + (size_t)j0;
+              f32x4_t mn, vn;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float Re = Rv[u][e];
+                float me, ve;
+                const float rt = adam_element<SB16>(sp, Re, mo[u][e], vo[u][e], me, ve);
+                a4[e] = __builtin_fmaf(rt, rt, a4[e]);     // (channels that are not this tile's are dropped below)
+                b4[e] = __builtin_fmaf(Re, Re, b4[e]);
+                mn[e] = me;
+                vn[e] = ve;
+              }
+              store4(d.M, idx, mn);
+              store4(d.V, idx, vn);
+            }
           }
         }
       }
-      a_sum += __shfl_xor(a_sum, 32, 64);
-      b_sum += __shfl_xor(b_sum, 32, 64);
-      if (lane < 32) {
-        red_a[cx.wm * kNT + jl] = a_sum;
-        red_b[cx.wm * kNT + jl] = b_sum;
-      }
+      __syncthreads();                  // the tile is consumed: its LDS now takes the sums
+      *reinterpret_cast<f32x4_t*>(red_a + cx.wave * kNT + jl0) = mk_f4(a4[0], a4[1], a4[2], a4[3]);
+      *reinterpret_cast<f32x4_t*>(red_b + cx.wave * kNT + jl0) = mk_f4(b4[0], b4[1], b4[2], b4[3]);
     }
+    if (lane < 32) csq[32 * cx.tile_of(0) + lane] = csq_own;
     __syncthreads();
     if (row_tiles > 1) {
       // several row tiles share these channels: leave this tile's sums for channel_factors_kernel
@@ -396,9 +477,10 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
         const int jl = cx.tid, j = cx.n0 + jl;
         if (j >= jmin && j < n) {
           float ae = red_a[jl], be = red_b[jl];
-          if (WM > 1) {
-            ae += red_a[kNT + jl];
-            be += red_b[kNT + jl];
+#pragma unroll
+          for (int w = 1; w < kWaves; ++w) {     // fixed order
+            ae += red_a[w * kNT + jl];
+            be += red_b[w * kNT + jl];
           }
           d.R[(size_t)(2 * row_tile) * n + j] = ae;
           d.R[(size_t)(2 * row_tile + 1) * n + j] = be;
@@ -413,9 +495,10 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
       float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
       if (j >= jmin && j < n) {
         float ae = red_a[jl], be = red_b[jl];
-        if (WM > 1) {
-          ae += red_a[kNT + jl];
-          be += red_b[kNT + jl];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) {       // fixed order
+          ae += red_a[w * kNT + jl];
+          be += red_b[w * kNT + jl];
         }
         const float c2 = csq[jl];
         const float sj = (be > 0.f) ? __builtin_sqrtf(ae) / __builtin_sqrtf(be) : 0.f;
@@ -494,7 +577,7 @@ hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, bool padded, 
                       hipStream_t st) {
   using C = Cfg<MT, WM>;
   const int lds_bytes = kRing * C::STAGE_BYTES;
-  static_assert(!FUSED || kRing * C::STAGE_BYTES >= (int)((2 * WM + 1) * kNT + 16) * (int)sizeof(float), "epilogue sums fit the ring");
+  static_assert(!FUSED || kRing * C::STAGE_BYTES >= (int)((2 * kWaves + 1) * kNT + 16) * (int)sizeof(float), "epilogue sums fit the ring");
   static std::atomic<bool> attr_done{false};   // (two threads arriving together both set the attribute: harmless)
   if (!attr_done.load(std::memory_order_acquire)) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&project_mfma_kernel<MT, WM, LEFT, FUSED, SB16>),

@@ -6,14 +6,14 @@ with tol = 1e-5 for fp32 gradients and 1e-3 for bf16 gradients; rms over the ten
 term is there because R = P G cancels: single entries can be arbitrarily small relative to the
 products summed.  That bound is applied as it stands to R, colsq, M, V and W.
 
-The factor s_j = ||R~[:,j]|| / ||R[:,j]|| divides by a column norm of R, so a channel whose
-projected gradient (or its history, through V, or its first moment M, which cancels when
-successive projected gradients have opposite signs) happens to be k times smaller than a
-typical one turns the admissible error of R into a k times larger relative error of s_j, and of
-everything that is multiplied by s_j (that channel's dW, and the tensor norm in proportion to
-the channel's weight in it).  condition_factors() computes k per channel from the oracle's own
-R, M and V by first-order error propagation (1 for a typical channel; for the tensor-wise
-factor, a ratio of Frobenius norms, it is 1 in practice); s, dW, norm and c are held to tol * k.
+The factor s_j = ||R~[:,j]|| / ||R[:,j]|| divides by a column norm of R.  For the tensor-wise factor
+and for channel-wise factors at rank >= 32 (plain_tolerance_applies) s, dW, the norm and c are held
+to the same tolerance.  Below that a channel's projected gradient can be arbitrarily small against
+the typical one (at rank 1 it is a single number that may fall next to zero), or its first moment can
+cancel, and the difference of the two sides' accumulation order, tiny as it is (E_IN_*), then shows
+in s_j enlarged: condition_factors() propagates that input error through the step and gives a
+factor k_j >= 1 (1 for all but such channels); s, dW, norm and c are held to tol * k, and run_parity
+asserts how many channels have k > 1 and how large k gets.
 """
 import math
 
@@ -76,6 +76,10 @@ def assert_close(name, got, ref, tol, extra_abs=0.0):
         k = int(np.argmax(err - bound))
         raise AssertionError("%s: %d of %d elements off; worst at flat %d: got %.9g ref %.9g (rms %.3g, tol %g)"
                              % (name, int(bad.sum()), ref.size, k, got.ravel()[k], ref.ravel()[k], rms, tol))
+    # how much of the bound was used (the largest err / bound; 0 where both vanish)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        used = np.where(bound > 0, err / bound, 0.0)
+    return float(used.max()) if used.size else 0.0
 
 
 def assert_rounds_within(name, got, exact, tol, extra_abs=0.0, min_pinned=None):
@@ -106,30 +110,60 @@ def assert_rounds_within(name, got, exact, tol, extra_abs=0.0, min_pinned=None):
                                 lo.ravel()[k], hi.ravel()[k]))
 
 
-def condition_factors(info, state, ocfg, t, tol):
-    """Per-channel amplification k_j >= 1 of the relative error of s_j (see the module text) and
-    its weighted mean for the tensor norm N = alpha sqrt(sum_j s_j^2 colsq_j).
+# What the two sides' projected gradients R can differ by: both form the same exact products and add
+# them in binary32 (the library) or fp64 (the oracle), in different orders.  Measured: below 4e-6 of
+# |R| + (a typical |R| of the channel) with bf16 gradients (m = 4096), 2.6e-6 with fp32 gradients (m = 1500).  The widening below is propagated from
+# THIS input error, not from the tolerance; where widening is in use, R is also held to it.
+E_IN_BF16 = 2e-5
+E_IN_F32 = 5e-6
 
-    First-order propagation of the admissible element errors dX = tol (|X| + rms X) of R, M, V
-    through R~ = M^ / (sqrt(V^) + eps), a_j = sum R~^2, b_j = sum R^2, s_j = sqrt(a_j / b_j).
-    For an element of typical size that propagation gives 5 tol (2 + 1 for R~, 2 for R); those
-    typical 4 tol in excess of the stated tolerance are taken off again, so a typical channel is
-    held to tol itself and an ill-conditioned one to its propagated bound.
-    """
+
+def condition_factors(info, state, ocfg, t, tol, e_in, acc, moments_adopted=False):
+    """Per-channel factor k_j >= 1 by which the bound on s_j is widened, and its weighted mean for the
+    tensor norm N = alpha sqrt(sum_j s_j^2 colsq_j).
+
+    Error model: the library's R differs from the oracle's by at most dR = e_in (|R[k,j]| + sqrt(colsq_j
+    / r)) per element: the accumulation error of a channel's products relative to that channel's own
+    scale (e_in = 0 without a projection: R is the gradient itself).  Its moments are built from its
+    own R, so they differ by the same recurrences applied to dR (dM <- beta1 dM + (1 - beta1) dR, dV <-
+    beta2 dV + (1 - beta2) (2 |R| dR + dR^2), kept in `acc` from step to step, plus one binary32
+    rounding per step), not by anything as large as the tolerance.  Those bounds go, to first order,
+    through R~ = M^ / (sqrt(V^) + eps): this step's dR along both moments at once (they move together),
+    the earlier steps' differences and the roundings with absolute values (no cancellation assumed);
+    then through a_j = sum R~^2, b_j = sum R^2, s_j = sqrt(a_j / b_j); the hardware reciprocal and
+    square root of the library add 3e-7 relative to R~.  k_j = max(1,
+    propagated relative error / tol): 1 unless the channel's projected gradient or its first moment
+    is tiny against its history (a single number near zero at rank 1; a first moment that cancels).
+    moments_adopted: the oracle continues from the library's stored moments (bfloat16 state), so
+    only this step's b_j carries dR."""
     R, M, V = info["R"], state.M, state.V
     bc1 = 1.0 - ocfg.beta1 ** t if ocfg.bias_correction else 1.0
     bc2 = 1.0 - ocfg.beta2 ** t if ocfg.bias_correction else 1.0
-    rms = lambda x: math.sqrt(float(np.mean(x * x)))
-    dR = tol * (np.abs(R) + rms(R))
-    dM = tol * (np.abs(M) + rms(M)) / bc1
-    dV = tol * (np.abs(V) + rms(V)) / bc2
+    # the channel's own scale: R[k, j] = sum_i z[k, i] G[i, j] / sqrt(r) has standard deviation
+    # sqrt(colsq_j / r) over the draws of z, and the accumulation error scales with it
+    r_rows = R.shape[0]
+    dR = e_in * (np.abs(R) + np.sqrt(info["colsq"] / r_rows)[None, :])
     Mh, Vh = M / bc1, V / bc2
     sq = np.sqrt(Vh)
     den = sq + ocfg.eps
-    with np.errstate(divide="ignore", invalid="ignore"):
-        d_sq = np.where(sq > 0, np.minimum(dV / (2.0 * sq), np.sqrt(dV)), np.sqrt(dV))
-        dRt = dM / den + np.abs(Mh) * d_sq / (den * den)
     Rt = info["Rt"]
+    if moments_adopted:
+        acc["dM"], acc["dV"] = np.zeros_like(R), np.zeros_like(R)
+        dRt = 3e-7 * np.abs(Rt)
+    else:
+        dM_prev, dV_prev = acc.get("dM", 0.0), acc.get("dV", 0.0)
+        # this step's dR enters M and V together: its effect on R~ is the derivative along both
+        # (at the first step M^ = R and V^ = R^2, R~ = R / (|R| + eps), and the derivative all but vanishes)
+        cm, cv = (1.0 - ocfg.beta1) / bc1, (1.0 - ocfg.beta2) * 2.0 * R / bc2
+        with np.errstate(divide="ignore", invalid="ignore"):
+            own = np.where(sq > 0, np.abs(cm / den - Mh * cv / (2.0 * sq * den * den)), cm / den) * dR
+            # earlier steps' differences (kept in acc) and this step's roundings are unrelated to it
+            iM = (ocfg.beta1 * dM_prev + np.abs(M) * 2.0 ** -23) / bc1
+            iV = (ocfg.beta2 * dV_prev + V * 2.0 ** -23 + (1.0 - ocfg.beta2) * dR * dR) / bc2
+            d_sq = np.where(sq > 0, np.minimum(iV / (2.0 * sq), np.sqrt(iV)), np.sqrt(iV))
+            dRt = own + iM / den + np.abs(Mh) * d_sq / (den * den) + 3e-7 * np.abs(Rt)
+        acc["dM"] = ocfg.beta1 * dM_prev + (1.0 - ocfg.beta1) * dR + np.abs(M) * 2.0 ** -23
+        acc["dV"] = ocfg.beta2 * dV_prev + (1.0 - ocfg.beta2) * (2.0 * np.abs(R) * dR + dR * dR) + V * 2.0 ** -23
     dRt = np.minimum(np.nan_to_num(dRt, nan=1.0, posinf=1e30), np.abs(Rt) + 1.0)
     da = np.sum(2.0 * np.abs(Rt) * dRt + dRt * dRt, axis=0)
     db = np.sum(2.0 * np.abs(R) * dR + dR * dR, axis=0)
@@ -142,7 +176,7 @@ def condition_factors(info, state, ocfg, t, tol):
     else:
         with np.errstate(divide="ignore", invalid="ignore"):
             rel = np.where(a > 0, da / (2.0 * a), 0.0) + np.where(b > 0, db / (2.0 * b), 0.0)
-    f = np.maximum(1.0, rel / tol - 4.0)
+    f = np.maximum(1.0, rel / tol)
     w = info["s"] ** 2 * info["colsq"]
     f_norm = float(np.sum(w * f) / np.sum(w)) if np.sum(w) > 0 else 1.0
     return f, f_norm
@@ -152,11 +186,37 @@ def to_host_f64(t):
     return t.detach().to("cpu").to(torch.float32).to(torch.float64).numpy()
 
 
+def plain_tolerance_applies(wl):
+    """Cases in which s, dW, the norm and c are held to the stated tolerance itself, with no widening
+    by condition_factors: the tensor-wise factor (a ratio of Frobenius norms over the whole tensor),
+    channel-wise factors at rank >= 16 on Gaussian or Student-t gradients (a channel's projected
+    gradient then is a sum over >= 16 rows and never much smaller than typical), and the rule without
+    projection (R is the gradient itself: the two sides start from identical numbers)."""
+    return wl.mode == "tensor" or wl.projection == "identity" or (
+        wl.rank >= 16 and wl.grad_kind in ("normal", "student_t") and wl.grad_scale >= 1e-6)
+
+
 def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side="auto", bias_correction=True,
-               boost=None, compare_steps=None, lr=None, progress=None):
+               boost=None, compare_steps=None, lr=None, progress=None, independent_w=False, widen=None,
+               max_widened_share=None, max_k=None, stats=None):
     """Steps the whole workload on the GPU and the tensors `check_ids` in the oracle.
     boost: {step: factor} multiplies that step's gradients.  Returns the number of limiter hits
-    seen by the oracle (so callers can assert the case was exercised)."""
+    seen by the oracle (so callers can assert the case was exercised).
+
+    widen: whether the bound on s, dW, norm and c may be widened per channel by condition_factors
+    (module text); None = by plain_tolerance_applies(wl).  Where it may, the share of channels (per
+    tensor and step) whose factor k exceeds 1 must stay below max_widened_share and k below max_k: a
+    widening that became common or huge would wave real errors through.  Defaults: a quarter of the
+    channels and k <= 10^4 with bf16 gradients (tolerance 1e-3, fifty times the input error); with fp32
+    gradients the tolerance 1e-5 is only twice the input error, the worst-case propagation
+    exceeds it on most channels by a small factor, so there the median k must stay below 20 and k
+    below 10^6 (at rank 1 a channel is a single number that can fall next to zero).  stats, a dict if given,
+    receives the largest share, the largest k and, per quantity, the largest used fraction of its bound.
+
+    independent_w: the oracle carries its own weights from step 0 (by default every step starts both
+    sides from the library's fp32 weights).  The two trajectories then differ by the admissible errors
+    of all earlier steps: the final weights are compared under the sum of the per-step bounds on dW
+    plus one binary32 rounding of W per step."""
     boost = boost or {}
     lr = wl.lr if lr is None else lr
     lr32 = f32(lr)
@@ -178,6 +238,15 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
     W_or = {i: to_host_f64(weights[i]) for i in check_ids}
     hits = 0
     f_norm_prev = {i: 0.0 for i in check_ids}
+    widen = (not plain_tolerance_applies(wl)) if widen is None else widen
+    stats = {} if stats is None else stats
+    stats.update({"widened_share": 0.0, "k_max": 1.0, "used": {}})
+    acc_bound = {i: 0.0 for i in check_ids}       # independent_w: accumulated admissible difference of the weights
+    e_in = 0.0 if identity else (E_IN_BF16 if bf16 else E_IN_F32)
+    cf_acc = {i: {} for i in check_ids}
+
+    def note(name, used):
+        stats["used"][name] = max(stats["used"].get(name, 0.0), used)
     for t in range(1, steps + 1):
         WL.make_grads(wl, t, device, out=grads, boost=boost.get(t, 1.0))
         before = {i: to_host_f64(weights[i]) for i in check_ids}
@@ -186,10 +255,12 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
         full = compare_steps is None or t in compare_steps
         for i in check_ids:
             G = to_host_f64(grads[i])
-            # every step starts both sides from the same fp32 weights (the GPU's): the weight-decay
-            # term reads W, and the two trajectories differ by the admissible error of earlier steps
-            W_or[i] = before[i].copy()
-            W_prev = before[i]
+            # by default every step starts both sides from the same fp32 weights (the GPU's): the
+            # weight-decay term reads W, and the two trajectories differ by the admissible error of
+            # earlier steps; independent_w: the oracle keeps its own
+            if not independent_w:
+                W_or[i] = before[i].copy()
+            W_prev = W_or[i].copy()
             tag = "%s tensor %d step %d " % (wl.name, i, t)
             adopt = None
             if state_bf16:
@@ -204,7 +275,17 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
                     return M_gpu, V_gpu
             info = O.step(ocfg, states[i], W_or[i], G, t, lr32, tensor_id=i, grad_is_bf16=bf16, adopt_moments=adopt)
             hits += info["c"] < 1.0
-            f_chan, f_norm = condition_factors(info, states[i], ocfg, t, tol)
+            f_chan, f_norm = condition_factors(info, states[i], ocfg, t, tol, e_in, cf_acc[i], moments_adopted=state_bf16)
+            if widen:
+                share, kmax, kmed = float(np.mean(f_chan > 1.0)), float(f_chan.max()), float(np.median(f_chan))
+                stats["widened_share"], stats["k_max"] = max(stats["widened_share"], share), max(stats["k_max"], kmax)
+                lim_share = max_widened_share if max_widened_share is not None else (0.25 if bf16 else 1.0)
+                lim_k = max_k if max_k is not None else (1e4 if bf16 else 1e6)
+                assert share <= lim_share and kmax <= lim_k and kmed <= (1.0 if bf16 else 20.0), \
+                    "%s tensor %d step %d: %.3f of the channels have a widened bound (limit %.3f), largest factor %.3g (limit %.3g), median %.3g" % (
+                        wl.name, i, t, share, lim_share, kmax, lim_k, kmed)
+            else:
+                f_chan, f_norm = np.ones_like(f_chan), 1.0
             f_c = f_norm + f_norm_prev[i]
             f_norm_prev[i] = f_norm
             # admissible error of this step's dW: the factors' relative error times |dW|
@@ -213,22 +294,27 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
             dw_ref = W_or[i] - W_prev
             rms_dw = math.sqrt(float(np.mean(dw_ref * dw_ref)))
             dw_bound = tol * f_dw * (np.abs(dw_ref) + rms_dw)
+            if independent_w:
+                # the decay term read different weights on the two sides
+                dw_bound = dw_bound + lr32 * ocfg.weight_decay * acc_bound[i]
+                acc_bound[i] = acc_bound[i] + dw_bound + (np.abs(W_or[i]) + np.abs(dw_ref)) * 2.0 ** -24
             if not full:
                 continue
             if not identity:
-                assert_close(tag + "R", to_host_f64(stepper.debug(i, A.APOLLO_DBG_R)), info["R"], tol)
-            assert_close(tag + "colsq", to_host_f64(stepper.debug(i, A.APOLLO_DBG_COLSQ)), info["colsq"], tol)
+                # (where the widening is in use, R is also held to the input error the widening is derived from)
+                note("R", assert_close(tag + "R", to_host_f64(stepper.debug(i, A.APOLLO_DBG_R)), info["R"], e_in if widen else tol))
+            note("colsq", assert_close(tag + "colsq", to_host_f64(stepper.debug(i, A.APOLLO_DBG_COLSQ)), info["colsq"], tol))
             if not state_bf16:
-                assert_close(tag + "M", moments(i, A.APOLLO_DBG_M), states[i].M, tol)
-                assert_close(tag + "V", moments(i, A.APOLLO_DBG_V), states[i].V, tol)
+                note("M", assert_close(tag + "M", moments(i, A.APOLLO_DBG_M), states[i].M, tol))
+                note("V", assert_close(tag + "V", moments(i, A.APOLLO_DBG_V), states[i].V, tol))
             s_gpu = to_host_f64(stepper.debug(i, A.APOLLO_DBG_S))
             s_ref = info["s"] if wl.mode == "channel" else info["s"][:1]
             f_s = f_chan if wl.mode == "channel" else f_chan[:1]
-            assert_close(tag + "s", s_gpu, s_ref, 0.0, extra_abs=tol * f_s * np.abs(s_ref))
+            note("s", assert_close(tag + "s", s_gpu, s_ref, 0.0, extra_abs=tol * f_s * np.abs(s_ref)))
             c_gpu = to_host_f64(stepper.debug(i, A.APOLLO_DBG_C))
-            assert_close(tag + "c", c_gpu, [info["c"]], tol * f_c)
-            assert_close(tag + "norm", to_host_f64(stepper.debug(i, A.APOLLO_DBG_NORM)), [info["norm"]],
-                         tol * f_norm)
+            note("c", assert_close(tag + "c", c_gpu, [info["c"]], tol * f_c))
+            note("norm", assert_close(tag + "norm", to_host_f64(stepper.debug(i, A.APOLLO_DBG_NORM)), [info["norm"]],
+                                      tol * f_norm))
             after = to_host_f64(weights[i])
             if float(c_gpu[0]) < 1.0 and not info["c"] < 1.0:         # only the GPU side limited (c ~ 1)
                 dw_bound = dw_bound + tol * f_c * (np.abs(dw_ref) + rms_dw)
@@ -237,10 +323,18 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
                 # admissible error of the oracle's unrounded new weight
                 assert_rounds_within(tag + "W", after, info["W_exact"], 0.0, extra_abs=dw_bound + np.abs(after) * 2.0 ** -24)
             else:
-                assert_close(tag + "dW", after - before[i], dw_ref, 0.0,
-                             extra_abs=dw_bound + np.abs(after) * 2.0 ** -24)
-                assert_close(tag + "W", after, W_or[i], tol, extra_abs=dw_bound)
+                note("dW", assert_close(tag + "dW", after - before[i], dw_ref, 0.0,
+                                        extra_abs=dw_bound + np.abs(after) * 2.0 ** -24))
+                if not independent_w:
+                    assert_close(tag + "W", after, W_or[i], tol, extra_abs=dw_bound)
         if progress:
             print("%s: step %d/%d compared" % (wl.name, t, steps), flush=True)
+    if independent_w:
+        # the library's weights after all steps against the oracle's own trajectory
+        for i in check_ids:
+            note("W_final", assert_close("%s tensor %d W after %d independent steps" % (wl.name, i, steps),
+                                         to_host_f64(weights[i]), W_or[i], 0.0, extra_abs=acc_bound[i]))
     stepper.close()
+    print("parity %s: widened share %.3f, largest factor %.3g, used fraction of the bounds: %s" % (
+        wl.name, stats["widened_share"], stats["k_max"], ", ".join("%s %.3g" % kv for kv in sorted(stats["used"].items()))), flush=True)
     return hits

@@ -16,7 +16,7 @@ import paper_2412_05270_amd as A
 from oracle import apollo as O
 from oracle import q8 as Q
 from paper_2412_05270_amd import workloads as WL
-from parity_util import (TOL_BF16, TOL_F32, assert_close, assert_rounds_within, condition_factors, f32, make_configs,
+from parity_util import (E_IN_BF16, E_IN_F32, TOL_BF16, TOL_F32, assert_close, assert_rounds_within, condition_factors, f32, make_configs,
                          to_host_f64)
 
 pytestmark = pytest.mark.gpu
@@ -28,6 +28,7 @@ def _run(wl, steps, lr, check_ids=None, progress=False):
     tol = TOL_BF16 if bf16 else TOL_F32
     cfg, ocfg = make_configs(wl)
     state_bf16 = wl.state_dtype == torch.bfloat16
+    cf_acc = {}
     if check_ids is None:
         # initial weights: N(0, w_std^2) quantised on the host (nearest)
         check_ids = list(range(len(wl.shapes)))
@@ -78,7 +79,8 @@ def _run(wl, steps, lr, check_ids=None, progress=False):
                     return M_gpu, V_gpu
             info = O.step(ocfg, states[i], Wq, to_host_f64(grads[i]), t, f32(lr), tensor_id=i, grad_is_bf16=bf16,
                           adopt_factors=adopt, adopt_moments=adopt_mv)
-            f_chan, f_norm = condition_factors(info, states[i], ocfg, t, tol)
+            f_chan, f_norm = condition_factors(info, states[i], ocfg, t, tol, E_IN_BF16 if bf16 else E_IN_F32,
+                                               cf_acc.setdefault(i, {}), moments_adopted=state_bf16)
             if not state_bf16:
                 assert_close(tag + "M", to_host_f64(st.debug(i, A.APOLLO_DBG_M)), states[i].M, tol)
                 assert_close(tag + "V", to_host_f64(st.debug(i, A.APOLLO_DBG_V)), states[i].V, tol)

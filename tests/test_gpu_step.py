@@ -268,3 +268,18 @@ def test_matrix_core_projection_at_rank_1024():
     wl = WL.Workload("mfma_r1024", 17, shapes, torch.bfloat16, "normal", 1e-2, rank=1024, refresh_interval=2,
                      steps=3, lr=1e-2)
     run_parity(wl, list(range(len(shapes))), wl.steps)
+
+
+@pytest.mark.parametrize("name,steps", [("single256", 10), ("llama60m", 12)])
+def test_weights_follow_an_independent_oracle_trajectory(name, steps):
+    """The other parity runs start every step from the library's weights; here the oracle carries its
+    own W from step 0 through all steps, with weight decay on (the decay term reads W), and the final
+    weights must agree within the accumulated per-step bounds: config 1 with all its 10 steps (fp32,
+    two re-samplings of P) and 12 steps of the LLaMA-60M set."""
+    wl = WL.workload(name)
+    wl.weight_decay = 0.1
+    wl.name = name + "_independent_w"
+    ids = [0] if name == "single256" else _first_and_last_layer(wl)
+    stats = {}
+    run_parity(wl, ids, steps, independent_w=True, stats=stats)
+    assert 0.0 < stats["used"]["W_final"] <= 1.0

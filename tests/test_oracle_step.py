@@ -598,3 +598,40 @@ def test_adopt_factors_scales_the_update_but_not_the_reported_factors():
     # own factors: s_j = 1 / |G_j|, c = 1; the update uses 3 s and c / 2: W = -lr * 1.5 * sign(G)
     assert np.allclose(info["s"], [0.5, 1.0]) and info["c"] == 1.0
     assert np.allclose(W, [[-0.75, -0.75]])
+
+
+@pytest.mark.parametrize("rows,cols", [(6, 11), (11, 6), (7, 7)])
+@pytest.mark.parametrize("mode,rank,projection", [(apollo.CHANNEL, 3, "random"), (apollo.TENSOR, 1, "random"),
+                                                  (apollo.CHANNEL, 1, "identity"), (apollo.TENSOR, 1, "identity")])
+@pytest.mark.parametrize("bias_correction,state_dtype", [(True, "f32"), (False, "f32"), (True, "bf16")])
+def test_first_step_closed_form_equals_the_recurrence_at_t_1(rows, cols, mode, rank, projection, bias_correction,
+                                                             state_dtype):
+    """first_step_closed_form restates step() at t = 1; both namespaces (numpy and torch) must give
+    what the recurrence gives from a zero state: R, colsq, M, V, s, the norm, c = 1 and the weight
+    change (gradient part + decay)."""
+    import torch
+    rng = np.random.default_rng(rows * 31 + cols)
+    G = gauss.round_to_bf16(rng.standard_normal((rows, cols)).astype(np.float32) * 1e-2).astype(np.float64)
+    G[:, 2] = 0.0 if rows <= cols else G[:, 2]          # a zero channel (0/0 in s_j) when channels are columns
+    if rows > cols:
+        G[2, :] = 0.0
+    W0 = rng.standard_normal((rows, cols)) * 0.02
+    cfg = apollo.Config(rank=rank, mode=mode, seed=77, eps=1e-8, scale=1.7, weight_decay=0.03, bias_correction=bias_correction,
+                   state_dtype=state_dtype, projection=projection, refresh_interval=4)
+    lr = 1e-2
+    st = apollo.init_state(cfg, rows, cols)
+    W = W0.copy()
+    info = apollo.step(cfg, st, W, G, 1, lr, tensor_id=5, grad_is_bf16=True)
+    m = min(rows, cols)
+    z = None if projection == "identity" else gauss.projection(77, 5, 0, rank, m, True)
+    for xp, conv, back in ((np, lambda x: x, lambda x: np.asarray(x)),
+                           (torch, lambda x: None if x is None else torch.from_numpy(np.ascontiguousarray(x)), lambda x: x.numpy() if hasattr(x, "numpy") else np.asarray(x))):
+        cf = apollo.first_step_closed_form(cfg, conv(G), lr, z=conv(z), xp=xp)
+        assert cf["left"] == info["left"] and cf["c"] == 1.0 == info["c"]
+        for key in ("R", "colsq", "s"):
+            np.testing.assert_allclose(back(cf[key]), info[key], rtol=1e-12, atol=1e-300, err_msg=key)
+        np.testing.assert_allclose(back(cf["M"]), st.M, rtol=1e-12, atol=1e-300)
+        np.testing.assert_allclose(back(cf["V"]), st.V, rtol=1e-12, atol=1e-300)
+        np.testing.assert_allclose(float(cf["norm"]), info["norm"], rtol=1e-12)
+        np.testing.assert_allclose(back(cf["dW_grad"]) - lr * cfg.weight_decay * W0, W - W0, rtol=1e-9, atol=1e-18)
+    assert np.any(info["s"] == 0.0) or mode == apollo.TENSOR
