@@ -11,8 +11,8 @@ kernel phase that takes the most time (algorithmic bytes or flops per step divid
 phase's HIP-event time, against the MI355X peak); "cpu_baseline" is the fp64 oracle timed on
 the host cores on a bounded sample of the same workload; "also" carries the same measurement
 for further variants on the same shapes (rank 256, which the benchmark definition asks for as well;
-bfloat16 and 8-bit storage) and for the benchmark definition's other full-size configurations (LLaMA-1B
-shapes at rank 512; LLaMA-13B shapes, Mini and rank 256, five timed steps of which the first re-samples
+bfloat16 and 8-bit storage) and for the benchmark definition's other configurations (LLaMA-60M shapes at
+rank 128; LLaMA-1B shapes at rank 512; LLaMA-13B shapes, Mini and rank 256, five timed steps of which the first re-samples
 P); "adamw_rest" the element-wise AdamW launch on the model's non-projected parameters.  Every step
 gets freshly drawn gradients (seed = 1000 * config + step); they are generated between the timed
 steps, outside the timed region: each step is bracketed by a device synchronisation on both sides,
@@ -322,7 +322,7 @@ def main():
     ap.add_argument("--workload", default="llama7b_mini")
     ap.add_argument("--also", default="llama7b_r256,llama7b_mini_bf16,llama7b_r256_bf16,llama7b_mini_q8",
                     help="further variants on the same shapes, comma separated ('' = none)")
-    ap.add_argument("--configs", default="llama1b,llama13b_mini,llama13b_r256",
+    ap.add_argument("--configs", default="llama60m,llama1b,llama13b_mini,llama13b_r256",
                     help="the benchmark definition's other full-size configurations, each on its own weights and "
                          "gradients, reported under 'also' (comma separated, '' = none); the LLaMA-13B ones time five "
                          "steps starting at step 201, which re-samples P (T = 200)")

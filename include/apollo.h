@@ -27,7 +27,10 @@
  *     the state buffer and the workspace (all DEVICE memory) and keeps them alive while the
  *     handle uses them.  The library owns only the host-side handle.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default
- *     stream) and return without synchronising.  Nothing is read back to the host.
+ *     stream) and return without synchronising the stream.  Nothing is read back to the host.
+ *     (One wait can occur: apollo_step copies the tensor pointers to the device through one of four
+ *     pinned staging slots when they differ from the previous call's; a call that changes them waits
+ *     for the copy made four such calls earlier, which has normally long finished.)
  *   - Functions returning apollo_status_t return APOLLO_OK (0) or a negative code; argument
  *     errors are detected before anything is launched.  apollo_last_error() gives the text.
  *   - `g` is the ordinary gradient (d loss / d W); the step subtracts.

@@ -18,7 +18,8 @@ Readings taken where the paper is silent or inconsistent:
   * P ~ N(0, 1/r) (Algorithm 1, Theorem A.1): unit-variance z times 1/sqrt(r).
   * The limiter acts on the Frobenius norm of the whole scaled gradient alpha * G diag(s), one
     number per tensor (Table 1 counts one stored norm); nothing is limited while the stored norm
-    is 0 (first step); the stored norm is the one after limiting.
+    is 0 (first step); the stored norm is the one after limiting; a step whose norm is not finite
+    (a gradient with inf or NaN in it) does not replace it.
   * A channel whose projected gradient is exactly zero gets s_j = 0 (0/0 otherwise).
   * M^R, V^R are kept when P is re-sampled.
   * Steps are 1-based: P is re-sampled when (t-1) mod T == 0, epoch = (t-1) div T.
@@ -174,7 +175,8 @@ def step(cfg, state, W, G, t, lr, tensor_id=0, grad_is_bf16=False, P=None, adopt
     if cfg.nl_gamma > 0 and state.prev_norm > 0 and norm > cfg.nl_gamma * state.prev_norm:
         c = cfg.nl_gamma * state.prev_norm / norm
         norm = cfg.nl_gamma * state.prev_norm
-    state.prev_norm = norm
+    if np.isfinite(norm):                         # (a non-finite step leaves the stored norm alone)
+        state.prev_norm = norm
     s_own, c_own = s, c
     if adopt_factors is not None:
         s, c = adopt_factors(s, c)

@@ -307,17 +307,23 @@ class AdamwStepper:
             raise ApolloError(APOLLO_EINVAL, apollo_adamw_last_error())
         self.state = torch.empty(sb, dtype=torch.uint8, device=device)
         self.workspace = torch.empty(wb, dtype=torch.uint8, device=device)
-        self.stream = torch.cuda.current_stream(device)
+        self.device = self.state.device
         rc, self.handle = apollo_adamw_init(cfg, self.shapes, self.state.data_ptr(), sb, self.workspace.data_ptr(), wb,
-                                            1 if zero_state else 0, self.stream.cuda_stream)
+                                            1 if zero_state else 0, self._stream())
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_adamw_last_error())
         self._tensors = (ApolloTensor * len(self.weights))()
         for i, (w, g) in enumerate(zip(self.weights, self.grads)):
             self._tensors[i] = ApolloTensor(w.data_ptr(), g.data_ptr())
 
+    def _stream(self):
+        """torch's current stream on the buffers' device, looked up at every call: the work is
+        ordered after whatever the caller has queued there (its gradients), on whichever stream
+        the caller has made current."""
+        return self.torch.cuda.current_stream(self.device).cuda_stream
+
     def step(self, step, lr):
-        rc = apollo_adamw_step(self.handle, self._tensors, step, lr, self.stream.cuda_stream)
+        rc = apollo_adamw_step(self.handle, self._tensors, step, lr, self._stream())
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_adamw_last_error(self.handle))
 
@@ -375,9 +381,9 @@ class ApolloStepper:
             raise ApolloError(APOLLO_EINVAL, apollo_last_error())
         self.state = torch.empty(sb, dtype=torch.uint8, device=device)
         self.workspace = torch.empty(wb, dtype=torch.uint8, device=device)
-        self.stream = torch.cuda.current_stream(device)
+        self.device = self.state.device
         rc, self.handle = apollo_init(cfg, self.shapes, self.state.data_ptr(), sb, self.workspace.data_ptr(), wb,
-                                      1 if zero_state else 0, self.stream.cuda_stream)
+                                      1 if zero_state else 0, self._stream())
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_last_error())
         self._tensors = (ApolloTensor * len(self.weights))()
@@ -389,8 +395,12 @@ class ApolloStepper:
         for i, (w, g, mt) in enumerate(zip(self.weights, self.grads, self.metas)):
             self._tensors[i] = ApolloTensor(w.data_ptr(), g.data_ptr(), mt.data_ptr() if mt is not None else None)
 
+    def _stream(self):
+        """torch's current stream on the buffers' device, looked up at every call (see AdamwStepper)."""
+        return self.torch.cuda.current_stream(self.device).cuda_stream
+
     def step(self, step, lr):
-        rc = apollo_step(self.handle, self._tensors, step, lr, self.stream.cuda_stream)
+        rc = apollo_step(self.handle, self._tensors, step, lr, self._stream())
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_last_error(self.handle))
 
@@ -412,7 +422,7 @@ class ApolloStepper:
             out = torch.empty(n, dtype=torch.float32, device=self.state.device)
         else:
             out = torch.empty(1, dtype=torch.float32, device=self.state.device)
-        rc = apollo_debug_get(self.handle, tensor, what, out.data_ptr(), out.numel() * 4, self.stream.cuda_stream)
+        rc = apollo_debug_get(self.handle, tensor, what, out.data_ptr(), out.numel() * 4, self._stream())
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_last_error(self.handle))
         return out
@@ -430,7 +440,7 @@ class ApolloStepper:
         out = torch.empty((self.cfg.rank, m), dtype=torch.bfloat16 if bf16 else torch.float32,
                           device=self.state.device)
         rc = apollo_debug_fill_projection(self.handle, tensor, step, out.data_ptr(),
-                                          APOLLO_BF16 if bf16 else APOLLO_F32, self.stream.cuda_stream)
+                                          APOLLO_BF16 if bf16 else APOLLO_F32, self._stream())
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_last_error(self.handle))
         return out

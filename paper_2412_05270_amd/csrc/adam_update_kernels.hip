@@ -285,7 +285,8 @@ hipError_t launch_adam_identity(const TensorDesc* d_descs, int count, int rows, 
 // ---------------------------------------------------------------------------------------------
 // Per-tensor scalars: the tensor-wise factor (Section 4.2), the norm of the scaled gradient
 // N = alpha sqrt(sum_j s_j^2 colsq_j) and the limiter (Eq. 3): if N > gamma N_prev the update is
-// rescaled to norm gamma N_prev, which is also what is remembered.  One wave per tensor.
+// rescaled to norm gamma N_prev, which is also what is remembered (unless it is not finite).  One
+// wave per tensor.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void finalize_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
   const TensorView d(descs[blockIdx.x]);
@@ -318,7 +319,9 @@ __global__ __launch_bounds__(64) void finalize_kernel(const TensorDesc* __restri
       c = sp.gamma * prev / norm;
       norm = sp.gamma * prev;
     }
-    *d.prev_norm = norm;
+    // A non-finite gradient makes this step's norm non-finite; the stored norm then stays what it
+    // was (a NaN there would switch the limiter off for good: every later comparison would be false).
+    if (norm - norm == 0.f) *d.prev_norm = norm;
     d.scal[0] = sp.lr * sp.alpha * c * (sp.tensor_mode ? s_tensor : 1.f);
     d.scal[1] = c;
     d.scal[2] = norm;

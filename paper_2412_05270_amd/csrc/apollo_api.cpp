@@ -354,9 +354,18 @@ hipError_t run_serial(GroupLaunches& L, const Plan& plan, hipStream_t st, hipEve
     e = L.fill(g, st);
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[1], st);
+  // the matrix-core groups share one launch (a small set then fills the chip at once, a large one has
+  // a single tail); the others are launched group by group
+  std::vector<MfmaGroupShape> mfma;
   for (const Group& g : plan.groups) {
     if (e != hipSuccess) break;
-    e = L.project(g, st);
+    if (g.path == Path::kMfma) mfma.push_back(MfmaGroupShape{g.first, g.count, g.rows, g.cols, g.left, g.pad_g});
+    else e = L.project(g, st);
+  }
+  if (e == hipSuccess && !mfma.empty()) {
+    L.what = "projection";
+    e = launch_project_mfma_groups(L.dd, mfma.data(), (int)mfma.size(), true, L.cfg.state_dtype == APOLLO_BF16, nullptr,
+                                   L.sp, st);
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[2], st);
   for (const Group& g : plan.groups) {

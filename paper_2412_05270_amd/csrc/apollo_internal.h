@@ -157,6 +157,14 @@ bool project_rank1_supported(int rows, int cols, bool left, bool bf16);
 // launch_channel_factors follows).  Not fused (count must be 1): R is stored to r_override (debug view).
 hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool padded,
                                bool fused, bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st);
+// The same for several shape groups in one launch (their blocks follow each other in the grid); `first`
+// is the group's first descriptor relative to d_descs.
+struct MfmaGroupShape {
+  int first, count, rows, cols;
+  bool left, padded;
+};
+hipError_t launch_project_mfma_groups(const TensorDesc* d_descs, const MfmaGroupShape* groups, int n_groups, bool fused,
+                                      bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st);
 hipError_t launch_channel_factors(const TensorDesc* d_descs, int count, int n, int row_tiles, hipStream_t st);
 int project_mfma_row_tiles(int r);
 int project_mfma_tiles(int n);

@@ -120,10 +120,12 @@ __device__ __forceinline__ void projection_quad(const PhiloxKeySchedule& ks, uin
   gauss_pair(c[2], c[3], z[2], z[3]);
 }
 
-// float -> bfloat16, round to nearest even (no NaN inputs occur here); returns the 16 bits.
+// float -> bfloat16, round to nearest even; returns the 16 bits.  A NaN stays a NaN (its upper bits,
+// made quiet): the rounding increment must not carry a NaN's payload into the exponent or sign.
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float v) {
   const uint32_t b = __float_as_uint(v);
-  return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+  const uint32_t rounded = (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+  return (b & 0x7FFFFFFFu) > 0x7F800000u ? ((b >> 16) | 0x0040u) : rounded;
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }

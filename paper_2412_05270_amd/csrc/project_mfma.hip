@@ -22,6 +22,7 @@
 // for each direct-to-LDS load separately); vmcnt is therefore managed by hand: every stage
 // issues the same number of loads per wave, and "stage s+1 has landed" is vmcnt(loads of one
 // stage) because the only younger loads are those of stage s+2.
+#include <algorithm>
 #include <atomic>
 
 #include "apollo_internal.h"
@@ -229,18 +230,18 @@ __device__ __forceinline__ void sched_kstep() {
 // kernel consumes; with several row tiles per channel tile (rank 96, 192, 512, ...) it leaves a_j, b_j
 // per row tile in the scratch and channel_factors_kernel adds them up.  SB16: the state is bfloat16.
 // Not FUSED: R itself is stored, to r_override (the debug view: no R is kept by a step).
+// `block` is the block's number within its shape group (see project_mfma_kernel).
 template <int MT, int WM, bool LEFT, bool FUSED, bool SB16>
-__global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
-                                                                    int tiles, int count, int padded,
-                                                                    float* __restrict__ r_override) {
+__device__ __forceinline__ void project_body(const TensorDesc* __restrict__ descs, const StepParams& sp, int tiles,
+                                             int count, int padded, float* __restrict__ r_override, int block,
+                                             unsigned char* lds) {
   using C = Cfg<MT, WM>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   // XCD-aware numbering: block w runs on XCD w % 8; XCD x works through tensors x, x+8, ...
   // Within a tensor the row tiles of one channel tile are neighbours on their XCD: they read the
   // same tile of G at about the same time, so all but the first find it in that XCD's L2.
   const int row_tiles = sp.r / C::RT;
-  const int xcd = blockIdx.x % kXcds, slot = (blockIdx.x / kXcds) / row_tiles;
-  const int row_tile = (blockIdx.x / kXcds) % row_tiles;
+  const int xcd = block % kXcds, slot = (block / kXcds) / row_tiles;
+  const int row_tile = (block / kXcds) % row_tiles;
   const int tensor = xcd + kXcds * (slot / tiles);
   if (tensor >= count) return;
   const TensorView d(descs[tensor]);
@@ -530,6 +531,40 @@ __global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc
   }
 }
 
+// One launch serves up to kMaxGroups shape groups (tensors of one shape and orientation each): the
+// blocks of the groups follow each other in the grid, every group's count a multiple of the XCD
+// count, so that block w still runs on XCD w % 8.  A set of a few small tensors then fills the chip
+// with one launch, and a large set has one tail of partly idle compute units instead of one per group.
+constexpr int kMaxGroups = 8;
+struct MfmaGroup {
+  int first, count;     // its descriptors: descs[first .. first + count)
+  int tiles;            // channel tiles per tensor
+  int blocks_end;       // one past its last block in the grid
+  int left, padded;     // rows projected; the gradient is read from the row-padded copy
+};
+struct MfmaGroups {
+  MfmaGroup g[kMaxGroups];
+  int n;
+};
+
+template <int MT, int WM, bool FUSED, bool SB16>
+__global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
+                                                                    MfmaGroups tbl, float* __restrict__ r_override) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int b = blockIdx.x;
+  int first = 0, count = 0, tiles = 1, left = 0, padded = 0, begin = 0;
+#pragma unroll
+  for (int i = 0; i < kMaxGroups; ++i) {
+    const int lo = i ? tbl.g[i - 1].blocks_end : 0;
+    if (i < tbl.n && b >= lo && b < tbl.g[i].blocks_end) {
+      first = tbl.g[i].first; count = tbl.g[i].count; tiles = tbl.g[i].tiles;
+      left = tbl.g[i].left; padded = tbl.g[i].padded; begin = lo;
+    }
+  }
+  if (left) project_body<MT, WM, true, FUSED, SB16>(descs + first, sp, tiles, count, padded, r_override, b - begin, lds);
+  else project_body<MT, WM, false, FUSED, SB16>(descs + first, sp, tiles, count, padded, r_override, b - begin, lds);
+}
+
 // Channel factors for ranks with several row tiles per channel tile: adds the row tiles' a_j, b_j (fixed
 // order), forms s_j (Eq. 4) and leaves the four block sums of 256 channels, as the fused epilogue does
 // when one block holds all rows.
@@ -572,43 +607,29 @@ __global__ __launch_bounds__(kNT) void channel_factors_kernel(const TensorDesc* 
         ((wsum[0][threadIdx.x] + wsum[1][threadIdx.x]) + wsum[2][threadIdx.x]) + wsum[3][threadIdx.x];
 }
 
-template <int MT, int WM, bool LEFT, bool FUSED, bool SB16>
-hipError_t launch_cfg(const TensorDesc* d_descs, int count, int n, bool padded, float* r_override, const StepParams& sp,
-                      hipStream_t st) {
+template <int MT, int WM, bool FUSED, bool SB16>
+hipError_t launch_cfg(const TensorDesc* d_descs, const MfmaGroups& tbl, float* r_override, const StepParams& sp, hipStream_t st) {
   using C = Cfg<MT, WM>;
   const int lds_bytes = kRing * C::STAGE_BYTES;
   static_assert(!FUSED || kRing * C::STAGE_BYTES >= (int)((2 * kWaves + 1) * kNT + 16) * (int)sizeof(float), "epilogue sums fit the ring");
   static std::atomic<bool> attr_done{false};   // (two threads arriving together both set the attribute: harmless)
   if (!attr_done.load(std::memory_order_acquire)) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&project_mfma_kernel<MT, WM, LEFT, FUSED, SB16>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&project_mfma_kernel<MT, WM, FUSED, SB16>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_done.store(true, std::memory_order_release);
   }
-  const int tiles = (n + kNT - 1) / kNT;
-  const int per_xcd = (count + kXcds - 1) / kXcds;
-  dim3 grid((unsigned)(kXcds * per_xcd * tiles * (sp.r / C::RT)), 1, 1);
-  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, LEFT, FUSED, SB16>), grid, dim3(kThreads), lds_bytes, st, d_descs, sp,
-                     tiles, count, padded ? 1 : 0, r_override);
+  dim3 grid((unsigned)tbl.g[tbl.n - 1].blocks_end, 1, 1);
+  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, FUSED, SB16>), grid, dim3(kThreads), lds_bytes, st, d_descs, sp, tbl, r_override);
   return hipGetLastError();
 }
 
-template <int MT, int WM, bool LEFT>
-hipError_t launch_variant(const TensorDesc* d_descs, int count, int n, bool padded, bool fused, bool state_bf16,
-                          float* r_override, const StepParams& sp, hipStream_t st) {
-  if (!fused) return launch_cfg<MT, WM, LEFT, false, false>(d_descs, count, n, padded, r_override, sp, st);
-  if (state_bf16) return launch_cfg<MT, WM, LEFT, true, true>(d_descs, count, n, padded, nullptr, sp, st);
-  return launch_cfg<MT, WM, LEFT, true, false>(d_descs, count, n, padded, nullptr, sp, st);
-}
-
-template <bool LEFT>
-hipError_t launch_side(const TensorDesc* d_descs, int count, int n, bool padded, bool fused, bool state_bf16,
-                       float* r_override, const StepParams& sp, hipStream_t st) {
-  const int r = sp.r;
-  if (r % 256 == 0) return launch_variant<4, 2, LEFT>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
-  if (r % 128 == 0) return launch_variant<2, 2, LEFT>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
-  if (r % 64 == 0) return launch_variant<1, 2, LEFT>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
-  return launch_variant<1, 1, LEFT>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
+template <int MT, int WM>
+hipError_t launch_variant(const TensorDesc* d_descs, const MfmaGroups& tbl, bool fused, bool state_bf16, float* r_override,
+                          const StepParams& sp, hipStream_t st) {
+  if (!fused) return launch_cfg<MT, WM, false, false>(d_descs, tbl, r_override, sp, st);
+  if (state_bf16) return launch_cfg<MT, WM, true, true>(d_descs, tbl, nullptr, sp, st);
+  return launch_cfg<MT, WM, true, false>(d_descs, tbl, nullptr, sp, st);
 }
 
 }  // namespace
@@ -636,12 +657,38 @@ int project_mfma_row_tiles(int r) { return r % 256 == 0 ? r / 256 : r % 128 == 0
 // Channel tiles per tensor (= block sums left per tensor).
 int project_mfma_tiles(int n) { return (n + kNT - 1) / kNT; }
 
+hipError_t launch_project_mfma_groups(const TensorDesc* d_descs, const MfmaGroupShape* groups, int n_groups, bool fused,
+                                      bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st) {
+  if (n_groups < 1 || fused == (r_override != nullptr) || (r_override && (n_groups != 1 || groups[0].count != 1)))
+    return hipErrorInvalidValue;
+  const int r = sp.r;
+  const int row_tiles = project_mfma_row_tiles(r);
+  for (int g0 = 0; g0 < n_groups; g0 += kMaxGroups) {
+    MfmaGroups tbl{};
+    tbl.n = std::min(kMaxGroups, n_groups - g0);
+    int blocks = 0;
+    for (int i = 0; i < tbl.n; ++i) {
+      const MfmaGroupShape& g = groups[g0 + i];
+      const int n = g.left ? g.cols : g.rows;
+      const int tiles = project_mfma_tiles(n);
+      const int per_xcd = (g.count + kXcds - 1) / kXcds;
+      blocks += kXcds * per_xcd * tiles * row_tiles;
+      tbl.g[i] = MfmaGroup{g.first, g.count, tiles, blocks, g.left ? 1 : 0, g.padded ? 1 : 0};
+    }
+    hipError_t e;
+    if (r % 256 == 0) e = launch_variant<4, 2>(d_descs, tbl, fused, state_bf16, r_override, sp, st);
+    else if (r % 128 == 0) e = launch_variant<2, 2>(d_descs, tbl, fused, state_bf16, r_override, sp, st);
+    else if (r % 64 == 0) e = launch_variant<1, 2>(d_descs, tbl, fused, state_bf16, r_override, sp, st);
+    else e = launch_variant<1, 1>(d_descs, tbl, fused, state_bf16, r_override, sp, st);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool padded,
                                bool fused, bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st) {
-  const int n = left ? cols : rows;
-  if (fused == (r_override != nullptr) || (r_override && count != 1)) return hipErrorInvalidValue;
-  return left ? launch_side<true>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st)
-              : launch_side<false>(d_descs, count, n, padded, fused, state_bf16, r_override, sp, st);
+  const MfmaGroupShape g{0, count, rows, cols, left, padded};
+  return launch_project_mfma_groups(d_descs, &g, 1, fused, state_bf16, r_override, sp, st);
 }
 
 hipError_t launch_channel_factors(const TensorDesc* d_descs, int count, int n, int row_tiles, hipStream_t st) {

@@ -1,6 +1,8 @@
-// Kernels that materialise the random stream: the per-step scratch copy of P for the
-// matrix-core projection, and the debug views used by the bit-exact stream checks.
-// (Algorithm 1: "P_t <- N_seed(0, 1/r)"; P is re-generated every step and is never state.)
+// Kernels that materialise the random stream: the scratch copy of P that the matrix-core and the
+// general projection read (written when the step's refresh interval differs from the one the
+// scratch holds, i.e. once per T steps, and kept in between as Algorithm 1 keeps P_t; never state:
+// a resumed run writes it again from the seed), and the debug views used by the bit-exact stream
+// checks.  (Algorithm 1: "P_t <- N_seed(0, 1/r)".)
 #include "apollo_internal.h"
 
 namespace apollo {

@@ -40,11 +40,11 @@ def test_default_run_prints_one_json_line_with_roofline_and_cpu_baseline():
     assert roof["traffic"] is None or roof["traffic"] > 0
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["sample"]
-    # four variants on the LLaMA-7B shapes, then the LLaMA-1B set and the two LLaMA-13B runs (five timed steps
-    # whatever --steps says, the first of them re-sampling P)
-    assert len(d["also"]) == 7 and all(a["finite"] and a["value"] > 1e10 for a in d["also"])
-    assert [a["benchmark_config"] for a in d["also"]] == [4, 4, 4, 4, 3, 5, 5]
-    for a in d["also"][5:]:
+    # four variants on the LLaMA-7B shapes, then the LLaMA-60M and LLaMA-1B sets and the two LLaMA-13B runs (five
+    # timed steps whatever --steps says, the first of them re-sampling P)
+    assert len(d["also"]) == 8 and all(a["finite"] and a["value"] > 1e10 for a in d["also"])
+    assert [a["benchmark_config"] for a in d["also"]] == [4, 4, 4, 4, 2, 3, 5, 5]
+    for a in d["also"][6:]:
         assert a["first_timed_step"] == 201 and a["phase_ms"]["update"] > 0
-    assert d["also"][6]["phase_ms"]["projection_fill"] > 0          # the re-sampling step is inside the timed region
+    assert d["also"][7]["phase_ms"]["projection_fill"] > 0          # the re-sampling step is inside the timed region
     assert d["adamw_rest"]["value"] > 1e9

@@ -283,3 +283,60 @@ def test_weights_follow_an_independent_oracle_trajectory(name, steps):
     stats = {}
     run_parity(wl, ids, steps, independent_w=True, stats=stats)
     assert 0.0 < stats["used"]["W_final"] <= 1.0
+
+
+def test_non_finite_gradient_keeps_the_stored_norm_and_nan_survives_bf16_storage():
+    """A step whose gradient holds an inf: the stored norm stays what it was (the oracle's reading:
+    a non-finite norm is not remembered), and with bfloat16 weights the poisoned weights read back as
+    NaN -- the rounding to bfloat16 must not turn a NaN into a finite number or a zero."""
+    shapes = [(64, 264), (264, 64)]
+    for rank, mode in ((32, "channel"), (1, "tensor")):
+        wl = WL.Workload("nonfinite", 18, shapes, torch.bfloat16, "normal", 1e-2, rank=rank, mode=mode, refresh_interval=10,
+                         steps=2, lr=1e-2, weight_dtype=torch.bfloat16)
+        cfg, _ = make_configs(wl)
+        weights = WL.make_weights(wl, DEV)
+        grads = WL.make_grads(wl, 1, DEV)
+        st = A.ApolloStepper(cfg, weights, grads, device=DEV)
+        st.step(1, wl.lr)
+        kept = [float(st.debug(i, A.APOLLO_DBG_NORM)[0]) for i in range(2)]
+        assert all(k > 0 and math.isfinite(k) for k in kept)
+        for g in grads:
+            g[3, 5] = float("inf")
+        st.step(2, wl.lr)
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert float(st.debug(i, A.APOLLO_DBG_NORM)[0]) == kept[i]
+            w = weights[i].float()
+            assert bool(torch.isnan(w).any()) and not bool(torch.isinf(w).any())
+        st.close()
+
+
+def test_the_stepper_follows_the_current_stream_at_every_call():
+    """The binding looks torch's current stream up per call: a stepper created on the default stream
+    and stepped inside `with torch.cuda.stream(other)` runs on `other`, ordered after the gradients
+    written there, and gives bit for bit what the same steps give on the default stream."""
+    wl = WL.Workload("streams", 19, [(128, 512), (512, 128), (96, 200)], torch.bfloat16, "normal", 1e-2, rank=32,
+                     refresh_interval=2, steps=4, lr=1e-2)
+    cfg, _ = make_configs(wl)
+    outs = []
+    for use_other in (False, True):
+        weights = WL.make_weights(wl, DEV)
+        grads = [torch.empty(s, dtype=wl.grad_dtype, device=DEV) for s in wl.shapes]
+        st = A.ApolloStepper(cfg, weights, grads, device=DEV)
+        torch.cuda.synchronize()
+        other = torch.cuda.Stream(device=DEV)
+        for t in range(1, wl.steps + 1):
+            if use_other and t % 2 == 0:
+                other.wait_stream(torch.cuda.current_stream(DEV))
+                with torch.cuda.stream(other):
+                    WL.make_grads(wl, t, DEV, out=grads)
+                    st.step(t, wl.lr)                # no synchronisation in between: stream order must do
+                torch.cuda.current_stream(DEV).wait_stream(other)
+            else:
+                WL.make_grads(wl, t, DEV, out=grads)
+                st.step(t, wl.lr)
+        torch.cuda.synchronize()
+        outs.append([w.clone() for w in weights] + [st.state.clone()])
+        st.close()
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)

@@ -635,3 +635,21 @@ def test_first_step_closed_form_equals_the_recurrence_at_t_1(rows, cols, mode, r
         np.testing.assert_allclose(float(cf["norm"]), info["norm"], rtol=1e-12)
         np.testing.assert_allclose(back(cf["dW_grad"]) - lr * cfg.weight_decay * W0, W - W0, rtol=1e-9, atol=1e-18)
     assert np.any(info["s"] == 0.0) or mode == apollo.TENSOR
+
+
+def test_a_non_finite_step_does_not_replace_the_stored_norm():
+    """A gradient with an inf in it makes the step's norm non-finite; the stored norm must survive it
+    (a NaN there would make every later limiter comparison false)."""
+    cfg = _cfg(rank=2, refresh_interval=10)
+    rng = np.random.default_rng(3)
+    G = rng.standard_normal((6, 9)) * 1e-2
+    st = apollo.init_state(cfg, 6, 9)
+    W = np.zeros((6, 9))
+    apollo.step(cfg, st, W, G, 1, 1e-3)
+    kept = st.prev_norm
+    assert kept > 0
+    bad = G.copy()
+    bad[1, 2] = np.inf
+    with np.errstate(all="ignore"):
+        apollo.step(cfg, st, W, bad, 2, 1e-3)
+    assert st.prev_norm == kept
