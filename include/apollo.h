@@ -201,6 +201,24 @@ apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg,
 apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, int32_t n_tensors,
                             int64_t step, float lr, void* hip_stream);
 
+/* The step in two parts, for callers that replay it from a HIP graph (a replayed launch cannot carry
+ * a new step number or learning rate in its kernel arguments):
+ *   apollo_step_prepare  writes the scalars of step `step` (bias corrections, refresh epoch, lr, ...) into
+ *                        the workspace with one small kernel and decides there whether that step has to
+ *                        write the scratch copy of P first (the scratch holds none, or another epoch's);
+ *   apollo_step_launch   enqueues the kernels of one step, which read those scalars from device memory:
+ *                        the same kernels, launch shapes and results as apollo_step (serial schedule).
+ * apollo_step_prepare(h, t, lr, s) followed by apollo_step_launch(h, tensors, n, s) equals apollo_step(h,
+ * tensors, n, t, lr, s) bit for bit.  Capture apollo_step_launch alone (it then only launches kernels:
+ * no copy, no memset, no event), after one ordinary call with the same tensor pointers -- a call whose
+ * pointers differ from the previous call's first copies them to the device, which does not belong into
+ * a graph -- and per iteration call apollo_step_prepare on the stream and launch the graph after it.
+ * The weights, gradients, state and workspace must be the buffers the graph was captured with.  The kernel
+ * that writes P is part of every replay and returns at once when the scratch is current. */
+apollo_status_t apollo_step_prepare(apollo_handle_t* h, int64_t step, float lr, void* hip_stream);
+apollo_status_t apollo_step_launch(apollo_handle_t* h, const apollo_tensor_t* tensors, int32_t n_tensors,
+                                   void* hip_stream);
+
 /* For callers that cannot allocate device memory or call anything that does (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): one step of Algorithm 1 on a short
  * tensor list, the same kernels and results as apollo_init(..., zero_state, ...) followed by

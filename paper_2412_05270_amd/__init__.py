@@ -18,6 +18,6 @@ from .binding import (  # noqa: F401
     apollo_adamw_state_offsets, apollo_adamw_step, apollo_adamw_workspace_bytes, apollo_debug_copy,
     apollo_debug_fill_projection, apollo_debug_gauss_parts, apollo_debug_get, apollo_debug_path,
     apollo_debug_philox, apollo_destroy, apollo_init, apollo_last_error, apollo_profile_enable,
-    apollo_profile_read, apollo_state_bytes, apollo_state_offsets, apollo_step, apollo_step_noalloc,
+    apollo_profile_read, apollo_state_bytes, apollo_state_offsets, apollo_step, apollo_step_launch, apollo_step_noalloc, apollo_step_prepare,
     apollo_workspace_bytes, APOLLO_NOALLOC_MAX_TENSORS, APOLLO_NOALLOC_SCRATCH_BYTES,
     library_path, load_library)

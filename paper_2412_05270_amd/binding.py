@@ -83,6 +83,10 @@ def load_library():
     lib.apollo_init.argtypes = [C.POINTER(vp), cfgp, shp, i32, vp, sz, vp, sz, i32, vp]
     lib.apollo_step.restype = i32
     lib.apollo_step.argtypes = [vp, C.POINTER(ApolloTensor), i32, i64, f32, vp]
+    lib.apollo_step_prepare.restype = i32
+    lib.apollo_step_prepare.argtypes = [vp, i64, f32, vp]
+    lib.apollo_step_launch.restype = i32
+    lib.apollo_step_launch.argtypes = [vp, C.POINTER(ApolloTensor), i32, vp]
     lib.apollo_step_noalloc.restype = i32
     lib.apollo_step_noalloc.argtypes = [cfgp, shp, C.POINTER(ApolloTensor), i32, vp, sz, i32, i64, f32, vp]
     lib.apollo_debug_fill_projection.restype = i32
@@ -173,6 +177,16 @@ def apollo_step(handle, tensors, step, lr, stream=None, n_tensors=None):
         tensors = arr
     n = n_tensors if n_tensors is not None else (len(tensors) if tensors is not None else 0)
     return load_library().apollo_step(handle, tensors, n, step, lr, stream)
+
+
+def apollo_step_prepare(handle, step, lr, stream=None):
+    return load_library().apollo_step_prepare(handle, step, lr, stream)
+
+
+def apollo_step_launch(handle, tensors, stream=None, n_tensors=None):
+    """tensors: a ctypes array of ApolloTensor."""
+    n = n_tensors if n_tensors is not None else (len(tensors) if tensors is not None else 0)
+    return load_library().apollo_step_launch(handle, tensors, n, stream)
 
 
 APOLLO_NOALLOC_SCRATCH_BYTES = 32 * 1024 * 1024
@@ -401,6 +415,18 @@ class ApolloStepper:
 
     def step(self, step, lr):
         rc = apollo_step(self.handle, self._tensors, step, lr, self._stream())
+        if rc != APOLLO_OK:
+            raise ApolloError(rc, apollo_last_error(self.handle))
+
+    def prepare(self, step, lr):
+        """The scalars of one step into device memory (for a step replayed from a graph)."""
+        rc = apollo_step_prepare(self.handle, step, lr, self._stream())
+        if rc != APOLLO_OK:
+            raise ApolloError(rc, apollo_last_error(self.handle))
+
+    def launch(self):
+        """The kernels of one step, reading what prepare() left: this is the call to capture."""
+        rc = apollo_step_launch(self.handle, self._tensors, self._stream())
         if rc != APOLLO_OK:
             raise ApolloError(rc, apollo_last_error(self.handle))
 

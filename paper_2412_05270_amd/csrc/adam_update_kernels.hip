@@ -1,6 +1,7 @@
 // Low-rank Adam moments + scaling factors (Algorithm 1, steps 2-3; Section 4.1, Eq. 4; Section
 // 4.2), the per-tensor norm-growth limiter (Section 3.2, Eq. 3) and the scaled weight update
 // (Algorithm 1, step 4).
+#include <algorithm>
 #include <type_traits>
 
 #include "apollo_internal.h"
@@ -28,7 +29,8 @@ constexpr int kLanes = 256 / kRG;
 // UA (with VEC = 4): n is not a multiple of 4, so a row of R, M^R, V^R starts at any element: the
 // quads are accessed with element alignment only, and the last thread of a row holds 1..3 channels.
 template <int VEC, bool SB16, int RSRC, bool UA = false>
-__global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
+__global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg, StepState* __restrict__ ss) {
+  const StepParams sp = step_params(sp_arg, ss);
   static_assert(!UA || VEC == 4, "element-aligned quads");
   typedef float vec_t __attribute__((ext_vector_type(VEC)));
   __shared__ float red_a[kRG > 1 ? kRG - 1 : 1][kLanes * VEC], red_b[kRG > 1 ? kRG - 1 : 1][kLanes * VEC];
@@ -165,22 +167,22 @@ __global__ __launch_bounds__(256) void adam_norms_kernel(const TensorDesc* __res
 int adam_norms_blocks(int n) { return ((n + 3) / 4 + kLanes - 1) / kLanes; }
 
 template <int RSRC>
-static hipError_t launch_adam_norms_t(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
+static hipError_t launch_adam_norms_t(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepArgs& sa,
                                       hipStream_t st) {
   dim3 grid((unsigned)adam_norms_blocks(n), (unsigned)count, 1);
   if ((n & 3) == 0) {
-    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
-    else hipLaunchKernelGGL((adam_norms_kernel<4, false, RSRC>), grid, dim3(256), 0, st, d_descs, sp);
+    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true, RSRC>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
+    else hipLaunchKernelGGL((adam_norms_kernel<4, false, RSRC>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
   } else {
-    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true, RSRC, true>), grid, dim3(256), 0, st, d_descs, sp);
-    else hipLaunchKernelGGL((adam_norms_kernel<4, false, RSRC, true>), grid, dim3(256), 0, st, d_descs, sp);
+    if (state_bf16) hipLaunchKernelGGL((adam_norms_kernel<4, true, RSRC, true>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
+    else hipLaunchKernelGGL((adam_norms_kernel<4, false, RSRC, true>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
+hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepArgs& sa,
                              hipStream_t st) {
-  return launch_adam_norms_t<0>(d_descs, count, n, state_bf16, sp, st);
+  return launch_adam_norms_t<0>(d_descs, count, n, state_bf16, sa, st);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -190,7 +192,8 @@ hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool s
 // order).  One block = four channels; it leaves the same four partial sums as adam_norms_kernel.
 // ---------------------------------------------------------------------------------------------
 template <bool GB16, bool SB16>
-__global__ __launch_bounds__(256) void adam_identity_rows_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
+__global__ __launch_bounds__(256) void adam_identity_rows_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg, StepState* __restrict__ ss) {
+  const StepParams sp = step_params(sp_arg, ss);
   __shared__ float blk[4][4];
   const TensorView d(descs[blockIdx.y]);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -267,17 +270,17 @@ __global__ __launch_bounds__(256) void adam_identity_rows_kernel(const TensorDes
 }
 
 hipError_t launch_adam_identity(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool g_bf16,
-                                bool state_bf16, const StepParams& sp, hipStream_t st) {
+                                bool state_bf16, const StepArgs& sa, hipStream_t st) {
   if (left)
-    return g_bf16 ? launch_adam_norms_t<2>(d_descs, count, cols, state_bf16, sp, st)
-                  : launch_adam_norms_t<1>(d_descs, count, cols, state_bf16, sp, st);
+    return g_bf16 ? launch_adam_norms_t<2>(d_descs, count, cols, state_bf16, sa, st)
+                  : launch_adam_norms_t<1>(d_descs, count, cols, state_bf16, sa, st);
   dim3 grid((unsigned)((rows + 3) / 4), (unsigned)count, 1);
   if (g_bf16) {
-    if (state_bf16) hipLaunchKernelGGL((adam_identity_rows_kernel<true, true>), grid, dim3(256), 0, st, d_descs, sp);
-    else hipLaunchKernelGGL((adam_identity_rows_kernel<true, false>), grid, dim3(256), 0, st, d_descs, sp);
+    if (state_bf16) hipLaunchKernelGGL((adam_identity_rows_kernel<true, true>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
+    else hipLaunchKernelGGL((adam_identity_rows_kernel<true, false>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
   } else {
-    if (state_bf16) hipLaunchKernelGGL((adam_identity_rows_kernel<false, true>), grid, dim3(256), 0, st, d_descs, sp);
-    else hipLaunchKernelGGL((adam_identity_rows_kernel<false, false>), grid, dim3(256), 0, st, d_descs, sp);
+    if (state_bf16) hipLaunchKernelGGL((adam_identity_rows_kernel<false, true>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
+    else hipLaunchKernelGGL((adam_identity_rows_kernel<false, false>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
   }
   return hipGetLastError();
 }
@@ -288,7 +291,8 @@ hipError_t launch_adam_identity(const TensorDesc* d_descs, int count, int rows, 
 // rescaled to norm gamma N_prev, which is also what is remembered (unless it is not finite).  One
 // wave per tensor.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void finalize_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
+__global__ __launch_bounds__(64) void finalize_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg, StepState* __restrict__ ss) {
+  const StepParams sp = step_params(sp_arg, ss);
   const TensorView d(descs[blockIdx.x]);
   const int lane = threadIdx.x;
   float t[4] = {0.f, 0.f, 0.f, 0.f};
@@ -326,11 +330,15 @@ __global__ __launch_bounds__(64) void finalize_kernel(const TensorDesc* __restri
     d.scal[1] = c;
     d.scal[2] = norm;
     d.scal[3] = s_tensor;
+    if (ss && blockIdx.x == 0) {        // this step's projection has run: the scratch holds this epoch's P
+      ss->p_epoch = sp.epoch;
+      ss->p_valid = 1;
+    }
   }
 }
 
-hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepParams& sp, hipStream_t st) {
-  hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)count), dim3(64), 0, st, d_descs, sp);
+hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepArgs& sa, hipStream_t st) {
+  hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)count), dim3(64), 0, st, d_descs, sa.host, sa.dev);
   return hipGetLastError();
 }
 
@@ -424,12 +432,11 @@ __device__ __forceinline__ void store_elems(APOLLO_GLOBAL void* base, size_t e0,
 // is still 16 bytes per lane).  ALIGNED: cols % EPT == 0, so a group never straddles a row and the
 // tensor has no ragged tail.
 template <bool BF16, int CHAN, bool ALIGNED, bool WB16, int EPT>
-__global__ __launch_bounds__(256) void update_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
-                                                     FastDiv div_cols) {
-  const TensorView d(descs[blockIdx.y]);
+__device__ __forceinline__ void update_body(const TensorDesc& desc, const StepParams& sp, const FastDiv& div_cols, uint32_t block) {
+  const TensorView d(desc);
   const uint32_t cols = (uint32_t)d.cols;
   const size_t total = (size_t)d.rows * (size_t)d.cols;
-  const size_t e0 = ((size_t)blockIdx.x * 256u + threadIdx.x) * (size_t)EPT;
+  const size_t e0 = ((size_t)block * 256u + threadIdx.x) * (size_t)EPT;
   if (e0 >= total) return;
   const float coef = d.scal[0];
   const float decay = sp.lr_decay;
@@ -482,44 +489,131 @@ __global__ __launch_bounds__(256) void update_kernel(const TensorDesc* __restric
   }
 }
 
+template <bool BF16, int CHAN, bool ALIGNED, bool WB16, int EPT>
+__global__ __launch_bounds__(256) void update_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg, StepState* __restrict__ ss,
+                                                     FastDiv div_cols) {
+  const StepParams sp = step_params(sp_arg, ss);
+  update_body<BF16, CHAN, ALIGNED, WB16, EPT>(descs[blockIdx.y], sp, div_cols, blockIdx.x);
+}
+
+// The same update for several shape groups in one launch (a small parameter set is bound by launch
+// latency and by launches that do not fill the chip): the blocks of the groups follow each other in a
+// one-dimensional grid, a block finds its group in the table, its tensor and its place in it.
+constexpr int kMaxUpdateGroups = 8;
+struct UpdateGroup {
+  int first, count;               // descriptors descs[first .. first + count)
+  uint32_t blocks_per_tensor;
+  uint32_t blocks_end;            // one past the group's last block
+  int chan, aligned;              // kChan*, cols % EPT == 0
+  FastDiv div_cols;
+};
+struct UpdateGroups {
+  UpdateGroup g[kMaxUpdateGroups];
+  int n;
+};
+
+template <bool BF16, bool WB16, int EPT>
+__global__ __launch_bounds__(256) void update_groups_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg,
+                                                            StepState* __restrict__ ss, UpdateGroups tbl) {
+  const StepParams sp = step_params(sp_arg, ss);
+  const uint32_t b = blockIdx.x;
+  UpdateGroup g = tbl.g[0];
+  uint32_t begin = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxUpdateGroups; ++i)
+    if (i < tbl.n && b >= tbl.g[i - 1].blocks_end) {
+      g = tbl.g[i];
+      begin = tbl.g[i - 1].blocks_end;
+    }
+  const uint32_t local = b - begin;
+  const uint32_t tensor = local / g.blocks_per_tensor, block = local - tensor * g.blocks_per_tensor;
+  const TensorDesc& d = descs[g.first + tensor];
+#define APOLLO_UPDATE_CASE(C, A) update_body<BF16, C, A, WB16, EPT>(d, sp, g.div_cols, block)
+  if (g.chan == kChanCol) { if (g.aligned) APOLLO_UPDATE_CASE(kChanCol, true); else APOLLO_UPDATE_CASE(kChanCol, false); }
+  else if (g.chan == kChanRow) { if (g.aligned) APOLLO_UPDATE_CASE(kChanRow, true); else APOLLO_UPDATE_CASE(kChanRow, false); }
+  else { if (g.aligned) APOLLO_UPDATE_CASE(kChanNone, true); else APOLLO_UPDATE_CASE(kChanNone, false); }
+#undef APOLLO_UPDATE_CASE
+}
+
+template <bool BF16, bool WB16>
+static hipError_t launch_update_groups_t(const TensorDesc* d_descs, const UpdateGroupShape* groups, int n_groups,
+                                         const StepArgs& sa, hipStream_t st) {
+  // one element count per thread for the whole launch: 8 only if every group allows it
+  int ept = (BF16 && WB16) ? 8 : 4;
+  for (int i = 0; i < n_groups; ++i)
+    if ((groups[i].cols & 7) != 0) ept = 4;
+  for (int g0 = 0; g0 < n_groups; g0 += kMaxUpdateGroups) {
+    UpdateGroups tbl{};
+    tbl.n = std::min(kMaxUpdateGroups, n_groups - g0);
+    uint64_t blocks = 0;
+    for (int i = 0; i < tbl.n; ++i) {
+      const UpdateGroupShape& g = groups[g0 + i];
+      const size_t total = (size_t)g.rows * g.cols;
+      const uint32_t bpt = (uint32_t)(((total + ept - 1) / ept + 255) / 256);
+      blocks += (uint64_t)bpt * g.count;
+      if (blocks >= (1ull << 31)) return hipErrorInvalidValue;
+      tbl.g[i] = UpdateGroup{g.first, g.count, bpt, (uint32_t)blocks,
+                             sa.host.tensor_mode ? kChanNone : (g.left ? kChanCol : kChanRow), (g.cols % ept) == 0 ? 1 : 0,
+                             make_fastdiv((uint32_t)g.cols)};
+    }
+    if (ept == 8) {
+      if constexpr (BF16 && WB16)
+        hipLaunchKernelGGL((update_groups_kernel<BF16, WB16, 8>), dim3((unsigned)blocks), dim3(256), 0, st, d_descs, sa.host, sa.dev, tbl);
+    } else {
+      hipLaunchKernelGGL((update_groups_kernel<BF16, WB16, 4>), dim3((unsigned)blocks), dim3(256), 0, st, d_descs, sa.host, sa.dev, tbl);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_update_groups(const TensorDesc* d_descs, const UpdateGroupShape* groups, int n_groups, bool bf16, bool w_bf16,
+                                const StepArgs& sa, hipStream_t st) {
+  if (bf16) return w_bf16 ? launch_update_groups_t<true, true>(d_descs, groups, n_groups, sa, st)
+                          : launch_update_groups_t<true, false>(d_descs, groups, n_groups, sa, st);
+  return w_bf16 ? launch_update_groups_t<false, true>(d_descs, groups, n_groups, sa, st)
+                : launch_update_groups_t<false, false>(d_descs, groups, n_groups, sa, st);
+}
+
 template <bool BF16, int CHAN, bool WB16>
-static hipError_t launch_update_t(const TensorDesc* d_descs, int count, int rows, int cols, const StepParams& sp,
+static hipError_t launch_update_t(const TensorDesc* d_descs, int count, int rows, int cols, const StepArgs& sa,
                                   hipStream_t st) {
   const FastDiv fd = make_fastdiv((uint32_t)cols);
   const size_t total = (size_t)rows * cols;
   if constexpr (BF16 && WB16) {
     if ((cols & 7) == 0) {
       dim3 grid((unsigned)((total / 8 + 255) / 256), (unsigned)count, 1);
-      hipLaunchKernelGGL((update_kernel<BF16, CHAN, true, WB16, 8>), grid, dim3(256), 0, st, d_descs, sp, fd);
+      hipLaunchKernelGGL((update_kernel<BF16, CHAN, true, WB16, 8>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, fd);
       return hipGetLastError();
     }
   }
   const size_t quads = (total + 3) / 4;
   dim3 grid((unsigned)((quads + 255) / 256), (unsigned)count, 1);
   if ((cols & 3) == 0)
-    hipLaunchKernelGGL((update_kernel<BF16, CHAN, true, WB16, 4>), grid, dim3(256), 0, st, d_descs, sp, fd);
+    hipLaunchKernelGGL((update_kernel<BF16, CHAN, true, WB16, 4>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, fd);
   else
-    hipLaunchKernelGGL((update_kernel<BF16, CHAN, false, WB16, 4>), grid, dim3(256), 0, st, d_descs, sp, fd);
+    hipLaunchKernelGGL((update_kernel<BF16, CHAN, false, WB16, 4>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, fd);
   return hipGetLastError();
 }
 
 template <bool BF16, bool WB16>
 static hipError_t launch_update_c(const TensorDesc* d_descs, int count, int rows, int cols, int chan,
-                                  const StepParams& sp, hipStream_t st) {
-  if (chan == kChanCol) return launch_update_t<BF16, kChanCol, WB16>(d_descs, count, rows, cols, sp, st);
-  if (chan == kChanRow) return launch_update_t<BF16, kChanRow, WB16>(d_descs, count, rows, cols, sp, st);
-  return launch_update_t<BF16, kChanNone, WB16>(d_descs, count, rows, cols, sp, st);
+                                  const StepArgs& sa, hipStream_t st) {
+  if (chan == kChanCol) return launch_update_t<BF16, kChanCol, WB16>(d_descs, count, rows, cols, sa, st);
+  if (chan == kChanRow) return launch_update_t<BF16, kChanRow, WB16>(d_descs, count, rows, cols, sa, st);
+  return launch_update_t<BF16, kChanNone, WB16>(d_descs, count, rows, cols, sa, st);
 }
 
 hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
-                         bool w_bf16, const StepParams& sp, hipStream_t st) {
-  const int chan = sp.tensor_mode ? kChanNone : (left ? kChanCol : kChanRow);
+                         bool w_bf16, const StepArgs& sa, hipStream_t st) {
+  const int chan = sa.host.tensor_mode ? kChanNone : (left ? kChanCol : kChanRow);
   if (bf16) {
-    return w_bf16 ? launch_update_c<true, true>(d_descs, count, rows, cols, chan, sp, st)
-                  : launch_update_c<true, false>(d_descs, count, rows, cols, chan, sp, st);
+    return w_bf16 ? launch_update_c<true, true>(d_descs, count, rows, cols, chan, sa, st)
+                  : launch_update_c<true, false>(d_descs, count, rows, cols, chan, sa, st);
   }
-  return w_bf16 ? launch_update_c<false, true>(d_descs, count, rows, cols, chan, sp, st)
-                : launch_update_c<false, false>(d_descs, count, rows, cols, chan, sp, st);
+  return w_bf16 ? launch_update_c<false, true>(d_descs, count, rows, cols, chan, sa, st)
+                : launch_update_c<false, false>(d_descs, count, rows, cols, chan, sa, st);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -551,8 +645,9 @@ __device__ __forceinline__ float row16_reduce(float v) {
 }
 
 template <bool BF16, int CHAN>
-__global__ __launch_bounds__(256) void update_q8_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
+__global__ __launch_bounds__(256) void update_q8_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg, StepState* __restrict__ ss,
                                                         FastDiv div_cols) {
+  const StepParams sp = step_params(sp_arg, ss);
   const TensorView d(descs[blockIdx.y]);
   const uint32_t cols = (uint32_t)d.cols;
   const size_t total = (size_t)d.rows * (size_t)d.cols;
@@ -631,22 +726,22 @@ __global__ __launch_bounds__(256) void update_q8_kernel(const TensorDesc* __rest
 
 template <bool BF16>
 static hipError_t launch_update_q8_t(const TensorDesc* d_descs, int count, int rows, int cols, int chan,
-                                     const StepParams& sp, hipStream_t st) {
+                                     const StepArgs& sa, hipStream_t st) {
   const FastDiv fd = make_fastdiv((uint32_t)cols);
   const size_t octs = (size_t)rows * cols / 8;
   dim3 grid((unsigned)((octs + 255) / 256), (unsigned)count, 1);
-  if (chan == kChanCol) hipLaunchKernelGGL((update_q8_kernel<BF16, kChanCol>), grid, dim3(256), 0, st, d_descs, sp, fd);
-  else if (chan == kChanRow) hipLaunchKernelGGL((update_q8_kernel<BF16, kChanRow>), grid, dim3(256), 0, st, d_descs, sp, fd);
-  else hipLaunchKernelGGL((update_q8_kernel<BF16, kChanNone>), grid, dim3(256), 0, st, d_descs, sp, fd);
+  if (chan == kChanCol) hipLaunchKernelGGL((update_q8_kernel<BF16, kChanCol>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, fd);
+  else if (chan == kChanRow) hipLaunchKernelGGL((update_q8_kernel<BF16, kChanRow>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, fd);
+  else hipLaunchKernelGGL((update_q8_kernel<BF16, kChanNone>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, fd);
   return hipGetLastError();
 }
 
 // cols must be a multiple of 128 (checked when the handle is created).
 hipError_t launch_update_q8(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
-                            const StepParams& sp, hipStream_t st) {
-  const int chan = sp.tensor_mode ? kChanNone : (left ? kChanCol : kChanRow);
-  return bf16 ? launch_update_q8_t<true>(d_descs, count, rows, cols, chan, sp, st)
-              : launch_update_q8_t<false>(d_descs, count, rows, cols, chan, sp, st);
+                            const StepArgs& sa, hipStream_t st) {
+  const int chan = sa.host.tensor_mode ? kChanNone : (left ? kChanCol : kChanRow);
+  return bf16 ? launch_update_q8_t<true>(d_descs, count, rows, cols, chan, sa, st)
+              : launch_update_q8_t<false>(d_descs, count, rows, cols, chan, sa, st);
 }
 
 }  // namespace apollo

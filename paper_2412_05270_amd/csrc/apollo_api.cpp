@@ -20,6 +20,7 @@ constexpr size_t kAlign = 256;
 constexpr int64_t kMaxDim = 1 << 20;       // rows / cols limit (grid dimensions, int indexing)
 constexpr int32_t kMaxTensors = 65535;     // gridDim.z
 constexpr int kRingSlots = 4;
+constexpr size_t kMergedUpdateMaxParams = 64u << 20;   // below this many parameters the update of all groups is one launch
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -57,6 +58,7 @@ struct Plan {
   std::vector<TensorPlan> t;
   std::vector<Group> groups;
   size_t state_bytes = 0, workspace_bytes = 0, desc_bytes = 0;
+  size_t ws_step = 0;            // offset of the StepState (device copy of a step's scalars) in the workspace
 };
 
 int fail(std::string& dst, int code, const char* fmt, long long a = 0, long long b = 0, long long c = 0) {
@@ -175,6 +177,8 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
   size_t ws = 0;
   plan.desc_bytes = (size_t)n * sizeof(TensorDesc);
   ws = align_up(plan.desc_bytes);
+  plan.ws_step = ws;
+  ws = align_up(ws + sizeof(StepState));
   for (int32_t k = 0; k < n; ++k) {
     TensorPlan& t = plan.t[k];
     t.ws_p = ws;
@@ -282,15 +286,15 @@ int upload_descs(apollo_handle* h, hipStream_t st) {
 struct GroupLaunches {
   const apollo_config_t& cfg;
   const TensorDesc* dd;        // DEVICE descriptor table
-  const StepParams& sp;
-  bool regenerate;             // write the scratch copy of P before projecting
+  StepArgs sa;                 // the step's scalars: by value, or in device memory (replayable step)
+  bool regenerate;             // launch the kernel that writes the scratch copy of P before projecting
   const char* what;
 
   // the transient copy of P (and of a gradient whose rows need padding) for the groups that read it from scratch
   hipError_t fill(const Group& g, hipStream_t s) {
     if (g.path == Path::kRank1 || g.path == Path::kIdentity) return hipSuccess;
     what = "projection fill";
-    hipError_t r = regenerate ? launch_fill_projection(dd + g.first, g.count, sp.r, g.m8, g.bf16, sp, s) : hipSuccess;
+    hipError_t r = regenerate ? launch_fill_projection(dd + g.first, g.count, sa.host.r, g.m8, g.bf16, sa, s) : hipSuccess;
     if (r == hipSuccess && g.pad_g) {
       what = "gradient padding";
       r = launch_pad_gradient(dd + g.first, g.count, g.rows, g.cols, g.ldg, s);
@@ -302,11 +306,11 @@ struct GroupLaunches {
     what = "projection";
     if (g.path == Path::kIdentity) return hipSuccess;
     if (g.path == Path::kRank1)
-      return launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sp, s);
+      return launch_project_rank1(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, g.n_slabs, sa, s);
     if (g.path == Path::kMfma)     // (fused: Algorithm 1's steps 1-3 in one kernel, see moments())
       return launch_project_mfma(dd + g.first, g.count, g.rows, g.cols, g.left, g.pad_g, g.fused,
-                                 cfg.state_dtype == APOLLO_BF16, nullptr, sp, s);
-    return launch_project_generic(dd + g.first, g.count, g.n, g.bf16, sp, s);
+                                 cfg.state_dtype == APOLLO_BF16, nullptr, sa, s);
+    return launch_project_generic(dd + g.first, g.count, g.n, g.bf16, sa, s);
   }
   // low-rank Adam moments, channel factors, block partial sums
   hipError_t moments(const Group& g, hipStream_t s) {
@@ -315,14 +319,14 @@ struct GroupLaunches {
       return g.row_tiles > 1 ? launch_channel_factors(dd + g.first, g.count, g.n, g.row_tiles, s) : hipSuccess;
     const bool state_bf16 = cfg.state_dtype == APOLLO_BF16;
     if (g.path == Path::kIdentity)
-      return launch_adam_identity(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, state_bf16, sp, s);
-    return launch_adam_norms(dd + g.first, g.count, g.n, state_bf16, sp, s);
+      return launch_adam_identity(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, state_bf16, sa, s);
+    return launch_adam_norms(dd + g.first, g.count, g.n, state_bf16, sa, s);
   }
   hipError_t update(const Group& g, hipStream_t s) {
     what = "weight update";
     if (cfg.weight_dtype == APOLLO_Q8)
-      return launch_update_q8(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, sp, s);
-    return launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, cfg.weight_dtype == APOLLO_BF16, sp, s);
+      return launch_update_q8(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, sa, s);
+    return launch_update(dd + g.first, g.count, g.rows, g.cols, g.left, g.bf16, cfg.weight_dtype == APOLLO_BF16, sa, s);
   }
 };
 
@@ -365,7 +369,7 @@ hipError_t run_serial(GroupLaunches& L, const Plan& plan, hipStream_t st, hipEve
   if (e == hipSuccess && !mfma.empty()) {
     L.what = "projection";
     e = launch_project_mfma_groups(L.dd, mfma.data(), (int)mfma.size(), true, L.cfg.state_dtype == APOLLO_BF16, nullptr,
-                                   L.sp, st);
+                                   L.sa, st);
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[2], st);
   for (const Group& g : plan.groups) {
@@ -376,12 +380,28 @@ hipError_t run_serial(GroupLaunches& L, const Plan& plan, hipStream_t st, hipEve
   // per-tensor factor, norm and limiter, all tensors in one launch
   if (e == hipSuccess) {
     L.what = "limiter";
-    e = launch_finalize(L.dd, (int)plan.t.size(), L.sp, st);
+    e = launch_finalize(L.dd, (int)plan.t.size(), L.sa, st);
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[4], st);
-  for (const Group& g : plan.groups) {
-    if (e != hipSuccess) break;
-    e = L.update(g, st);
+  // A small set (bound by launch latency, and its per-group launches do not fill the chip) updates all
+  // groups of one gradient type in one launch; a large one group by group (the same arithmetic either way).
+  size_t params = 0;
+  for (const TensorPlan& t : plan.t) params += (size_t)t.rows * t.cols;
+  const bool merged = params < kMergedUpdateMaxParams && L.cfg.weight_dtype != APOLLO_Q8 && plan.groups.size() > 1;
+  if (merged) {
+    for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {       // bf16 gradients, then fp32 gradients
+      std::vector<UpdateGroupShape> ug;
+      for (const Group& g : plan.groups)
+        if (g.bf16 == (pass == 0)) ug.push_back(UpdateGroupShape{g.first, g.count, g.rows, g.cols, g.left});
+      if (ug.empty()) continue;
+      L.what = "weight update";
+      e = launch_update_groups(L.dd, ug.data(), (int)ug.size(), pass == 0, L.cfg.weight_dtype == APOLLO_BF16, L.sa, st);
+    }
+  } else {
+    for (const Group& g : plan.groups) {
+      if (e != hipSuccess) break;
+      e = L.update(g, st);
+    }
   }
   if (pev && e == hipSuccess) e = hipEventRecord(pev[5], st);
   return e;
@@ -468,6 +488,9 @@ apollo_status_t apollo_init(apollo_handle_t** out, const apollo_config_t* cfg, c
       e = hipEventCreateWithFlags(&h->ev_proj[i], hipEventDisableTiming);
   }
   if (e == hipSuccess && zero_state) e = launch_fill_zero(h->state, h->plan.state_bytes, st);
+  // the device copy of the step scalars starts with "the scratch holds no P"
+  if (e == hipSuccess)
+    e = launch_set_step(reinterpret_cast<StepState*>(h->ws + h->plan.ws_step), make_step_params(*cfg, 1, 0.f), false, true, st);
   if (e != hipSuccess) {
     hip_fail(g_last_error, e, "apollo_init");
     apollo_destroy(h);
@@ -529,8 +552,14 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   const int64_t epoch = (step - 1) / (int64_t)h->cfg.refresh_interval;
   const bool regenerate = epoch != h->p_epoch || st != h->p_stream;
   h->p_epoch = -1;                      // until this step is enqueued completely
-  GroupLaunches L{h->cfg, dd, sp, regenerate, ""};
+  GroupLaunches L{h->cfg, dd, StepArgs{sp, nullptr}, regenerate, ""};
   const char*& what = L.what;
+  if (regenerate && e == hipSuccess) {
+    // the ordinary step keeps its books on the host; the device-side books of the replayable step
+    // (apollo_step_launch) must not believe in a P that this step is about to replace
+    what = "step state";
+    e = launch_set_step(reinterpret_cast<StepState*>(h->ws + h->plan.ws_step), sp, false, true, st);
+  }
   auto fill = [&](const Group& g, hipStream_t s) { return L.fill(g, s); };
   auto project = [&](const Group& g, hipStream_t s) { return L.project(g, s); };
   auto moments = [&](const Group& g, hipStream_t s) { return L.moments(g, s); };
@@ -559,7 +588,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
       if (e == hipSuccess) e = moments(g, s);
       if (e == hipSuccess) {
         what = "limiter";
-        e = launch_finalize(dd + g.first, g.count, sp, s);
+        e = launch_finalize(dd + g.first, g.count, L.sa, s);
       }
       if (e == hipSuccess) e = update(g, s);
     }
@@ -580,6 +609,55 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   if (e != hipSuccess) return hip_fail(h->err, e, what);
   h->p_epoch = epoch;
   h->p_stream = st;
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_step_prepare(apollo_handle_t* h, int64_t step, float lr, void* hip_stream) {
+  if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
+  if (step < 1) return fail(h->err, APOLLO_EINVAL, "step %lld < 1 (steps are 1-based)", step);
+  if (!std::isfinite(lr)) return fail(h->err, APOLLO_EINVAL, "learning rate is not finite");
+  const hipError_t e = launch_set_step(reinterpret_cast<StepState*>(h->ws + h->plan.ws_step), make_step_params(h->cfg, step, lr),
+                                       false, false, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(h->err, e, "step state");
+  return APOLLO_OK;
+}
+
+apollo_status_t apollo_step_launch(apollo_handle_t* h, const apollo_tensor_t* tensors, int32_t n_tensors, void* hip_stream) {
+  if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
+  const int32_t n = (int32_t)h->plan.t.size();
+  if (!tensors) return fail(h->err, APOLLO_EINVAL, "null tensor list");
+  if (n_tensors != n) return fail(h->err, APOLLO_EINVAL, "n_tensors %lld differs from the %lld given to apollo_init", n_tensors, n);
+  bool changed = !h->have_ptrs;
+  for (int32_t k = 0; k < n; ++k) {
+    if (!tensors[k].w || !tensors[k].g) return fail(h->err, APOLLO_EINVAL, "tensor %lld: null w or g", k);
+    if (((uintptr_t)tensors[k].w | (uintptr_t)tensors[k].g) & 15u)
+      return fail(h->err, APOLLO_EINVAL, "tensor %lld: w / g not 16-byte aligned", k);
+    if (h->cfg.weight_dtype == APOLLO_Q8 && (!tensors[k].w_meta || ((uintptr_t)tensors[k].w_meta & 7u)))
+      return fail(h->err, APOLLO_EINVAL, "tensor %lld: w_meta null or not 8-byte aligned", k);
+    if (tensors[k].w != h->last[k].w || tensors[k].g != h->last[k].g || tensors[k].w_meta != h->last[k].w_meta) changed = true;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (changed) {       // (a copy request: not what a stream under capture should see -- see the header)
+    for (int32_t k = 0; k < n; ++k) {
+      TensorDesc& d = h->desc[h->plan.t[k].desc_index];
+      d.w = tensors[k].w;
+      d.w_meta = static_cast<float*>(tensors[k].w_meta);
+      d.g = tensors[k].g;
+      h->last[k] = tensors[k];
+    }
+    const int rc = upload_descs(h, st);
+    if (rc != APOLLO_OK) return rc;
+    h->have_ptrs = true;
+  }
+  // The kernels read the step's scalars from device memory; what the host passes by value only shapes
+  // the launches (rank, mode).  The kernel that writes P is always launched and decides on the device
+  // (it returns at once unless apollo_step_prepare found the scratch to hold another epoch's P).
+  h->p_epoch = -1;     // the host no longer knows which P the scratch holds: the next apollo_step writes it again
+  const TensorDesc* dd = reinterpret_cast<const TensorDesc*>(h->ws);
+  GroupLaunches L{h->cfg, dd, StepArgs{make_step_params(h->cfg, 1, 0.f), reinterpret_cast<StepState*>(h->ws + h->plan.ws_step)},
+                  true, ""};
+  const hipError_t e = run_serial(L, h->plan, st, nullptr);
+  if (e != hipSuccess) return hip_fail(h->err, e, L.what);
   return APOLLO_OK;
 }
 
@@ -667,7 +745,7 @@ apollo_status_t apollo_debug_get(apollo_handle_t* h, int32_t tensor, int32_t wha
         if (!h->have_ptrs || h->p_epoch < 0) return fail(h->err, APOLLO_EINVAL, "no step has run on this handle yet");
         StepParams sp = make_step_params(h->cfg, h->p_epoch * (int64_t)h->cfg.refresh_interval + 1, 0.f);
         const hipError_t e = launch_project_mfma(reinterpret_cast<const TensorDesc*>(h->ws) + t.desc_index, 1, t.rows, t.cols,
-                                                 t.left, t.pad_g, false, false, static_cast<float*>(out), sp,
+                                                 t.left, t.pad_g, false, false, static_cast<float*>(out), StepArgs{sp, nullptr},
                                                  static_cast<hipStream_t>(hip_stream));
         if (e != hipSuccess) return hip_fail(h->err, e, "projection (debug)");
         return APOLLO_OK;
@@ -831,7 +909,7 @@ apollo_status_t apollo_step_noalloc(const apollo_config_t* cfg, const apollo_sha
   const StepParams sp = make_step_params(*cfg, step, lr);
   // the scratch is shared by every call on this GPU and keeps nothing between calls: P is generated
   // in every call (nothing else in it is read before it is written within a step)
-  GroupLaunches L{*cfg, dd, sp, true, ""};
+  GroupLaunches L{*cfg, dd, StepArgs{sp, nullptr}, true, ""};
   e = run_serial(L, plan, st, nullptr);
   if (e != hipSuccess) return hip_fail(err, e, L.what);
   return APOLLO_OK;

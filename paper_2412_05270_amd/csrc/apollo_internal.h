@@ -51,6 +51,39 @@ struct StepParams {
   int32_t q8_stochastic;
 };
 
+// A step's scalars and the bookkeeping of the projection scratch in DEVICE memory (in the workspace),
+// for steps that are replayed from a HIP graph: a replayed launch cannot carry new kernel arguments,
+// so its kernels read the scalars from here, where apollo_step_prepare wrote them.
+struct StepState {
+  StepParams sp;
+  uint32_t p_epoch;    // refresh epoch of the P the scratch holds (written by the limiter kernel of every step)
+  int32_t p_valid;     // 0: the scratch holds no P yet
+  int32_t regen;       // this step has to write the scratch copy of P first (set by apollo_step_prepare)
+  int32_t pad;
+};
+
+// How the launches of a step get their scalars: by value (dev == nullptr: the ordinary step), or from
+// device memory (a step that may be captured and replayed).  `host` is always filled: the launchers
+// take what shapes the launch (rank, mode) from it, and those do not change from step to step.
+struct StepArgs {
+  StepParams host;
+  StepState* dev;
+};
+// The scalars as a kernel sees them.  The device copy is read as constant memory (scalar loads: the
+// values stay wave-uniform in scalar registers, as kernel arguments are); no kernel writes the
+// scalars while a step's kernels run (apollo_step_prepare's kernel precedes them in stream order).
+__device__ __forceinline__ StepParams step_params(const StepParams& by_value, const StepState* ss) {
+  static_assert(sizeof(StepParams) % 4 == 0, "copied word by word");
+  typedef const __attribute__((address_space(4))) uint32_t* constant_words_t;
+  if (!ss) return by_value;
+  StepParams out;
+  constant_words_t src = (constant_words_t)(uintptr_t)(&ss->sp);
+  uint32_t* dst = reinterpret_cast<uint32_t*>(&out);
+#pragma unroll
+  for (int i = 0; i < (int)(sizeof(StepParams) / 4); ++i) dst[i] = src[i];
+  return out;
+}
+
 // Pointers read from a TensorDesc are generic to the compiler; every buffer they name is device
 // global memory.  Saying so turns flat_load / flat_store into global_load / global_store, which
 // do not tie up the LDS counter (a flat access makes every later LDS wait also wait for it).
@@ -144,19 +177,19 @@ hipError_t launch_adamw(const AdamwDesc* d_descs, const uint32_t* d_block_tensor
 
 // ---- launchers (defined in the .hip files); all enqueue on `st` and return the launch status
 hipError_t launch_fill_projection(const TensorDesc* d_descs, int count, int r, int m8, bool bf16,
-                                  const StepParams& sp, hipStream_t st);
+                                  const StepArgs& sa, hipStream_t st);
 hipError_t launch_fill_projection_rowmajor(void* out, bool out_bf16, int r, int m, uint32_t tensor_id,
                                            const StepParams& sp, hipStream_t st);
 hipError_t launch_project_generic(const TensorDesc* d_descs, int count, int n, bool bf16,
-                                  const StepParams& sp, hipStream_t st);
+                                  const StepArgs& sa, hipStream_t st);
 hipError_t launch_project_rank1(const TensorDesc* d_descs, int count, int rows, int cols, bool left,
-                                bool bf16, int n_slabs, const StepParams& sp, hipStream_t st);
+                                bool bf16, int n_slabs, const StepArgs& sa, hipStream_t st);
 bool project_rank1_supported(int rows, int cols, bool left, bool bf16);
 // fused (the step): the kernel also performs the moment update and the channel sums, and the factors
 // when one block holds all rows of its channels (project_mfma_row_tiles(r) == 1; otherwise
 // launch_channel_factors follows).  Not fused (count must be 1): R is stored to r_override (debug view).
 hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool padded,
-                               bool fused, bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st);
+                               bool fused, bool state_bf16, float* r_override, const StepArgs& sa, hipStream_t st);
 // The same for several shape groups in one launch (their blocks follow each other in the grid); `first`
 // is the group's first descriptor relative to d_descs.
 struct MfmaGroupShape {
@@ -164,29 +197,39 @@ struct MfmaGroupShape {
   bool left, padded;
 };
 hipError_t launch_project_mfma_groups(const TensorDesc* d_descs, const MfmaGroupShape* groups, int n_groups, bool fused,
-                                      bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st);
+                                      bool state_bf16, float* r_override, const StepArgs& sa, hipStream_t st);
 hipError_t launch_channel_factors(const TensorDesc* d_descs, int count, int n, int row_tiles, hipStream_t st);
 int project_mfma_row_tiles(int r);
 int project_mfma_tiles(int n);
 bool project_mfma_needs_padding(int rows, int cols, bool left);
 hipError_t launch_pad_gradient(const TensorDesc* d_descs, int count, int rows, int cols, int ldg, hipStream_t st);
 bool project_mfma_supported(int rows, int cols, bool left, bool bf16, int r);
-hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepParams& sp,
+hipError_t launch_adam_norms(const TensorDesc* d_descs, int count, int n, bool state_bf16, const StepArgs& sa,
                              hipStream_t st);
-hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepParams& sp, hipStream_t st);
+hipError_t launch_finalize(const TensorDesc* d_descs, int count, const StepArgs& sa, hipStream_t st);
 hipError_t launch_update(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
-                         bool w_bf16, const StepParams& sp, hipStream_t st);
+                         bool w_bf16, const StepArgs& sa, hipStream_t st);
+// The same for several shape groups of one gradient type in one launch (small parameter sets).
+struct UpdateGroupShape {
+  int first, count, rows, cols;
+  bool left;
+};
+hipError_t launch_update_groups(const TensorDesc* d_descs, const UpdateGroupShape* groups, int n_groups, bool bf16, bool w_bf16,
+                                const StepArgs& sa, hipStream_t st);
 int adam_norms_blocks(int n);
 hipError_t launch_adam_identity(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool g_bf16,
-                                bool state_bf16, const StepParams& sp, hipStream_t st);
+                                bool state_bf16, const StepArgs& sa, hipStream_t st);
 hipError_t launch_update_q8(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
-                            const StepParams& sp, hipStream_t st);
+                            const StepArgs& sa, hipStream_t st);
 hipError_t launch_bf16_to_f32(float* dst, const void* src, size_t count, hipStream_t st);
 hipError_t launch_philox_words(const uint32_t* ctr, uint32_t k0, uint32_t k1, uint32_t* out,
                                int64_t count, hipStream_t st);
 hipError_t launch_gauss_parts(uint32_t first, int64_t count, float* radius, float* cosv, float* sinv,
                               hipStream_t st);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+// Writes a step's scalars into device memory and decides whether that step has to write P first:
+// force_regen, or the scratch holds none, or one of another refresh epoch.  reset: mark the scratch empty.
+hipError_t launch_set_step(StepState* d_state, const StepParams& sp, bool force_regen, bool reset, hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 
 }  // namespace apollo

@@ -17,7 +17,8 @@ __device__ __forceinline__ float load_g(const APOLLO_GLOBAL void* g, size_t idx,
 // Gm(i, j) is G[i][j] when the rows are projected (left) and G[j][i] otherwise.
 // ---------------------------------------------------------------------------------------------
 template <bool BF16>
-__global__ __launch_bounds__(256) void project_generic_kernel(const TensorDesc* __restrict__ descs, StepParams sp) {
+__global__ __launch_bounds__(256) void project_generic_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg, StepState* __restrict__ ss) {
+  const StepParams sp = step_params(sp_arg, ss);
   __shared__ float Gs[32][65];
   __shared__ float Ps[32][33];
   const TensorView d(descs[blockIdx.z]);
@@ -88,13 +89,13 @@ __global__ __launch_bounds__(256) void project_generic_kernel(const TensorDesc* 
   if (blockIdx.y == 0 && tid < 64 && j0 + tid < n) d.colsq[j0 + tid] = sq;
 }
 
-hipError_t launch_project_generic(const TensorDesc* d_descs, int count, int n, bool bf16, const StepParams& sp,
+hipError_t launch_project_generic(const TensorDesc* d_descs, int count, int n, bool bf16, const StepArgs& sa,
                                   hipStream_t st) {
-  dim3 grid((unsigned)((n + 63) / 64), (unsigned)((sp.r + 31) / 32), (unsigned)count);
+  dim3 grid((unsigned)((n + 63) / 64), (unsigned)((sa.host.r + 31) / 32), (unsigned)count);
   if (bf16)
-    hipLaunchKernelGGL(project_generic_kernel<true>, grid, dim3(256), 0, st, d_descs, sp);
+    hipLaunchKernelGGL(project_generic_kernel<true>, grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
   else
-    hipLaunchKernelGGL(project_generic_kernel<false>, grid, dim3(256), 0, st, d_descs, sp);
+    hipLaunchKernelGGL(project_generic_kernel<false>, grid, dim3(256), 0, st, d_descs, sa.host, sa.dev);
   return hipGetLastError();
 }
 
@@ -156,8 +157,9 @@ __device__ __forceinline__ void gen_z_to_lds(float* zs, int i0, int count, int m
 constexpr int kMiniSlabRowsMax = 1024;
 
 template <bool BF16>
-__global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
+__global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg, StepState* __restrict__ ss,
                                                                  int slab_rows) {
+  const StepParams sp = step_params(sp_arg, ss);
   __shared__ float zs[kMiniSlabRowsMax];
   __shared__ float red[2][3][64][9];
   const TensorView d(descs[blockIdx.z]);
@@ -235,7 +237,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 template <bool BF16>
 __global__ __launch_bounds__(256) void project_rank1_right_kernel(const TensorDesc* __restrict__ descs,
-                                                                  StepParams sp) {
+                                                                  StepParams sp_arg, StepState* __restrict__ ss) {
+  const StepParams sp = step_params(sp_arg, ss);
   extern __shared__ float zs[];
   const TensorView d(descs[blockIdx.z]);
   const int rows = d.rows, cols = d.cols;
@@ -287,16 +290,16 @@ bool project_rank1_supported(int rows, int cols, bool left, bool bf16) {
 }
 
 hipError_t launch_project_rank1(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
-                                int n_slabs, const StepParams& sp, hipStream_t st) {
+                                int n_slabs, const StepArgs& sa, hipStream_t st) {
   if (left) {
     const int slab_rows = (((rows + n_slabs - 1) / n_slabs) + 3) & ~3;   // multiple of 4: slabs start on a quad
     dim3 grid((unsigned)((cols / 8 + 63) / 64), (unsigned)n_slabs, (unsigned)count);
-    if (bf16) hipLaunchKernelGGL(project_rank1_left_kernel<true>, grid, dim3(256), 0, st, d_descs, sp, slab_rows);
-    else hipLaunchKernelGGL(project_rank1_left_kernel<false>, grid, dim3(256), 0, st, d_descs, sp, slab_rows);
+    if (bf16) hipLaunchKernelGGL(project_rank1_left_kernel<true>, grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, slab_rows);
+    else hipLaunchKernelGGL(project_rank1_left_kernel<false>, grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, slab_rows);
   } else {
     dim3 grid((unsigned)((rows + kMiniRightRowsPerBlock - 1) / kMiniRightRowsPerBlock), 1, (unsigned)count);
-    if (bf16) hipLaunchKernelGGL(project_rank1_right_kernel<true>, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sp);
-    else hipLaunchKernelGGL(project_rank1_right_kernel<false>, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sp);
+    if (bf16) hipLaunchKernelGGL(project_rank1_right_kernel<true>, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sa.host, sa.dev);
+    else hipLaunchKernelGGL(project_rank1_right_kernel<false>, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sa.host, sa.dev);
   }
   return hipGetLastError();
 }

@@ -548,9 +548,11 @@ struct MfmaGroups {
 };
 
 template <int MT, int WM, bool FUSED, bool SB16>
-__global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp,
-                                                                    MfmaGroups tbl, float* __restrict__ r_override) {
+__global__ __launch_bounds__(kThreads) void project_mfma_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg,
+                                                                    StepState* __restrict__ ss, MfmaGroups tbl,
+                                                                    float* __restrict__ r_override) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const StepParams sp = step_params(sp_arg, ss);
   const int b = blockIdx.x;
   int first = 0, count = 0, tiles = 1, left = 0, padded = 0, begin = 0;
 #pragma unroll
@@ -608,7 +610,7 @@ __global__ __launch_bounds__(kNT) void channel_factors_kernel(const TensorDesc* 
 }
 
 template <int MT, int WM, bool FUSED, bool SB16>
-hipError_t launch_cfg(const TensorDesc* d_descs, const MfmaGroups& tbl, float* r_override, const StepParams& sp, hipStream_t st) {
+hipError_t launch_cfg(const TensorDesc* d_descs, const MfmaGroups& tbl, float* r_override, const StepArgs& sa, hipStream_t st) {
   using C = Cfg<MT, WM>;
   const int lds_bytes = kRing * C::STAGE_BYTES;
   static_assert(!FUSED || kRing * C::STAGE_BYTES >= (int)((2 * kWaves + 1) * kNT + 16) * (int)sizeof(float), "epilogue sums fit the ring");
@@ -620,16 +622,16 @@ hipError_t launch_cfg(const TensorDesc* d_descs, const MfmaGroups& tbl, float* r
     attr_done.store(true, std::memory_order_release);
   }
   dim3 grid((unsigned)tbl.g[tbl.n - 1].blocks_end, 1, 1);
-  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, FUSED, SB16>), grid, dim3(kThreads), lds_bytes, st, d_descs, sp, tbl, r_override);
+  hipLaunchKernelGGL((project_mfma_kernel<MT, WM, FUSED, SB16>), grid, dim3(kThreads), lds_bytes, st, d_descs, sa.host, sa.dev, tbl, r_override);
   return hipGetLastError();
 }
 
 template <int MT, int WM>
 hipError_t launch_variant(const TensorDesc* d_descs, const MfmaGroups& tbl, bool fused, bool state_bf16, float* r_override,
-                          const StepParams& sp, hipStream_t st) {
-  if (!fused) return launch_cfg<MT, WM, false, false>(d_descs, tbl, r_override, sp, st);
-  if (state_bf16) return launch_cfg<MT, WM, true, true>(d_descs, tbl, nullptr, sp, st);
-  return launch_cfg<MT, WM, true, false>(d_descs, tbl, nullptr, sp, st);
+                          const StepArgs& sa, hipStream_t st) {
+  if (!fused) return launch_cfg<MT, WM, false, false>(d_descs, tbl, r_override, sa, st);
+  if (state_bf16) return launch_cfg<MT, WM, true, true>(d_descs, tbl, nullptr, sa, st);
+  return launch_cfg<MT, WM, true, false>(d_descs, tbl, nullptr, sa, st);
 }
 
 }  // namespace
@@ -658,10 +660,10 @@ int project_mfma_row_tiles(int r) { return r % 256 == 0 ? r / 256 : r % 128 == 0
 int project_mfma_tiles(int n) { return (n + kNT - 1) / kNT; }
 
 hipError_t launch_project_mfma_groups(const TensorDesc* d_descs, const MfmaGroupShape* groups, int n_groups, bool fused,
-                                      bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st) {
+                                      bool state_bf16, float* r_override, const StepArgs& sa, hipStream_t st) {
   if (n_groups < 1 || fused == (r_override != nullptr) || (r_override && (n_groups != 1 || groups[0].count != 1)))
     return hipErrorInvalidValue;
-  const int r = sp.r;
+  const int r = sa.host.r;
   const int row_tiles = project_mfma_row_tiles(r);
   for (int g0 = 0; g0 < n_groups; g0 += kMaxGroups) {
     MfmaGroups tbl{};
@@ -676,19 +678,19 @@ hipError_t launch_project_mfma_groups(const TensorDesc* d_descs, const MfmaGroup
       tbl.g[i] = MfmaGroup{g.first, g.count, tiles, blocks, g.left ? 1 : 0, g.padded ? 1 : 0};
     }
     hipError_t e;
-    if (r % 256 == 0) e = launch_variant<4, 2>(d_descs, tbl, fused, state_bf16, r_override, sp, st);
-    else if (r % 128 == 0) e = launch_variant<2, 2>(d_descs, tbl, fused, state_bf16, r_override, sp, st);
-    else if (r % 64 == 0) e = launch_variant<1, 2>(d_descs, tbl, fused, state_bf16, r_override, sp, st);
-    else e = launch_variant<1, 1>(d_descs, tbl, fused, state_bf16, r_override, sp, st);
+    if (r % 256 == 0) e = launch_variant<4, 2>(d_descs, tbl, fused, state_bf16, r_override, sa, st);
+    else if (r % 128 == 0) e = launch_variant<2, 2>(d_descs, tbl, fused, state_bf16, r_override, sa, st);
+    else if (r % 64 == 0) e = launch_variant<1, 2>(d_descs, tbl, fused, state_bf16, r_override, sa, st);
+    else e = launch_variant<1, 1>(d_descs, tbl, fused, state_bf16, r_override, sa, st);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
 hipError_t launch_project_mfma(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool padded,
-                               bool fused, bool state_bf16, float* r_override, const StepParams& sp, hipStream_t st) {
+                               bool fused, bool state_bf16, float* r_override, const StepArgs& sa, hipStream_t st) {
   const MfmaGroupShape g{0, count, rows, cols, left, padded};
-  return launch_project_mfma_groups(d_descs, &g, 1, fused, state_bf16, r_override, sp, st);
+  return launch_project_mfma_groups(d_descs, &g, 1, fused, state_bf16, r_override, sa, st);
 }
 
 hipError_t launch_channel_factors(const TensorDesc* d_descs, int count, int n, int row_tiles, hipStream_t st) {

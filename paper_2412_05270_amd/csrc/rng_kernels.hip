@@ -12,7 +12,9 @@ namespace apollo {
 // one contiguous run of the fragment-major scratch layout (8 bytes per thread for bf16).
 template <bool BF16>
 __global__ __launch_bounds__(256) void fill_projection_kernel(const TensorDesc* __restrict__ descs,
-                                                              StepParams sp, int m8) {
+                                                              StepParams sp_arg, StepState* __restrict__ ss, int m8) {
+  if (ss && !ss->regen) return;       // a replayed step whose scratch already holds this epoch's P
+  const StepParams sp = step_params(sp_arg, ss);
   const TensorView d(descs[blockIdx.y]);
   const int r = sp.r;
   const size_t total = (size_t)r * (size_t)(m8 >> 2);
@@ -43,13 +45,13 @@ __global__ __launch_bounds__(256) void fill_projection_kernel(const TensorDesc* 
 }
 
 hipError_t launch_fill_projection(const TensorDesc* d_descs, int count, int r, int m8, bool bf16,
-                                  const StepParams& sp, hipStream_t st) {
+                                  const StepArgs& sa, hipStream_t st) {
   const size_t total = (size_t)r * (size_t)(m8 >> 2);
   dim3 grid((unsigned)((total + 255) / 256), (unsigned)count, 1);
   if (bf16)
-    hipLaunchKernelGGL(fill_projection_kernel<true>, grid, dim3(256), 0, st, d_descs, sp, m8);
+    hipLaunchKernelGGL(fill_projection_kernel<true>, grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, m8);
   else
-    hipLaunchKernelGGL(fill_projection_kernel<false>, grid, dim3(256), 0, st, d_descs, sp, m8);
+    hipLaunchKernelGGL(fill_projection_kernel<false>, grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, m8);
   return hipGetLastError();
 }
 
@@ -162,6 +164,22 @@ hipError_t launch_gauss_parts(uint32_t first, int64_t count, float* radius, floa
   if (count == 0) return hipSuccess;
   hipLaunchKernelGGL(gauss_parts_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, first, count,
                      radius, cosv, sinv);
+  return hipGetLastError();
+}
+
+// A step's scalars into device memory (see StepState), and whether the step has to write P first.
+__global__ __launch_bounds__(64) void set_step_kernel(StepState* __restrict__ ss, StepParams sp, int force_regen, int reset) {
+  if (threadIdx.x != 0) return;
+  if (reset) {
+    ss->p_valid = 0;
+    ss->p_epoch = 0;
+  }
+  ss->sp = sp;
+  ss->regen = (force_regen || !ss->p_valid || ss->p_epoch != sp.epoch) ? 1 : 0;
+}
+
+hipError_t launch_set_step(StepState* d_state, const StepParams& sp, bool force_regen, bool reset, hipStream_t st) {
+  hipLaunchKernelGGL(set_step_kernel, dim3(1), dim3(64), 0, st, d_state, sp, force_regen ? 1 : 0, reset ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
     assert {"apollo_init", "apollo_step", "apollo_state_bytes", "apollo_workspace_bytes", "apollo_destroy",
             "apollo_debug_fill_projection", "apollo_debug_get", "apollo_state_offsets", "apollo_last_error",
             "apollo_debug_philox", "apollo_debug_gauss_parts", "apollo_debug_copy", "apollo_debug_path", "apollo_profile_enable",
-            "apollo_profile_read", "apollo_step_noalloc", "apollo_adamw_state_bytes", "apollo_adamw_state_offsets",
+            "apollo_profile_read", "apollo_step_noalloc", "apollo_step_prepare", "apollo_step_launch", "apollo_adamw_state_bytes", "apollo_adamw_state_offsets",
             "apollo_adamw_workspace_bytes", "apollo_adamw_init", "apollo_adamw_step", "apollo_adamw_last_error",
             "apollo_adamw_destroy"} <= names
     for n in names:
@@ -168,6 +168,8 @@ def test_unknown_schedule_and_rounding_are_rejected():
 
 def test_null_handle_calls_fail_cleanly():
     assert A.apollo_step(None, [(16, 32)], 1, 0.1) == A.APOLLO_EINVAL
+    assert A.apollo_step_prepare(None, 1, 0.1) == A.APOLLO_EINVAL
+    assert A.apollo_step_launch(None, None) == A.APOLLO_EINVAL
     assert A.apollo_debug_get(None, 0, A.APOLLO_DBG_M, 16, 4) == A.APOLLO_EINVAL
     assert A.apollo_debug_fill_projection(None, 0, 1, 16, A.APOLLO_F32) == A.APOLLO_EINVAL
     assert A.apollo_debug_gauss_parts(1 << 24, 1, 16, 16, 16) == A.APOLLO_EINVAL
