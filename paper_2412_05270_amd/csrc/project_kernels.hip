@@ -102,7 +102,8 @@ hipError_t launch_project_generic(const TensorDesc* d_descs, int count, int n, b
 // ---------------------------------------------------------------------------------------------
 // Rank 1 (APOLLO-Mini): R[j] = sum_i z[i] Gm[i, j] is a matrix-vector product, bound by the one
 // pass over G.  z is generated into LDS by the block that needs it; G is read with 16-byte
-// loads (eight bf16).  Requires cols % 8 == 0 and bf16 gradients.
+// loads (eight bf16, or two loads of four fp32); a row length that is not a multiple of 8 takes the
+// same loads unaligned and the ragged last octet of a row element by element.
 // ---------------------------------------------------------------------------------------------
 
 // unpack eight bf16 (one 16-byte load) to floats
@@ -117,18 +118,49 @@ __device__ __forceinline__ void unpack8(const u32x4_t& v, float f[8]) {
   f[7] = __uint_as_float(v.w & 0xFFFF0000u);
 }
 
-// Eight consecutive gradient elements at octet index o of a row-major array, as floats, streamed:
-// one 16-byte load of bf16, or two of fp32.
-template <bool BF16>
-__device__ __forceinline__ void load_octet(const APOLLO_GLOBAL void* g, size_t o, float f[8]) {
+// Eight consecutive gradient elements starting at element index `elem` of a row-major array, as
+// floats, streamed: one 16-byte load of bf16, or two of fp32.  elem is a multiple of 8 (the loads are
+// naturally aligned) unless UA: then it is any element index, and the loads are declared aligned to
+// the element type only (global memory takes unaligned vector accesses).
+template <bool BF16, bool UA>
+__device__ __forceinline__ void load_octet(const APOLLO_GLOBAL void* g, size_t elem, float f[8]) {
+  typedef uint32_t u32x4_ua_t __attribute__((ext_vector_type(4), aligned(2)));
+  typedef float f32x4_ua_t __attribute__((ext_vector_type(4), aligned(4)));
   if constexpr (BF16) {
-    unpack8(__builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(g) + o), f);
+    const APOLLO_GLOBAL uint16_t* p = reinterpret_cast<const APOLLO_GLOBAL uint16_t*>(g) + elem;
+    if constexpr (UA) {
+      const u32x4_ua_t t = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x4_ua_t*>(p));
+      u32x4_t v;
+      v.x = t.x; v.y = t.y; v.z = t.z; v.w = t.w;
+      unpack8(v, f);
+    } else {
+      unpack8(__builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL u32x4_t*>(p)), f);
+    }
   } else {
-    const APOLLO_GLOBAL f32x4_t* p = reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(g) + 2 * o;
-    const f32x4_t lo = __builtin_nontemporal_load(p), hi = __builtin_nontemporal_load(p + 1);
-    f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w;
-    f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
+    const APOLLO_GLOBAL float* p = reinterpret_cast<const APOLLO_GLOBAL float*>(g) + elem;
+    if constexpr (UA) {
+      const f32x4_ua_t lo = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL f32x4_ua_t*>(p));
+      const f32x4_ua_t hi = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL f32x4_ua_t*>(p) + 1);
+      f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w;
+      f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
+    } else {
+      const f32x4_t lo = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(p));
+      const f32x4_t hi = __builtin_nontemporal_load(reinterpret_cast<const APOLLO_GLOBAL f32x4_t*>(p) + 1);
+      f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w;
+      f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
+    }
   }
+}
+
+// The first cnt (1..7) of eight consecutive elements, one at a time (the ragged end of a row whose
+// length is not a multiple of 8); the rest read as 0.
+template <bool BF16>
+__device__ __forceinline__ void load_octet_part(const APOLLO_GLOBAL void* g, size_t elem, int cnt, float f[8]) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = 0.f;
+#pragma unroll
+  for (int e = 0; e < 7; ++e)
+    if (e < cnt) f[e] = load_g(g, elem + e, BF16);
 }
 
 // Generates z[i0 .. i0+count) (count % 4 == 0 or the tail beyond m ignored) into zs[0 .. count).
@@ -156,7 +188,7 @@ __device__ __forceinline__ void gen_z_to_lds(float* zs, int i0, int count, int m
 // combined through LDS.  Output: partial R and colsq of this slab.
 constexpr int kMiniSlabRowsMax = 1024;
 
-template <bool BF16>
+template <bool BF16, bool UA>
 __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDesc* __restrict__ descs, StepParams sp_arg, StepState* __restrict__ ss,
                                                                  int slab_rows) {
   const StepParams sp = step_params(sp_arg, ss);
@@ -171,16 +203,23 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
   __syncthreads();
   const int cv = blockIdx.x * 64 + tx;          // column octet
   const bool active = cv * 8 < cols;
+  // UA (a row length that is not a multiple of 8): rows start at any element, and the last octet
+  // of a row has only cnt columns
+  const int cnt = min(8, cols - cv * 8);
   float acc[8], sq[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = sq[e] = 0.f;
   if (active) {
-    const size_t stride = (size_t)(cols >> 3);      // octets per row
+    auto ld = [&](int row, float f[8]) {
+      const size_t elem = (size_t)row * (size_t)cols + (size_t)cv * 8;
+      if (!UA || cnt == 8) load_octet<BF16, UA>(d.g, elem, f);
+      else load_octet_part<BF16>(d.g, elem, cnt, f);
+    };
     int i = i0 + ty;
     for (; i + 12 < i1; i += 16) {
       float f[4][8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) load_octet<BF16>(d.g, (size_t)(i + 4 * u) * stride + (size_t)cv, f[u]);
+      for (int u = 0; u < 4; ++u) ld(i + 4 * u, f[u]);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const float z = zs[i + 4 * u - i0];
@@ -193,7 +232,7 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
     }
     for (; i < i1; i += 4) {
       float f[8];
-      load_octet<BF16>(d.g, (size_t)i * stride + (size_t)cv, f);
+      ld(i, f);
       const float z = zs[i - i0];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -217,8 +256,10 @@ __global__ __launch_bounds__(256) void project_rank1_left_kernel(const TensorDes
     for (int e = 0; e < 8; ++e) {
       const float a = ((acc[e] + red[0][0][tx][e]) + red[0][1][tx][e]) + red[0][2][tx][e];
       const float b = ((sq[e] + red[1][0][tx][e]) + red[1][1][tx][e]) + red[1][2][tx][e];
-      Rp[e] = a;            // r = 1: 1/sqrt(r) = 1
-      Cp[e] = b;
+      if (!UA || e < cnt) {
+        Rp[e] = a;          // r = 1: 1/sqrt(r) = 1
+        Cp[e] = b;
+      }
     }
   }
 }
@@ -235,17 +276,17 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-template <bool BF16>
+template <bool BF16, bool UA>
 __global__ __launch_bounds__(256) void project_rank1_right_kernel(const TensorDesc* __restrict__ descs,
                                                                   StepParams sp_arg, StepState* __restrict__ ss) {
   const StepParams sp = step_params(sp_arg, ss);
   extern __shared__ float zs[];
   const TensorView d(descs[blockIdx.z]);
   const int rows = d.rows, cols = d.cols;
-  gen_z_to_lds(zs, 0, cols, cols, sp, (uint32_t)d.tensor_id, BF16);
+  gen_z_to_lds(zs, 0, (cols + 7) & ~7, cols, sp, (uint32_t)d.tensor_id, BF16);   // (zeros behind a ragged end)
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int nv = cols >> 3;
+  const int nv = (cols + 7) >> 3;          // octets per row; with UA the last one may have only cols % 8 elements
   const int row_begin = blockIdx.x * kMiniRightRowsPerBlock + wave * (kMiniRightRowsPerBlock / 4);
   const int row_end = min(rows, row_begin + kMiniRightRowsPerBlock / 4);
   for (int i = row_begin; i < row_end; i += 4) {
@@ -255,7 +296,9 @@ __global__ __launch_bounds__(256) void project_rank1_right_kernel(const TensorDe
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int ii = min(i + u, rows - 1);
-        load_octet<BF16>(d.g, (size_t)ii * nv + v0, fv[u]);
+        const size_t elem = (size_t)ii * (size_t)cols + (size_t)v0 * 8;
+        if (!UA || v0 * 8 + 8 <= cols) load_octet<BF16, UA>(d.g, elem, fv[u]);
+        else load_octet_part<BF16>(d.g, elem, cols - v0 * 8, fv[u]);
       }
       const f32x4_t za = reinterpret_cast<const f32x4_t*>(zs)[2 * v0];
       const f32x4_t zb = reinterpret_cast<const f32x4_t*>(zs)[2 * v0 + 1];
@@ -283,7 +326,6 @@ __global__ __launch_bounds__(256) void project_rank1_right_kernel(const TensorDe
 
 bool project_rank1_supported(int rows, int cols, bool left, bool bf16) {
   (void)bf16;
-  if ((cols & 7) != 0) return false;
   if (!left && cols > kMiniRightMaxM) return false;
   (void)rows;
   return true;
@@ -291,15 +333,21 @@ bool project_rank1_supported(int rows, int cols, bool left, bool bf16) {
 
 hipError_t launch_project_rank1(const TensorDesc* d_descs, int count, int rows, int cols, bool left, bool bf16,
                                 int n_slabs, const StepArgs& sa, hipStream_t st) {
+  const bool ua = (cols & 7) != 0;     // rows of the gradient do not start on 16-byte boundaries
   if (left) {
     const int slab_rows = (((rows + n_slabs - 1) / n_slabs) + 3) & ~3;   // multiple of 4: slabs start on a quad
-    dim3 grid((unsigned)((cols / 8 + 63) / 64), (unsigned)n_slabs, (unsigned)count);
-    if (bf16) hipLaunchKernelGGL(project_rank1_left_kernel<true>, grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, slab_rows);
-    else hipLaunchKernelGGL(project_rank1_left_kernel<false>, grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, slab_rows);
+    dim3 grid((unsigned)(((cols + 7) / 8 + 63) / 64), (unsigned)n_slabs, (unsigned)count);
+    if (bf16 && !ua) hipLaunchKernelGGL((project_rank1_left_kernel<true, false>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, slab_rows);
+    else if (bf16) hipLaunchKernelGGL((project_rank1_left_kernel<true, true>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, slab_rows);
+    else if (!ua) hipLaunchKernelGGL((project_rank1_left_kernel<false, false>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, slab_rows);
+    else hipLaunchKernelGGL((project_rank1_left_kernel<false, true>), grid, dim3(256), 0, st, d_descs, sa.host, sa.dev, slab_rows);
   } else {
     dim3 grid((unsigned)((rows + kMiniRightRowsPerBlock - 1) / kMiniRightRowsPerBlock), 1, (unsigned)count);
-    if (bf16) hipLaunchKernelGGL(project_rank1_right_kernel<true>, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sa.host, sa.dev);
-    else hipLaunchKernelGGL(project_rank1_right_kernel<false>, grid, dim3(256), (size_t)cols * sizeof(float), st, d_descs, sa.host, sa.dev);
+    const size_t lds = (size_t)((cols + 7) & ~7) * sizeof(float);
+    if (bf16 && !ua) hipLaunchKernelGGL((project_rank1_right_kernel<true, false>), grid, dim3(256), lds, st, d_descs, sa.host, sa.dev);
+    else if (bf16) hipLaunchKernelGGL((project_rank1_right_kernel<true, true>), grid, dim3(256), lds, st, d_descs, sa.host, sa.dev);
+    else if (!ua) hipLaunchKernelGGL((project_rank1_right_kernel<false, false>), grid, dim3(256), lds, st, d_descs, sa.host, sa.dev);
+    else hipLaunchKernelGGL((project_rank1_right_kernel<false, true>), grid, dim3(256), lds, st, d_descs, sa.host, sa.dev);
   }
   return hipGetLastError();
 }

@@ -63,6 +63,9 @@ def workload(name):
     if name == "llama1b":
         return Workload(name, 3, llama_shapes(2048, 5461, 24), torch.bfloat16, "student_t", 1e-3, rank=512,
                         steps=20)
+    if name == "llama1b_mini":           # APOLLO-Mini on the 1B shapes: rows of 5461 elements start on no 16-byte boundary
+        return Workload(name, 3, llama_shapes(2048, 5461, 24), torch.bfloat16, "student_t", 1e-3, rank=1,
+                        mode="tensor", scale=MINI_SCALE, steps=20)
     if name == "llama7b_mini":
         return Workload(name, 4, llama_shapes(4096, 11008, 32), torch.bfloat16, "normal", 1e-3, rank=1,
                         mode="tensor", scale=MINI_SCALE, steps=20)

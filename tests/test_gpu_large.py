@@ -14,6 +14,7 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("name,steps", [
     ("llama1b", 3),
+    ("llama1b_mini", 3),            # rank 1 on rows of 5461 elements (unaligned 16-byte accesses, ragged last octet)
     ("llama7b_mini", 3),
     ("llama7b_r256", 2),
     ("llama13b_mini", 2),
@@ -182,6 +183,7 @@ def test_full_size_sets_run_on_the_kernels_meant_for_them():
     from parity_util import make_configs
     dev = "cuda:0"
     expect = {"llama60m": A.APOLLO_PATH_MATRIX_CORE, "llama1b": A.APOLLO_PATH_MATRIX_CORE,
+              "llama1b_mini": A.APOLLO_PATH_RANK1,
               "llama7b_mini": A.APOLLO_PATH_RANK1, "llama7b_r256": A.APOLLO_PATH_MATRIX_CORE,
               "llama13b_mini": A.APOLLO_PATH_RANK1, "llama13b_r256": A.APOLLO_PATH_MATRIX_CORE,
               "llama7b_mini_q8": A.APOLLO_PATH_RANK1, "llama7b_identity": A.APOLLO_PATH_NONE,

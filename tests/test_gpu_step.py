@@ -55,6 +55,21 @@ def test_ragged_shapes_both_sides_with_weight_decay_and_limiter(dtype, mode, ran
     run_parity(wl, list(range(len(RAGGED))), wl.steps, boost={4: 3.0})
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_rank_one_takes_the_streaming_kernel_for_any_row_length(dtype):
+    """Row lengths that are not a multiple of 8 (rows that start on no 16-byte boundary, a ragged last
+    octet) are served by the rank-1 kernels too, not by the general projection; their results are what
+    test_ragged_shapes_both_sides_with_weight_decay_and_limiter compares with the oracle."""
+    wl = WL.Workload("ragged", 7, RAGGED, dtype, "normal", 1e-2, rank=1, mode="tensor", scale=2.0)
+    cfg, _ = make_configs(wl)
+    weights = [torch.zeros(s, dtype=torch.float32, device=DEV) for s in RAGGED]
+    grads = [torch.zeros(s, dtype=dtype, device=DEV) for s in RAGGED]
+    st = A.ApolloStepper(cfg, weights, grads, device=DEV)
+    for i in range(len(RAGGED)):
+        assert st.path(i) == (A.APOLLO_PATH_RANK1, 0), (RAGGED[i], st.path(i))
+    st.close()
+
+
 # shapes chosen so that the matrix-core projection runs with 1, 2, 3 and 5 pipeline stages (m = 64,
 # 128, 192, 320), a ragged (shifted) last channel tile (n = 264, 520, 1376), exactly one tile
 # (n = 256), and both orientations
