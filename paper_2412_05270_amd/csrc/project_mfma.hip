@@ -132,27 +132,28 @@ struct Ctx {
     }
   }
 
-  // all loads of stage s (clamped) into ring buffer `buf`: P tile first, then the G tile
-  __device__ __forceinline__ void issue(int s, int buf) const {
+  // load u (0 .. LOADS-1) of stage s (clamped) into ring buffer `buf`: the P tile's loads first, then the G tile's
+  __device__ __forceinline__ void issue_one(int s, int buf, int u) const {
     s = min(s, last_stage);
     const uint32_t a_base = lds_base + (uint32_t)(buf * C::STAGE_BYTES);
     const uint32_t b_base = a_base + (uint32_t)C::A_BYTES;
-    const APOLLO_GLOBAL u32x4_t* a_src = Pg + (size_t)((kKT / 8) * s) * r + rbase;
-    if (C::A_CHUNKS > 0) {
-#pragma unroll
-      for (int u = 0; u < C::A_LOADS; ++u) dma16(a_src, a_off[u], a_base + (uint32_t)(wave * 64 + kThreads * u) * 16u);
-    } else {
-      dma16(a_src, a_off[0], a_base + (uint32_t)(min(wave, C::A_SLOTS / 64 - 1) * 64) * 16u);
-    }
-    if (LEFT) {
+    if (u < C::A_LOADS) {
+      const APOLLO_GLOBAL u32x4_t* a_src = Pg + (size_t)((kKT / 8) * s) * r + rbase;
+      if (C::A_CHUNKS > 0) dma16(a_src, a_off[u], a_base + (uint32_t)(wave * 64 + kThreads * u) * 16u);
+      else dma16(a_src, a_off[0], a_base + (uint32_t)(min(wave, C::A_SLOTS / 64 - 1) * 64) * 16u);
+    } else if (LEFT) {
+      const int ub = u - C::A_LOADS;
       const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(kKT * s + 4 * wave) * ldg + n0;
-#pragma unroll
-      for (int u = 0; u < C::B_LOADS; ++u) dma16(b_src, b_off[u], b_base + (uint32_t)(4 * wave + 2 * u) * 512u);
+      dma16(b_src, b_off[ub], b_base + (uint32_t)(4 * wave + 2 * ub) * 512u);
     } else {
+      const int ub = u - C::A_LOADS;
       const APOLLO_GLOBAL uint16_t* b_src = G + (size_t)(n0 + 32 * wave) * m + kKT * s;
-#pragma unroll
-      for (int u = 0; u < C::B_LOADS; ++u) dma16(b_src, b_off[u], b_base + (uint32_t)(2 * wave + u) * 1024u);
+      dma16(b_src, b_off[ub], b_base + (uint32_t)(2 * wave + ub) * 1024u);
     }
+  }
+  __device__ __forceinline__ void issue(int s, int buf) const {
+#pragma unroll
+    for (int u = 0; u < C::LOADS; ++u) issue_one(s, buf, u);
   }
 
   // n-tile (32 channels) of the block that this wave's fragment b covers.  The order is rotated
@@ -160,38 +161,41 @@ struct Ctx {
   // channels: every wave then sums the norms of its fragment 0 only, and together they cover all.
   __device__ __forceinline__ int tile_of(int b) const { return wn * C::NTW + (b ^ wm); }
 
-  __device__ __forceinline__ void read_frags(int buf, int ks, bf16x8_t (&af)[MT], bf16x8_t (&bf)[C::NTW]) const {
+  // fragment a (32 rows of P x 16 reduction indices of k-step ks) of the stage in ring buffer `buf`
+  __device__ __forceinline__ bf16x8_t read_a(int buf, int ks, int a) const {
     const unsigned char* A = lds + buf * C::STAGE_BYTES;
-    const unsigned char* B = A + C::A_BYTES;
     const int oct = 2 * ks + (lane >> 5);
-#pragma unroll
-    for (int a = 0; a < MT; ++a)
-      af[a] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(
-                                               A + (size_t)(oct * C::RT + wm * 32 * MT + a * 32 + (lane & 31)) * 16));
+    return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(
+                                            A + (size_t)(oct * C::RT + wm * 32 * MT + a * 32 + (lane & 31)) * 16));
+  }
+  // fragment b (16 reduction indices x 32 channels)
+  __device__ __forceinline__ bf16x8_t read_b(int buf, int ks, int b) const {
+    const unsigned char* B = lds + buf * C::STAGE_BYTES + C::A_BYTES;
     if (LEFT) {
       const int q = lane >> 4, s16 = lane & 15;
       const int e_s = s16 >> 2, g_s = s16 & 3;
+      const int col0 = 32 * tile_of(b) + 16 * (q & 1) + 4 * g_s;
+      s16x4_t h[2];
 #pragma unroll
-      for (int b = 0; b < C::NTW; ++b) {
-        const int col0 = 32 * tile_of(b) + 16 * (q & 1) + 4 * g_s;
-        s16x4_t h[2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const int k = 16 * ks + 8 * (q >> 1) + 4 * t + e_s;
-          const unsigned char* p = B + k * 512 + (((col0 >> 3) ^ (4 * (k & 3))) * 16) + ((col0 >> 2) & 1) * 8;
-          h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((APOLLO_LDS s16x4_t*)(p));
-        }
-        typedef short s16x8_t __attribute__((ext_vector_type(8)));
-        const s16x8_t both = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
-        bf[b] = __builtin_bit_cast(bf16x8_t, both);
+      for (int t = 0; t < 2; ++t) {
+        const int k = 16 * ks + 8 * (q >> 1) + 4 * t + e_s;
+        const unsigned char* p = B + k * 512 + (((col0 >> 3) ^ (4 * (k & 3))) * 16) + ((col0 >> 2) & 1) * 8;
+        h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((APOLLO_LDS s16x4_t*)(p));
       }
+      typedef short s16x8_t __attribute__((ext_vector_type(8)));
+      const s16x8_t both = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8_t, both);
     } else {
-#pragma unroll
-      for (int b = 0; b < C::NTW; ++b) {
-        const int j = 32 * tile_of(b) + (lane & 31);
-        bf[b] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(B + j * 64 + ((oct ^ ((j >> 2) & 3)) * 16)));
-      }
+      const int oct = 2 * ks + (lane >> 5);
+      const int j = 32 * tile_of(b) + (lane & 31);
+      return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(B + j * 64 + ((oct ^ ((j >> 2) & 3)) * 16)));
     }
+  }
+  __device__ __forceinline__ void read_frags(int buf, int ks, bf16x8_t (&af)[MT], bf16x8_t (&bf)[C::NTW]) const {
+#pragma unroll
+    for (int a = 0; a < MT; ++a) af[a] = read_a(buf, ks, a);
+#pragma unroll
+    for (int b = 0; b < C::NTW; ++b) bf[b] = read_b(buf, ks, b);
   }
 };
 
@@ -292,14 +296,30 @@ __device__ __forceinline__ void project_body(const TensorDesc* __restrict__ desc
     // every wave is past stage s-1, whose buffer then receives stage s+3
     wait_vmcnt<(kRing - 3) * C::LOADS>();
     __syncthreads();
-    cx.issue(s + kRing - 1, (s + kRing - 1) % kRing);
     __builtin_amdgcn_sched_barrier(0);
-    // k-step 1 of stage s, fragments of k-step 0 of stage s+1 on their way
-    cx.read_frags((s + 1) % kRing, 0, af0, bf0);
-    mfma_block<MT, C::NTW>(acc, af1, bf1);
-    sq = sq_accum8(bf1[0], sq);
-    sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (4 + MT * C::NTW - 1) / (MT * C::NTW)>();
-    __builtin_amdgcn_sched_barrier(0);
+    // k-step 1 of stage s, with the fragments of k-step 0 of stage s+1 and the loads of stage s+3 spread
+    // between its MFMAs: the texture path takes a wave's 1 KB load every few tens of cycles only, and a
+    // wave that waits to issue one issues nothing else.  Issued in one burst behind the barrier, the
+    // eight waves' loads queue up and the matrix cores idle meanwhile; issued one at a time behind an
+    // MFMA each, a load waits while that MFMA (and the other wave's) run.
+    {
+      constexpr int NM = MT * C::NTW, NR = MT + C::NTW, NS = NM > NR ? NM : NR;
+      const int nb = (s + 1) % kRing, lb = (s + kRing - 1) % kRing;
+#pragma unroll
+      for (int i = 0; i < NS; ++i) {
+        if (i < MT) af0[i] = cx.read_a(nb, 0, i);
+        else if (i < NR) bf0[i - MT] = cx.read_b(nb, 0, i - MT);
+        if (i < NM) {
+          acc[i / C::NTW][i % C::NTW] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i / C::NTW], bf1[i % C::NTW], acc[i / C::NTW][i % C::NTW], 0, 0, 0);
+#pragma unroll
+          for (int u = 0; u < C::LOADS; ++u)
+            if ((u * NM) / C::LOADS == i) cx.issue_one(s + kRing - 1, lb, u);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      sq = sq_accum8(bf1[0], sq);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   wait_vmcnt<0>();      // drain the (clamped, redundant) loads still in flight before LDS is reused
 
