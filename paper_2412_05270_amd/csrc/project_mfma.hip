@@ -6,8 +6,9 @@
 // owns a (32 MT) x (32 WM) sub-tile.  A wave issues at most one instruction every four cycles, so
 // with a single wave per SIMD every address, wait and load instruction is time the matrix core
 // idles; with two, one wave's bookkeeping hides behind the other's MFMAs.  The reduced dimension
-// is walked in stages of 32 through a ring of kRing LDS buffers; the loads of stage s+3 are in
-// flight while stage s is multiplied.  A direct-to-LDS load puts lane i's 16 bytes at (uniform
+// is walked in stages of 32 through a ring of kRing LDS buffers; the loads of stages s+1 .. s+3
+// are in flight or landed while stage s is multiplied, and stage s's buffer is refilled (with stage s+4) as soon as
+// its second half has gone to registers.  A direct-to-LDS load puts lane i's 16 bytes at (uniform
 // base) + 16 i, so the LDS image of a wave's load is fixed to "64 consecutive 16-byte slots";
 // which global 16 bytes a lane fetches is free, and that freedom is used to swizzle (the LDS has
 // 64 banks of 4 bytes; a b128 read is served 16 lanes at a time, a b64 read 32 lanes at a time):
@@ -277,10 +278,10 @@ __device__ __forceinline__ void project_body(const TensorDesc* __restrict__ desc
   float sq = 0.f;    // squared norm of this wave's fragment-0 channels (see tile_of)
   bf16x8_t af0[MT], bf0[C::NTW], af1[MT], bf1[C::NTW];
 
-  // prologue: three stages requested, wait for the first
+  // prologue: every buffer of the ring requested, wait for the first
 #pragma unroll
-  for (int p = 0; p < kRing - 1; ++p) cx.issue(p, p);
-  wait_vmcnt<(kRing - 2) * C::LOADS>();
+  for (int p = 0; p < kRing; ++p) cx.issue(p, p);
+  wait_vmcnt<(kRing - 1) * C::LOADS>();
   __syncthreads();
   cx.read_frags(0, 0, af0, bf0);
 
@@ -292,19 +293,21 @@ __device__ __forceinline__ void project_body(const TensorDesc* __restrict__ desc
     sq = sq_accum8(bf0[0], sq);
     sched_kstep<MT + (LEFT ? 2 : 1) * C::NTW, MT * C::NTW, (4 + MT * C::NTW - 1) / (MT * C::NTW)>();
     __builtin_amdgcn_sched_barrier(0);
-    // stage s+1 has landed once only the loads of stage s+2 are outstanding; after the barrier
-    // every wave is past stage s-1, whose buffer then receives stage s+3
-    wait_vmcnt<(kRing - 3) * C::LOADS>();
+    // stage s+1 has landed once only the loads of the stages behind it are outstanding.  After the
+    // barrier no wave reads stage s's buffer again (its second half went to registers at the top of
+    // this iteration, and every wave has waited for those reads), so it receives stage s + kRing
+    wait_vmcnt<(kRing - 2) * C::LOADS>();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's fragment reads of stage s have returned
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    // k-step 1 of stage s, with the fragments of k-step 0 of stage s+1 and the loads of stage s+3 spread
+    // k-step 1 of stage s, with the fragments of k-step 0 of stage s+1 and the loads of stage s + kRing spread
     // between its MFMAs: the texture path takes a wave's 1 KB load every few tens of cycles only, and a
     // wave that waits to issue one issues nothing else.  Issued in one burst behind the barrier, the
     // eight waves' loads queue up and the matrix cores idle meanwhile; issued one at a time behind an
     // MFMA each, a load waits while that MFMA (and the other wave's) run.
     {
       constexpr int NM = MT * C::NTW, NR = MT + C::NTW, NS = NM > NR ? NM : NR;
-      const int nb = (s + 1) % kRing, lb = (s + kRing - 1) % kRing;
+      const int nb = (s + 1) % kRing, lb = s % kRing;
 #pragma unroll
       for (int i = 0; i < NS; ++i) {
         if (i < MT) af0[i] = cx.read_a(nb, 0, i);
@@ -313,7 +316,7 @@ __device__ __forceinline__ void project_body(const TensorDesc* __restrict__ desc
           acc[i / C::NTW][i % C::NTW] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i / C::NTW], bf1[i % C::NTW], acc[i / C::NTW][i % C::NTW], 0, 0, 0);
 #pragma unroll
           for (int u = 0; u < C::LOADS; ++u)
-            if ((u * NM) / C::LOADS == i) cx.issue_one(s + kRing - 1, lb, u);
+            if ((u * NM) / C::LOADS == i) cx.issue_one(s + kRing, lb, u);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
