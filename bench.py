@@ -108,7 +108,7 @@ def algorithmic_work(wl):
     }
 
 
-def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=True, first_step=1):
+def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=True, first_step=1, graph_leg=True):
     """Times `steps` steps after `warmup` untimed ones, step numbers first_step, first_step + 1, ...
     Every step (warm-up and timed) first gets freshly drawn gradients into the same buffers (seed =
     1000 * config + step), generated outside the timed region; a timed step is bracketed by a device
@@ -167,8 +167,13 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
         roof = {"bound": "hbm", "achieved": w["bytes"] / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": hbm_frac, "traffic": None}
     roof["kernel"] = KERNEL_OF_PHASE[dom]
+    groups = len(set(wl.shapes))
+    # sets below 64 M parameters run the update of all shape groups as one launch of update_groups_kernel
+    merged_update = wl.weight_dtype != torch.uint8 and groups > 1 and wl.n_params < (64 << 20)
     if dom == "update" and wl.weight_dtype == torch.uint8:
         roof["kernel"] = "update_q8_kernel"
+    if dom == "update" and merged_update:
+        roof["kernel"] = "update_groups_kernel"
     if dom == "projection" and wl.rank == 1:
         roof["kernel"] = "project_rank1_left_kernel + project_rank1_right_kernel"
     roof["traffic"] = measured_traffic(wl.name, roof["kernel"] if dom == "update" else KERNEL_OF_PHASE[dom]
@@ -179,7 +184,8 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
     roof["algorithmic"] = w["bytes"]
     roof["phase"] = dom
     roof["ms_per_step"] = phase_ms[dom]
-    roof["launches_per_step"] = len(set(wl.shapes))
+    # the matrix-core projection covers all shape groups with one launch, and so does the update of small sets
+    roof["launches_per_step"] = 1 if (dom == "projection" and fused) or (dom == "update" and merged_update) else groups
     pw = work["projection"]
     t_proj = phase_ms["projection"] * 1e-3
     proj = {"kernel": "project_mfma_kernel" if wl.rank > 1 else "project_rank1_{left,right}_kernel",
@@ -200,7 +206,7 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
         "finite": finite, "state_gb": state_bytes / 1e9, "workspace_gb": ws_bytes / 1e9,
         "first_timed_step": first_step + warmup,
     }
-    if wl.n_params < 100e6 and metas is None:
+    if graph_leg and wl.n_params < 100e6 and metas is None:
         # a set this small is bound by launch latency: the same steps replayed from a HIP graph (the kernels of a
         # step captured once; per step one small kernel writes the step's scalars, then the graph is launched)
         st = A.ApolloStepper(cfg, weights, grads, device=dev)
@@ -216,16 +222,21 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
             t += 1
         torch.cuda.synchronize()
         wall_g = 0.0
-        for _ in range(steps):
+        g0 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        g1 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        for k in range(steps):
             WL.make_grads(wl, t, dev, out=grads)
             torch.cuda.synchronize()
             h0 = time.perf_counter()
+            g0[k].record()
             st.prepare(t, wl.lr)
             graph.replay()
+            g1[k].record()
             torch.cuda.synchronize()
             wall_g += time.perf_counter() - h0
             t += 1
         res["graph_replay_ms_per_step"] = wall_g / steps * 1e3
+        res["graph_replay_device_ms_per_step"] = sum(g0[k].elapsed_time(g1[k]) for k in range(steps)) / steps
         del graph
         st.close()
         del st
@@ -255,6 +266,7 @@ def entry_of(wl, r):
             "min_ms_per_step": r["min_ms_per_step"], "first_timed_step": r["first_timed_step"],
             "phase_ms": r["phase_ms"], "overlap_schedule_ms_per_step": r.get("overlap_schedule_ms_per_step"),
             "graph_replay_ms_per_step": r.get("graph_replay_ms_per_step"),
+            "graph_replay_device_ms_per_step": r.get("graph_replay_device_ms_per_step"),
             "roofline": r["roofline"], "whole_step_hbm_frac": r["whole_step_hbm_frac"],
             "projection_roofline": r["projection_roofline"], "state_gb": r["state_gb"], "workspace_gb": r["workspace_gb"],
             "finite": r["finite"]}
@@ -363,6 +375,8 @@ def main():
     ap.add_argument("--no-overlap-leg", action="store_true",
                     help="skip the extra, separately timed run of the optional two-stream schedule (for "
                          "profiles of the default schedule alone)")
+    ap.add_argument("--no-graph-leg", action="store_true",
+                    help="skip the extra run of small sets replayed from a HIP graph (for profiles of the eager step alone)")
     ap.add_argument("--library-gemm-context", type=int, default=0, metavar="RANK",
                     help="also time torch.matmul on the projection's contraction at this rank (context only)")
     ap.add_argument("--only-adamw-rest", action="store_true", help="run only that launch (for profiling it)")
@@ -401,7 +415,8 @@ def main():
     weights = WL.make_q8_weights(wl, dev) if wl.weight_dtype == torch.uint8 else WL.make_weights(wl, dev)
     grads = [torch.empty(s, dtype=wl.grad_dtype, device=dev) for s in wl.shapes]
     torch.cuda.synchronize()
-    main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg)
+    main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg,
+                       graph_leg=not args.no_graph_leg)
     cpu = None
     if not args.no_cpu_baseline:      # before `weights` is replaced by another variant's storage type
         cpu = cpu_baseline(A, WL, torch, wl, weights, grads)
@@ -415,7 +430,8 @@ def main():
             torch.cuda.empty_cache()
             weights = WL.make_q8_weights(wl2, dev) if wl2.weight_dtype == torch.uint8 else WL.make_weights(wl2, dev)
             cur_wdt = wl2.weight_dtype
-        r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg)
+        r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg,
+                     graph_leg=not args.no_graph_leg)
         also.append(entry_of(wl2, r2))
     del weights, grads
     torch.cuda.empty_cache()
