@@ -281,7 +281,8 @@ apollo_status_t apollo_debug_copy(void* dst, const void* src, size_t bytes, void
  * to 16 bytes (bf16 gradients, rows projected, odd row length).  For callers and tests that want to
  * know that a shape runs where they expect it to run. */
 enum {
-  APOLLO_PATH_RANK1 = 0,        /* streaming mat-vec kernels (rank 1, row length a multiple of 8)   */
+  APOLLO_PATH_RANK1 = 0,        /* streaming mat-vec kernels (rank 1; any row length, a tall tensor's
+                                   rows up to 16384 elements)                                       */
   APOLLO_PATH_MATRIX_CORE = 1,  /* bf16 MFMA kernel (bf16 gradients, rank a multiple of 32, projected
                                    dimension a multiple of 64, at least 256 channels): Algorithm 1's
                                    steps 1-3 in one kernel -- the moment update and the channel norms
