@@ -112,7 +112,7 @@ def test_one_tensor_beyond_four_gibibytes_on_sampled_channels(shape, rank):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name", ["llama7b_mini", "llama7b_r256", "llama1b", "llama7b_identity"])
+@pytest.mark.parametrize("name", ["llama7b_mini", "llama7b_r256", "llama1b", "llama1b_mini", "llama7b_identity"])
 def test_every_tensor_of_a_full_set_at_step_one(name):
     """The recurrence of the oracle follows a handful of tensors of a full-size set; this covers ALL of
     them, every element, for the first step, where Algorithm 1 has a short closed form
