@@ -198,7 +198,7 @@ def plain_tolerance_applies(wl):
 
 def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side="auto", bias_correction=True,
                boost=None, compare_steps=None, lr=None, progress=None, independent_w=False, widen=None,
-               max_widened_share=None, max_k=None, stats=None):
+               max_widened_share=None, max_k=None, stats=None, max_median_k=None):
     """Steps the whole workload on the GPU and the tensors `check_ids` in the oracle.
     boost: {step: factor} multiplies that step's gradients.  Returns the number of limiter hits
     seen by the oracle (so callers can assert the case was exercised).
@@ -210,7 +210,8 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
     channels and k <= 10^4 with bf16 gradients (tolerance 1e-3, fifty times the input error); with fp32
     gradients the tolerance 1e-5 is only twice the input error, the worst-case propagation
     exceeds it on most channels by a small factor, so there the median k must stay below 20 and k
-    below 10^6 (at rank 1 a channel is a single number that can fall next to zero).  stats, a dict if given,
+    below 10^6 (at rank 1 a channel is a single number that can fall next to zero); max_median_k replaces the
+    limit on the median.  stats, a dict if given,
     receives the largest share, the largest k and, per quantity, the largest used fraction of its bound.
 
     independent_w: the oracle carries its own weights from step 0 (by default every step starts both
@@ -281,7 +282,8 @@ def run_parity(wl, check_ids, steps, device="cuda:0", seed=0x5EED5EED1234, side=
                 stats["widened_share"], stats["k_max"] = max(stats["widened_share"], share), max(stats["k_max"], kmax)
                 lim_share = max_widened_share if max_widened_share is not None else (0.25 if bf16 else 1.0)
                 lim_k = max_k if max_k is not None else (1e4 if bf16 else 1e6)
-                assert share <= lim_share and kmax <= lim_k and kmed <= (1.0 if bf16 else 20.0), \
+                lim_med = max_median_k if max_median_k is not None else (1.0 if bf16 else 20.0)
+                assert share <= lim_share and kmax <= lim_k and kmed <= lim_med, \
                     "%s tensor %d step %d: %.3f of the channels have a widened bound (limit %.3f), largest factor %.3g (limit %.3g), median %.3g" % (
                         wl.name, i, t, share, lim_share, kmax, lim_k, kmed)
             else:
