@@ -457,6 +457,21 @@ __device__ __forceinline__ void update_body(const TensorDesc& desc, const StepPa
 #pragma unroll
         for (int e = 0; e < EPT; ++e) k[e] *= sr;
       }
+    } else if (col + EPT <= cols && e0 + EPT <= total) {
+      // the thread's elements lie in one row (all but the threads at a row's end): their factors are
+      // consecutive, one element-aligned vector load, or one factor for all
+      if (CHAN == kChanCol) {
+        typedef float f32x4_ua_t __attribute__((ext_vector_type(4), aligned(4)));
+#pragma unroll
+        for (int i = 0; i < EPT / 4; ++i) {
+          const f32x4_ua_t sv = *reinterpret_cast<const APOLLO_GLOBAL f32x4_ua_t*>(d.s + col + 4 * i);
+          k[4 * i] *= sv.x; k[4 * i + 1] *= sv.y; k[4 * i + 2] *= sv.z; k[4 * i + 3] *= sv.w;
+        }
+      } else {
+        const float sr = d.s[row];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) k[e] *= sr;
+      }
     } else {
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
