@@ -108,7 +108,8 @@ def algorithmic_work(wl):
     }
 
 
-def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=True, first_step=1, graph_leg=True):
+def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=True, first_step=1, graph_leg=True,
+            phase_pass="auto"):
     """Times `steps` steps after `warmup` untimed ones, step numbers first_step, first_step + 1, ...
     Every step (warm-up and timed) first gets freshly drawn gradients into the same buffers (seed =
     1000 * config + step), generated outside the timed region; a timed step is bracketed by a device
@@ -126,7 +127,12 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
         st.step(t, wl.lr)
         t += 1
     torch.cuda.synchronize()
-    A.apollo_profile_enable(st.handle, True)
+    # The library's HIP events around its phases cost a few microseconds each: nothing against a step of
+    # milliseconds, a fifth of the step of a set that is bound by launch latency.  Such a set is timed
+    # without them, as a caller runs it, and stepped the same number of times again for the per-phase times.
+    separate = phase_pass == "separate" or (phase_pass == "auto" and wl.n_params < 100e6)
+    if not separate:
+        A.apollo_profile_enable(st.handle, True)
     e0 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]   # (the stepper uses torch's current stream)
     e1 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     wall = 0.0
@@ -141,6 +147,13 @@ def measure(A, WL, torch, wl, weights, grads, steps, warmup, dev, overlap_leg=Tr
         wall += time.perf_counter() - h0
         t += 1
     per_step = [e0[k].elapsed_time(e1[k]) for k in range(steps)]
+    if separate:
+        A.apollo_profile_enable(st.handle, True)
+        for k in range(steps):
+            WL.make_grads(wl, t, dev, out=grads)
+            st.step(t, wl.lr)
+            t += 1
+        torch.cuda.synchronize()
     rc, ms, n = A.apollo_profile_read(st.handle)
     assert rc == 0 and n == steps, (rc, n)
     A.apollo_profile_enable(st.handle, False)
@@ -375,6 +388,10 @@ def main():
     ap.add_argument("--no-overlap-leg", action="store_true",
                     help="skip the extra, separately timed run of the optional two-stream schedule (for "
                          "profiles of the default schedule alone)")
+    ap.add_argument("--phase-pass", choices=["auto", "same", "separate"], default="auto",
+                    help="per-phase times from the timed steps themselves (same) or from as many further steps "
+                         "(separate: the timed steps then run without the library's events); auto: separate for "
+                         "sets below 100 M parameters")
     ap.add_argument("--no-graph-leg", action="store_true",
                     help="skip the extra run of small sets replayed from a HIP graph (for profiles of the eager step alone)")
     ap.add_argument("--library-gemm-context", type=int, default=0, metavar="RANK",
@@ -416,7 +433,7 @@ def main():
     grads = [torch.empty(s, dtype=wl.grad_dtype, device=dev) for s in wl.shapes]
     torch.cuda.synchronize()
     main_res = measure(A, WL, torch, wl, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg,
-                       graph_leg=not args.no_graph_leg)
+                       graph_leg=not args.no_graph_leg, phase_pass=args.phase_pass)
     cpu = None
     if not args.no_cpu_baseline:      # before `weights` is replaced by another variant's storage type
         cpu = cpu_baseline(A, WL, torch, wl, weights, grads)
@@ -431,7 +448,7 @@ def main():
             weights = WL.make_q8_weights(wl2, dev) if wl2.weight_dtype == torch.uint8 else WL.make_weights(wl2, dev)
             cur_wdt = wl2.weight_dtype
         r2 = measure(A, WL, torch, wl2, weights, grads, args.steps, args.warmup, dev, not args.no_overlap_leg,
-                     graph_leg=not args.no_graph_leg)
+                     graph_leg=not args.no_graph_leg, phase_pass=args.phase_pass)
         also.append(entry_of(wl2, r2))
     del weights, grads
     torch.cuda.empty_cache()
@@ -440,9 +457,9 @@ def main():
         w3 = WL.make_weights(wl3, dev)
         g3 = [torch.empty(s, dtype=wl3.grad_dtype, device=dev) for s in wl3.shapes]
         if wl3.config_id == 5:      # "P refreshed on step 1 and every 200 steps, 5 steps timed": the first timed step is 201
-            r3 = measure(A, WL, torch, wl3, w3, g3, 5, args.warmup, dev, False, first_step=201 - args.warmup)
+            r3 = measure(A, WL, torch, wl3, w3, g3, 5, args.warmup, dev, False, first_step=201 - args.warmup, phase_pass=args.phase_pass)
         else:
-            r3 = measure(A, WL, torch, wl3, w3, g3, args.steps, args.warmup, dev, False)
+            r3 = measure(A, WL, torch, wl3, w3, g3, args.steps, args.warmup, dev, False, phase_pass=args.phase_pass)
         also.append(entry_of(wl3, r3))
         del w3, g3
         torch.cuda.empty_cache()
