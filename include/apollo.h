@@ -69,7 +69,7 @@ enum { APOLLO_F32 = 0, APOLLO_BF16 = 1, APOLLO_Q8 = 2 /* weights only: see apoll
 /* rounding of the 8-bit weight codes */
 enum { APOLLO_ROUND_NEAREST = 0, APOLLO_ROUND_STOCHASTIC = 1 };
 /* launch schedule of a step */
-enum { APOLLO_SCHEDULE_SERIAL = 0, APOLLO_SCHEDULE_OVERLAP = 1 };
+enum { APOLLO_SCHEDULE_SERIAL = 0, APOLLO_SCHEDULE_OVERLAP = 1, APOLLO_SCHEDULE_CHUNKED = 2 };
 /* granularity of the scaling factor: APOLLO (Eq. 4) or APOLLO-Mini (Section 4.2) */
 enum { APOLLO_CHANNEL = 0, APOLLO_TENSOR = 1 };
 /* which dimension is projected away: AUTO = the smaller one (Algorithm 1's m <= n);
@@ -114,7 +114,7 @@ typedef struct {
   int32_t state_dtype;      /* APOLLO_F32 (0, default) or APOLLO_BF16: element type of M^R, V^R */
   int32_t projection;       /* APOLLO_PROJ_RANDOM (0, default) or APOLLO_PROJ_IDENTITY          */
   int32_t weight_rounding;  /* APOLLO_ROUND_* of the codes when weight_dtype is APOLLO_Q8       */
-  int32_t schedule;         /* APOLLO_SCHEDULE_SERIAL (0, default) or APOLLO_SCHEDULE_OVERLAP    */
+  int32_t schedule;         /* APOLLO_SCHEDULE_SERIAL (0, default), _OVERLAP or _CHUNKED          */
 } apollo_config_t;
 
 /* APOLLO_SCHEDULE_OVERLAP: when some projection runs on the matrix cores (bf16 gradients, rank a
@@ -127,6 +127,17 @@ typedef struct {
  * (about 3 % of a rank-256 step: the projection and the streaming kernels contend for the same
  * load path), which is why it is not the default.  Steps recorded by apollo_profile_enable use the
  * serial schedule, which is the one that has phases to time. */
+
+/* APOLLO_SCHEDULE_CHUNKED: P is not kept from step to step.  For rank > 1 the default schedules hold
+ * every tensor's P in the workspace for a whole refresh interval (Algorithm 1 holds P_t until it is
+ * re-sampled), r x m elements per tensor -- 0.47 GB for the LLaMA-7B matrices at rank 256.  With this
+ * schedule a step works through each shape group in chunks of tensors whose P together fit 128 MiB:
+ * generate the chunk's P from the seed, project the chunk (the moment update included where the
+ * projection runs on the matrix cores), go on to the next chunk over the same scratch; limiter and
+ * update follow as usual.  apollo_workspace_bytes shrinks accordingly (7B, rank 256: 0.13 GB); every
+ * step pays the generation (about 2 % of such a step) and a few more launches.  Results are
+ * bit-identical to APOLLO_SCHEDULE_SERIAL.  apollo_step_launch (the replayable step) is not offered
+ * with it (APOLLO_EUNSUPPORTED); apollo_step_noalloc ignores the schedule. */
 
 /* APOLLO_Q8: group-wise 8-bit weights (Section 5.4 / Table 6 combine APOLLO with 8-bit integer
  * weights quantised in groups of 128, and say no more; the reading taken is the usual asymmetric

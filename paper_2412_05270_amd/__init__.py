@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     APOLLO_DBG_R, APOLLO_DBG_S, APOLLO_DBG_V, APOLLO_EHIP, APOLLO_EINVAL, APOLLO_ENOMEM, APOLLO_ESTATE,
     APOLLO_EUNSUPPORTED, APOLLO_F32, APOLLO_OK, APOLLO_PATH_GENERAL, APOLLO_PATH_MATRIX_CORE,
     APOLLO_PATH_NONE, APOLLO_PATH_RANK1, APOLLO_PROJ_IDENTITY, APOLLO_PROJ_RANDOM, APOLLO_Q8,
-    APOLLO_ROUND_NEAREST, APOLLO_ROUND_STOCHASTIC, APOLLO_SCHEDULE_OVERLAP, APOLLO_SCHEDULE_SERIAL,
+    APOLLO_ROUND_NEAREST, APOLLO_ROUND_STOCHASTIC, APOLLO_SCHEDULE_OVERLAP, APOLLO_SCHEDULE_CHUNKED, APOLLO_SCHEDULE_SERIAL,
     APOLLO_SIDE_AUTO, APOLLO_SIDE_LEFT, APOLLO_SIDE_RIGHT, APOLLO_TENSOR,
     AdamwStepper, ApolloAdamwConfig, ApolloConfig, ApolloError, ApolloFlatShape, ApolloShape,
     ApolloStepper, ApolloTensor,

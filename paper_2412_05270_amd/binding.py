@@ -13,7 +13,7 @@ _LIB_NAME = "libapollo_mi355x.so"
 APOLLO_OK, APOLLO_EINVAL, APOLLO_ENOMEM, APOLLO_ESTATE, APOLLO_EHIP, APOLLO_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 APOLLO_F32, APOLLO_BF16, APOLLO_Q8 = 0, 1, 2
 APOLLO_ROUND_NEAREST, APOLLO_ROUND_STOCHASTIC = 0, 1
-APOLLO_SCHEDULE_SERIAL, APOLLO_SCHEDULE_OVERLAP = 0, 1
+APOLLO_SCHEDULE_SERIAL, APOLLO_SCHEDULE_OVERLAP, APOLLO_SCHEDULE_CHUNKED = 0, 1, 2
 APOLLO_CHANNEL, APOLLO_TENSOR = 0, 1
 APOLLO_SIDE_AUTO, APOLLO_SIDE_LEFT, APOLLO_SIDE_RIGHT = 0, 1, 2
 APOLLO_PROJ_RANDOM, APOLLO_PROJ_IDENTITY = 0, 1

@@ -1,5 +1,6 @@
 // Host side of the APOLLO step library: argument checking, buffer layout, the per-step launch
 // schedule.  The interface is documented in include/apollo.h.
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdio>
@@ -21,6 +22,7 @@ constexpr int64_t kMaxDim = 1 << 20;       // rows / cols limit (grid dimensions
 constexpr int32_t kMaxTensors = 65535;     // gridDim.z
 constexpr int kRingSlots = 4;
 constexpr size_t kMergedUpdateMaxParams = 64u << 20;   // below this many parameters the update of all groups is one launch
+constexpr size_t kChunkPBytes = 128u << 20;            // APOLLO_SCHEDULE_CHUNKED: scratch for the P of one chunk of tensors
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -52,6 +54,7 @@ struct Group {
   int32_t n_slabs;
   bool pad_g, fused;
   int32_t ldg, row_tiles;
+  int32_t chunk;                 // APOLLO_SCHEDULE_CHUNKED: tensors whose P share the scratch at a time (else count)
 };
 
 struct Plan {
@@ -88,8 +91,9 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     return fail(err, APOLLO_EUNSUPPORTED, "weight_dtype must be fp32, bf16 or q8 and state_dtype fp32 or bf16");
   if (cfg->weight_rounding != APOLLO_ROUND_NEAREST && cfg->weight_rounding != APOLLO_ROUND_STOCHASTIC)
     return fail(err, APOLLO_EINVAL, "unknown weight_rounding %lld", cfg->weight_rounding);
-  if (cfg->schedule != APOLLO_SCHEDULE_OVERLAP && cfg->schedule != APOLLO_SCHEDULE_SERIAL)
+  if (cfg->schedule != APOLLO_SCHEDULE_OVERLAP && cfg->schedule != APOLLO_SCHEDULE_SERIAL && cfg->schedule != APOLLO_SCHEDULE_CHUNKED)
     return fail(err, APOLLO_EINVAL, "unknown schedule %lld", cfg->schedule);
+  const bool chunked = cfg->schedule == APOLLO_SCHEDULE_CHUNKED;
   const size_t state_elem = cfg->state_dtype == APOLLO_BF16 ? 2 : sizeof(float);
 
   plan.t.resize(n);
@@ -156,6 +160,7 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     g.rows = a.rows; g.cols = a.cols; g.m = a.m; g.n = a.n; g.m8 = a.m8;
     g.left = a.left; g.bf16 = a.bf16; g.path = a.path; g.n_slabs = a.n_slabs; g.pad_g = a.pad_g; g.fused = a.fused; g.row_tiles = a.row_tiles; g.ldg = a.ldg;
     g.count = 0;
+    g.chunk = 0;
     const int32_t gi = (int32_t)plan.groups.size();
     for (int32_t j = k; j < n; ++j) {
       const TensorPlan& b = plan.t[j];
@@ -182,7 +187,7 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
   for (int32_t k = 0; k < n; ++k) {
     TensorPlan& t = plan.t[k];
     t.ws_p = ws;
-    if (t.path != Path::kRank1 && t.path != Path::kIdentity) ws = align_up(ws + (size_t)cfg->rank * t.m8 * (t.bf16 ? 2 : 4));
+    if (!chunked && t.path != Path::kRank1 && t.path != Path::kIdentity) ws = align_up(ws + (size_t)cfg->rank * t.m8 * (t.bf16 ? 2 : 4));
     t.ws_gpad = ws;
     if (t.pad_g) ws = align_up(ws + (size_t)t.rows * t.ldg * 2);
     t.ws_r = ws;
@@ -199,6 +204,26 @@ int make_plan(const apollo_config_t* cfg, const apollo_shape_t* shapes, int32_t 
     ws = align_up(ws + (size_t)t.k2_blocks * 4 * sizeof(float));
     t.ws_scal = ws;
     ws = align_up(ws + 8 * sizeof(float));
+  }
+  // P scratch of the chunked schedule: one region, used by one chunk of a group's tensors at a time
+  for (Group& g : plan.groups) g.chunk = g.count;
+  if (chunked) {
+    const size_t region = ws;
+    size_t region_bytes = 0;
+    for (Group& g : plan.groups) {
+      if (g.path == Path::kRank1 || g.path == Path::kIdentity) continue;
+      const size_t pb = align_up((size_t)cfg->rank * g.m8 * (g.bf16 ? 2 : 4));
+      g.chunk = (int32_t)std::max<size_t>(1, std::min<size_t>((size_t)g.count, kChunkPBytes / pb));
+      region_bytes = std::max(region_bytes, (size_t)g.chunk * pb);
+    }
+    for (int32_t k = 0; k < n; ++k) {
+      TensorPlan& t = plan.t[k];
+      const Group& g = plan.groups[group_of[k]];
+      if (g.path == Path::kRank1 || g.path == Path::kIdentity) continue;
+      const size_t pb = align_up((size_t)cfg->rank * g.m8 * (g.bf16 ? 2 : 4));
+      t.ws_p = region + (size_t)((t.desc_index - g.first) % g.chunk) * pb;
+    }
+    ws = align_up(ws + region_bytes);
   }
   plan.workspace_bytes = ws;
   return APOLLO_OK;
@@ -407,6 +432,52 @@ hipError_t run_serial(GroupLaunches& L, const Plan& plan, hipStream_t st, hipEve
   return e;
 }
 
+// APOLLO_SCHEDULE_CHUNKED: as run_serial, but P is generated anew in every step, chunk by chunk of a
+// group's tensors over one scratch region, each chunk projected before the next one overwrites it.
+hipError_t run_chunked(GroupLaunches& L, const Plan& plan, hipStream_t st, hipEvent_t* pev) {
+  hipError_t e = hipSuccess;
+  if (pev) e = hipEventRecord(pev[1], st);      // (generation and projection alternate: both count as projection)
+  const bool state_bf16 = L.cfg.state_dtype == APOLLO_BF16;
+  for (const Group& g : plan.groups) {
+    if (e != hipSuccess) break;
+    if (g.path == Path::kRank1 || g.path == Path::kIdentity) {
+      e = L.project(g, st);
+      continue;
+    }
+    if (g.pad_g) {
+      L.what = "gradient padding";
+      e = launch_pad_gradient(L.dd + g.first, g.count, g.rows, g.cols, g.ldg, st);
+    }
+    for (int32_t c0 = 0; c0 < g.count && e == hipSuccess; c0 += g.chunk) {
+      const int32_t cnt = std::min(g.chunk, g.count - c0);
+      const TensorDesc* d0 = L.dd + g.first + c0;
+      L.what = "projection fill";
+      e = launch_fill_projection(d0, cnt, L.sa.host.r, g.m8, g.bf16, L.sa, st);
+      if (e != hipSuccess) break;
+      L.what = "projection";
+      e = g.path == Path::kMfma ? launch_project_mfma(d0, cnt, g.rows, g.cols, g.left, g.pad_g, g.fused, state_bf16, nullptr, L.sa, st)
+                                : launch_project_generic(d0, cnt, g.n, g.bf16, L.sa, st);
+    }
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[2], st);
+  for (const Group& g : plan.groups) {
+    if (e != hipSuccess) break;
+    e = L.moments(g, st);
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[3], st);
+  if (e == hipSuccess) {
+    L.what = "limiter";
+    e = launch_finalize(L.dd, (int)plan.t.size(), L.sa, st);
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[4], st);
+  for (const Group& g : plan.groups) {
+    if (e != hipSuccess) break;
+    e = L.update(g, st);
+  }
+  if (pev && e == hipSuccess) e = hipEventRecord(pev[5], st);
+  return e;
+}
+
 }  // namespace
 
 extern "C" {
@@ -550,7 +621,8 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
   // steps, after a jump in the step number) or when the caller switched streams (the copy was
   // written in the other stream's order); otherwise the step reads what is there.
   const int64_t epoch = (step - 1) / (int64_t)h->cfg.refresh_interval;
-  const bool regenerate = epoch != h->p_epoch || st != h->p_stream;
+  const bool chunked = h->cfg.schedule == APOLLO_SCHEDULE_CHUNKED;       // the scratch never holds a whole step's P
+  const bool regenerate = chunked || epoch != h->p_epoch || st != h->p_stream;
   h->p_epoch = -1;                      // until this step is enqueued completely
   GroupLaunches L{h->cfg, dd, StepArgs{sp, nullptr}, regenerate, ""};
   const char*& what = L.what;
@@ -605,7 +677,7 @@ apollo_status_t apollo_step(apollo_handle_t* h, const apollo_tensor_t* tensors, 
     return APOLLO_OK;
   }
 
-  if (e == hipSuccess) e = run_serial(L, h->plan, st, pev);
+  if (e == hipSuccess) e = chunked ? run_chunked(L, h->plan, st, pev) : run_serial(L, h->plan, st, pev);
   if (e != hipSuccess) return hip_fail(h->err, e, what);
   h->p_epoch = epoch;
   h->p_stream = st;
@@ -624,6 +696,8 @@ apollo_status_t apollo_step_prepare(apollo_handle_t* h, int64_t step, float lr, 
 
 apollo_status_t apollo_step_launch(apollo_handle_t* h, const apollo_tensor_t* tensors, int32_t n_tensors, void* hip_stream) {
   if (!h) return fail(g_last_error, APOLLO_EINVAL, "null handle");
+  if (h->cfg.schedule == APOLLO_SCHEDULE_CHUNKED)
+    return fail(h->err, APOLLO_EUNSUPPORTED, "the replayable step is not offered with APOLLO_SCHEDULE_CHUNKED");
   const int32_t n = (int32_t)h->plan.t.size();
   if (!tensors) return fail(h->err, APOLLO_EINVAL, "null tensor list");
   if (n_tensors != n) return fail(h->err, APOLLO_EINVAL, "n_tensors %lld differs from the %lld given to apollo_init", n_tensors, n);
@@ -744,6 +818,11 @@ apollo_status_t apollo_debug_get(apollo_handle_t* h, int32_t tensor, int32_t wha
         if (bytes != rn) return fail(h->err, APOLLO_EINVAL, "selector %lld holds %lld bytes, %lld given", what, (long long)rn, (long long)bytes);
         if (!h->have_ptrs || h->p_epoch < 0) return fail(h->err, APOLLO_EINVAL, "no step has run on this handle yet");
         StepParams sp = make_step_params(h->cfg, h->p_epoch * (int64_t)h->cfg.refresh_interval + 1, 0.f);
+        if (h->cfg.schedule == APOLLO_SCHEDULE_CHUNKED) {      // the scratch holds the P of a group's last chunk
+          const hipError_t ef = launch_fill_projection(reinterpret_cast<const TensorDesc*>(h->ws) + t.desc_index, 1, h->cfg.rank, t.m8,
+                                                       t.bf16, StepArgs{sp, nullptr}, static_cast<hipStream_t>(hip_stream));
+          if (ef != hipSuccess) return hip_fail(h->err, ef, "projection fill (debug)");
+        }
         const hipError_t e = launch_project_mfma(reinterpret_cast<const TensorDesc*>(h->ws) + t.desc_index, 1, t.rows, t.cols,
                                                  t.left, t.pad_g, false, false, static_cast<float*>(out), StepArgs{sp, nullptr},
                                                  static_cast<hipStream_t>(hip_stream));
@@ -858,7 +937,11 @@ apollo_status_t apollo_step_noalloc(const apollo_config_t* cfg, const apollo_sha
     return fail(err, APOLLO_EUNSUPPORTED, "apollo_step_noalloc takes at most %lld tensors per call, %lld given",
                 APOLLO_NOALLOC_MAX_TENSORS, n_tensors);
   Plan plan;
-  int rc = make_plan(cfg, shapes, n_tensors, plan, err);
+  if (!cfg) return fail(err, APOLLO_EINVAL, "null config or shape list");
+  apollo_config_t serial_cfg = *cfg;      // one call, one pass over P: the schedule does not apply
+  if (serial_cfg.schedule == APOLLO_SCHEDULE_OVERLAP || serial_cfg.schedule == APOLLO_SCHEDULE_CHUNKED)
+    serial_cfg.schedule = APOLLO_SCHEDULE_SERIAL;
+  int rc = make_plan(&serial_cfg, shapes, n_tensors, plan, err);
   if (rc != APOLLO_OK) return rc;
   if (!tensors || !state) return fail(err, APOLLO_EINVAL, "null tensor list or state buffer");
   if ((uintptr_t)state & (kAlign - 1)) return fail(err, APOLLO_ESTATE, "state not 256-byte aligned");

@@ -176,6 +176,41 @@ def test_every_tensor_of_a_full_set_at_step_one(name):
     torch.cuda.empty_cache()
 
 
+def test_chunked_schedule_at_full_size_equals_the_serial_one():
+    """APOLLO_SCHEDULE_CHUNKED on the LLaMA-7B matrices at rank 256: the groups of 128 and 64 tensors are
+    worked through in chunks of 64 (128 MiB of P), every chunk's P generated over the same scratch.  Steps
+    200 and 201 (a re-sampling between them): every weight tensor and the whole state must carry the same
+    bits as after the serial schedule (compared through exact integer fingerprints), with a quarter of
+    the workspace."""
+    import paper_2412_05270_amd as A
+    from parity_util import make_configs
+    dev = "cuda:0"
+    wl = WL.workload("llama7b_r256")
+
+    def fingerprint(x):
+        return int(x.contiguous().view(torch.int32).to(torch.int64).sum())
+    prints, ws = [], []
+    for schedule in (A.APOLLO_SCHEDULE_SERIAL, A.APOLLO_SCHEDULE_CHUNKED):
+        cfg, _ = make_configs(wl)
+        cfg.schedule = schedule
+        weights = WL.make_weights(wl, dev)
+        grads = [torch.empty(s, dtype=wl.grad_dtype, device=dev) for s in wl.shapes]
+        st = A.ApolloStepper(cfg, weights, grads, device=dev)
+        ws.append(st.workspace.numel())
+        got = []
+        for t in (200, 201):
+            WL.make_grads(wl, t, dev, out=grads)
+            st.step(t, wl.lr)
+            torch.cuda.synchronize()
+            got.append([fingerprint(w) for w in weights] + [fingerprint(st.state)])
+        prints.append(got)
+        st.close()
+        del weights, grads, st
+        torch.cuda.empty_cache()
+    assert prints[0] == prints[1]
+    assert ws[1] * 3 < ws[0]
+
+
 def test_full_size_sets_run_on_the_kernels_meant_for_them():
     """No silent fallback: every tensor of the benchmark's sets is served by the projection kernel
     written for it (the library reports its choice per tensor)."""

@@ -214,6 +214,43 @@ def test_overlapped_and_serial_schedules_agree_bit_for_bit():
             assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("dtype,rank,sdt", [(torch.bfloat16, 64, torch.float32), (torch.bfloat16, 96, torch.bfloat16),
+                                            (torch.float32, 8, torch.float32)])
+def test_chunked_and_serial_schedules_agree_bit_for_bit(dtype, rank, sdt, monkeypatch):
+    """APOLLO_SCHEDULE_CHUNKED keeps no P between steps: every step generates it chunk by chunk of a
+    shape group's tensors over one scratch region and projects each chunk before the next overwrites it.
+    The same P, the same kernels per tensor: W and the whole state must equal the serial schedule's
+    exactly at every step, with a smaller workspace, across re-samplings, for the matrix-core and the
+    general projection (R of a matrix-core tensor is recomputed for the debug view from a P that has to
+    be generated again: compared too).  The chunk size is a compile-time 128 MiB: tensors of 8 MiB of P
+    each (rank 64 x 65536 columns would be needed) do not belong into a test, so the tensors here form
+    one chunk per group -- the case of several chunks per group runs at full size in
+    tests/test_gpu_large.py."""
+    shapes = [(128, 512)] * 3 + [(512, 128)] * 2 + [(256, 256)] * 4 + [(96, 333)]
+    wl = WL.Workload("chunked", 15, shapes, dtype, "normal", 1e-2, rank=rank, refresh_interval=2, steps=5,
+                     lr=1e-2, weight_decay=0.01, state_dtype=sdt)
+    runs, ws_bytes = [], []
+    for schedule in (A.APOLLO_SCHEDULE_CHUNKED, A.APOLLO_SCHEDULE_SERIAL):
+        cfg, _ = make_configs(wl)
+        cfg.schedule = schedule
+        weights = WL.make_weights(wl, DEV)
+        grads = [torch.empty(s, dtype=wl.grad_dtype, device=DEV) for s in wl.shapes]
+        st = A.ApolloStepper(cfg, weights, grads, device=DEV)
+        ws_bytes.append(st.workspace.numel())
+        snaps = []
+        for t in range(1, wl.steps + 1):
+            WL.make_grads(wl, t, DEV, out=grads)
+            st.step(t, wl.lr)
+            torch.cuda.synchronize()
+            snaps.append([w.clone() for w in weights] + [st.state.clone(), st.debug(1, A.APOLLO_DBG_R), st.debug(4, A.APOLLO_DBG_R)])
+        st.close()
+        runs.append(snaps)
+    assert ws_bytes[0] < ws_bytes[1]
+    for a, b in zip(*runs):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+
+
 def test_projection_scratch_follows_jumps_of_the_step_number():
     """The generated P stays in the workspace within a refresh interval and is re-generated when
     the step's interval differs from the one held: a handle that is stepped 1, 2, 7, 3, 8 (T = 3:
