@@ -89,3 +89,20 @@ def test_replay_from_a_graph_equals_the_ordinary_step_at_every_replay(mode, rank
     del graph
     ref.close()
     new.close()
+
+
+def test_the_replayable_step_is_refused_with_the_chunked_schedule():
+    """APOLLO_SCHEDULE_CHUNKED keeps no P between steps and decides nothing on the device: the two-part step
+    is not offered with it, and says so instead of running."""
+    wl = WL.Workload("chunked_launch", 83, [(128, 512), (256, 256)], BF, "normal", 1e-2, rank=32)
+    cfg, _ = make_configs(wl)
+    cfg.schedule = A.APOLLO_SCHEDULE_CHUNKED
+    weights = WL.make_weights(wl, DEV)
+    grads = WL.make_grads(wl, 1, DEV)
+    st = A.ApolloStepper(cfg, weights, grads, device=DEV)
+    st.step(1, wl.lr)
+    st.prepare(2, wl.lr)
+    with pytest.raises(A.ApolloError) as err:
+        st.launch()
+    assert err.value.status == A.APOLLO_EUNSUPPORTED and "CHUNKED" in str(err.value)
+    st.close()
