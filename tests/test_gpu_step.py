@@ -215,7 +215,7 @@ def test_overlapped_and_serial_schedules_agree_bit_for_bit():
 
 
 @pytest.mark.parametrize("dtype,rank,sdt", [(torch.bfloat16, 64, torch.float32), (torch.bfloat16, 96, torch.bfloat16),
-                                            (torch.float32, 8, torch.float32)])
+                                            (torch.float32, 8, torch.float32), (torch.bfloat16, 1, torch.float32)])
 def test_chunked_and_serial_schedules_agree_bit_for_bit(dtype, rank, sdt, monkeypatch):
     """APOLLO_SCHEDULE_CHUNKED keeps no P between steps: every step generates it chunk by chunk of a
     shape group's tensors over one scratch region and projects each chunk before the next overwrites it.
@@ -245,7 +245,7 @@ def test_chunked_and_serial_schedules_agree_bit_for_bit(dtype, rank, sdt, monkey
             snaps.append([w.clone() for w in weights] + [st.state.clone(), st.debug(1, A.APOLLO_DBG_R), st.debug(4, A.APOLLO_DBG_R)])
         st.close()
         runs.append(snaps)
-    assert ws_bytes[0] < ws_bytes[1]
+    assert ws_bytes[0] < ws_bytes[1] or rank == 1        # (rank 1 has no scratch copy of P under any schedule)
     for a, b in zip(*runs):
         for x, y in zip(a, b):
             assert torch.equal(x, y)
